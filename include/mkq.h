@@ -1,0 +1,215 @@
+/*
+ * mkq.h -- C ABI of libmkq: the 4-bit (W4A4) quantized BERT linear layer of
+ * MKQ-BERT (arXiv 2203.13483) for AMD MI355X (gfx950).
+ *
+ * Conventions that hold for every entry point unless it says otherwise
+ *   - returns an int status: MKQ_OK (0) or a negative MKQ_ERR_* code; nothing
+ *     throws, nothing prints;
+ *   - every pointer is a DEVICE pointer owned by the caller (the library keeps
+ *     no reference after the call is enqueued), except arguments whose names
+ *     end in _host and the parameter structs themselves, which are read on the
+ *     host during the call;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream); the call does not synchronise and does not allocate;
+ *   - matrices are row-major and dense (row stride = number of columns) unless
+ *     a leading dimension is given; device pointers must be 16-byte aligned;
+ *   - argument errors are detected on the host before anything is enqueued, so
+ *     a failing call has no effect on device memory.
+ *
+ * Packed int4 ("I4") tensors use the canonical nibble packing: element k of a
+ * row is the low nibble of byte k/2 when k is even, the high nibble when k is
+ * odd, two's complement, rows of K/2 bytes.
+ */
+#ifndef MKQ_H
+#define MKQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MKQ_OK = 0,
+    MKQ_ERR_NULL = -1,        /* a required pointer is NULL */
+    MKQ_ERR_SHAPE = -2,       /* a dimension is negative / not a supported multiple */
+    MKQ_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
+    MKQ_ERR_SCALE = -4,       /* a host-side step size is <= 0, NaN or Inf */
+    MKQ_ERR_DTYPE = -5,       /* unknown / unsupported MKQ_* dtype or activation enum */
+    MKQ_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than the *_workspace_bytes value */
+    MKQ_ERR_UNSUPPORTED = -7, /* valid request outside what the kernels cover (e.g. K >= 131072) */
+    MKQ_ERR_HIP = -8          /* the HIP runtime reported an error at launch */
+};
+
+enum { MKQ_F32 = 0, MKQ_F16 = 1, MKQ_BF16 = 2, MKQ_I4 = 3 };
+enum { MKQ_ACT_NONE = 0, MKQ_ACT_GELU = 1 };
+
+const char *mkq_status_string(int status);
+int mkq_version(void);
+
+/* Quantizer of section 3.1, Eq. 1, integer part, 4 bits, one step for the whole
+ * tensor (per-tensor scale):  code = round(clamp(x / s_x, -8, 7)), binary32
+ * divide, round half to even, NaN -> 0.
+ *   x      [M, K] of x_dtype (MKQ_F32 or MKQ_F16), row stride ldx elements
+ *   q_out  [M, K/2] bytes, canonical packing
+ * K must be a multiple of 32.  M == 0 is a no-op.
+ * Errors: NULL, SHAPE (M<0, K<0, K%32, ldx<K), ALIGN, SCALE, DTYPE, HIP. */
+int mkq_quantize(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, float s_x,
+                 uint8_t *q_out, void *stream);
+
+/* Abs-max calibration of section 3.1 (third paragraph):  s = max|x| / 7, written
+ * to s_out[0] (per_row == 0) or s_out[m] for every row (per_row != 0).  An
+ * all-zero tensor / row gets s = 1.  x_dtype MKQ_F32 or MKQ_F16.
+ * Errors: NULL, SHAPE, ALIGN, DTYPE, HIP. */
+int mkq_absmax_scale(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, int per_row,
+                     float *s_out, void *stream);
+
+/* Offline weight preparation (Eq. 1 with one step per row = per output channel;
+ * abs-max calibration when s_w_in is NULL).
+ *   W        [N, K] binary32, row n = output channel n
+ *   s_w_in   [N] steps to use, or NULL to calibrate  s_w[n] = max_k |W[n,k]| / 7
+ *            (all-zero row -> 1).  Given steps must be > 0 and finite (precondition;
+ *            they live on the device and are not checked).
+ *   s_w_out  [N] the steps actually used (may alias s_w_in)
+ *   Wq_out   mkq_packed_weight_bytes(N, K) bytes in the layout the GEMM reads
+ *            (currently the canonical packing, rows of K/2 bytes)
+ * K must be a multiple of 32.
+ * Errors: NULL, SHAPE, ALIGN, HIP. */
+size_t mkq_packed_weight_bytes(int64_t N, int64_t K);
+int mkq_pack_weights_int4(const float *W, int64_t N, int64_t K, const float *s_w_in,
+                          float *s_w_out, uint8_t *Wq_out, void *stream);
+
+/* Packs already-quantized int8 codes (values in [-8, 7]; higher bits are
+ * discarded) of a [rows, K] matrix into the weight / activation layout. */
+int mkq_pack_codes_int4(const int8_t *codes, int64_t rows, int64_t K, uint8_t *q_out, void *stream);
+
+/* Inverse of the weight layout: int8 codes [N, K] (for tests and inspection). */
+int mkq_unpack_weights_int4(const uint8_t *Wq, int64_t N, int64_t K, int8_t *codes_out,
+                            void *stream);
+
+/* Optional parts of the linear's epilogue. */
+typedef struct mkq_epilogue {
+    int act;              /* MKQ_ACT_*; applied after bias and residual (GELU: erf form, FFN of section 3.2) */
+    const void *residual; /* NULL or [M, N] added after the bias */
+    int residual_dtype;   /* MKQ_F32 or MKQ_F16 */
+    float s_next;         /* step of the next layer's activation quantizer; used when out_dtype == MKQ_I4
+                             or q_out != NULL */
+    uint8_t *q_out;       /* NULL, or [M, N/2] packed codes of the binary32 result under s_next, written
+                             in addition to a float `out` */
+    int32_t *acc_out;     /* NULL, or [M, N] raw int32 accumulators (for parity checks) */
+} mkq_epilogue;
+
+/* The quantized linear layer  y = x W^T + b  with both operands in 4 bits
+ * (the int4 matrix multiplication of sections 1 and 5.4 applied to the linears
+ * of section 3.2):
+ *     acc[m,n] = sum_k a[m,k] * w[n,k]                      (int32, exact)
+ *     y[m,n]   = fma((float)acc, s_x * s_w[n], bias[n])     (binary32)
+ *     y       += residual;  y = act(y)                      (optional)
+ *     out      = narrow(y)  or  codes(y; s_next) packed     (Eq. 1 again)
+ *   a        [M, K]: packed codes (a_dtype == MKQ_I4, rows of K/2 bytes) or float
+ *            activations (MKQ_F32 / MKQ_F16), which are first quantized with s_x
+ *            into `workspace`
+ *   Wq, s_w  from mkq_pack_weights_int4;  bias [N] binary32 or NULL
+ *   out      [M, N] of out_dtype (F32, F16, BF16) or [M, N/2] bytes (I4); may be
+ *            NULL when epi->q_out or epi->acc_out is the only result wanted
+ *   epi      NULL = no activation, no residual, no extra outputs
+ *   workspace  at least mkq_linear_int4_workspace_bytes(M, N, K, a_dtype) bytes
+ *              (0 for packed input: then workspace may be NULL)
+ * K % 32 == 0, K < 131072; N even when codes are written.  M == 0 is a no-op.
+ * Errors: NULL, SHAPE, ALIGN, SCALE (s_x, s_next), DTYPE, WORKSPACE, UNSUPPORTED, HIP. */
+size_t mkq_linear_int4_workspace_bytes(int64_t M, int64_t N, int64_t K, int a_dtype);
+int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,
+                    const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                    const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream);
+
+/* 16-bit float baseline linear (same epilogue, no quantizers):
+ *   a [M, K] binary16, W [N, K] binary16, bias [N] binary32 or NULL, binary32
+ *   accumulation, out [M, N] of out_dtype (F32 or F16), residual binary16 or NULL.
+ * K % 32 == 0.  Errors: NULL, SHAPE, ALIGN, DTYPE, HIP. */
+int mkq_linear_fp16(const void *a, const void *W, const float *bias, int64_t M, int64_t N,
+                    int64_t K, void *out, int out_dtype, int act, const void *residual,
+                    void *stream);
+
+/* One post-LN BERT encoder layer (multi-head attention and feed-forward network
+ * of section 3.2) with all six linears W4A4; LayerNorm, softmax and GELU are
+ * computed in binary32 (section 5), the attention products in binary16 with
+ * binary32 accumulation, hidden states are stored in binary16.
+ *
+ *   c0  = codes(h; sx_qkv)                      (or q_in, if the caller has them)
+ *   qkv = Lin_qkv(c0)                           [M, 3*hidden], q | k | v
+ *   ctx = softmax(q k^T / sqrt(d_k)) v          per sequence and head, d_k = hidden/heads
+ *   u   = Lin_ao(codes(ctx; sx_ao)) + h
+ *   h1  = LayerNorm1(u)
+ *   d   = Lin_down(codes(GELU(Lin_up(codes(h1; sx_up))); sx_down)) + h1
+ *   out = LayerNorm2(d)
+ *
+ * The struct lives on the host; the pointers inside are device pointers. */
+typedef struct mkq_bert_layer_params {
+    int64_t batch, seq, hidden, heads, ffn;
+    const uint8_t *Wq_qkv, *Wq_ao, *Wq_up, *Wq_down; /* packed; qkv is [3*hidden, hidden] */
+    const float *sw_qkv, *sw_ao, *sw_up, *sw_down;   /* per-output-channel steps */
+    const float *b_qkv, *b_ao, *b_up, *b_down;       /* biases, binary32 */
+    float sx_qkv, sx_ao, sx_up, sx_down;             /* learned per-tensor activation steps */
+    const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
+    float ln_eps;
+    float s_out_next; /* > 0: also write codes(out; s_out_next) to q_out_next */
+} mkq_bert_layer_params;
+
+/* Byte offsets of the layer's intermediates inside its workspace (all 256-byte
+ * aligned); tests read them back stage by stage. */
+typedef struct mkq_bert_layer_workspace_layout {
+    size_t c0;   /* [M, hidden/2]   codes of the input                     */
+    size_t qkv;  /* [M, 3*hidden]   binary16                                */
+    size_t c1;   /* [M, hidden/2]   codes of the attention context          */
+    size_t u;    /* [M, hidden]     binary16, attention output + residual   */
+    size_t h1;   /* [M, hidden]     binary16, LayerNorm1 output             */
+    size_t c2;   /* [M, hidden/2]   codes of h1                             */
+    size_t c3;   /* [M, ffn/2]      codes of GELU(FFN-up)                   */
+    size_t d;    /* [M, hidden]     binary16, FFN output + residual         */
+    size_t total;
+} mkq_bert_layer_workspace_layout;
+
+int mkq_bert_layer_workspace(const mkq_bert_layer_params *p_host,
+                             mkq_bert_layer_workspace_layout *layout_host);
+
+/*   h_in   [M, hidden] binary16 (h_dtype == MKQ_F16) or binary32, M = batch*seq
+ *   q_in   NULL, or packed codes of h_in under sx_qkv (skips the first quantizer)
+ *   h_out  [M, hidden] binary16
+ *   q_out_next  [M, hidden/2] bytes, required iff s_out_next > 0
+ * hidden % 32 == 0, ffn % 32 == 0, hidden % heads == 0, d_k in {32, 64, 128}, seq <= 512.
+ * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, WORKSPACE, UNSUPPORTED, HIP. */
+int mkq_bert_layer_int4(const mkq_bert_layer_params *p_host, const void *h_in, int h_dtype,
+                        const uint8_t *q_in, void *h_out, uint8_t *q_out_next, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/* The same layer in the 16-bit float baseline (no quantizers). */
+typedef struct mkq_bert_layer_params_fp16 {
+    int64_t batch, seq, hidden, heads, ffn;
+    const void *W_qkv, *W_ao, *W_up, *W_down; /* binary16 [N, K] */
+    const float *b_qkv, *b_ao, *b_up, *b_down;
+    const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
+    float ln_eps;
+} mkq_bert_layer_params_fp16;
+
+size_t mkq_bert_layer_fp16_workspace_bytes(const mkq_bert_layer_params_fp16 *p_host);
+int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *p_host, const void *h_in /* binary16 */,
+                        void *h_out /* binary16 */, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/* Building blocks of the layer, exported for stage-wise parity checks.
+ * LayerNorm over the last dimension in binary32 (section 5); x binary16 [M, D];
+ * y binary16 [M, D] (may be NULL); q_out (NULL or [M, D/2]) receives
+ * codes(y_binary32; s_next).  D % 8 == 0, D <= 8192. */
+int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                  float eps, void *y, float s_next, uint8_t *q_out, void *stream);
+
+/* Attention core of section 3.2 on a fused binary16 qkv buffer [batch*seq, 3*hidden]:
+ * ctx binary16 [batch*seq, hidden] (may be NULL) and/or q_out packed codes under s_next. */
+int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
+                  void *ctx, float s_next, uint8_t *q_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MKQ_H */

@@ -1,0 +1,335 @@
+"""Python binding of libmkq (MI355X-native W4A4 BERT linear layer).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libmkq.so``.  PyTorch is used for device memory and streams.  There is no
+fallback: if the library has not been built, loading it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmkq.so")
+
+MKQ_OK = 0
+MKQ_ERR_NULL, MKQ_ERR_SHAPE, MKQ_ERR_ALIGN, MKQ_ERR_SCALE = -1, -2, -3, -4
+MKQ_ERR_DTYPE, MKQ_ERR_WORKSPACE, MKQ_ERR_UNSUPPORTED, MKQ_ERR_HIP = -5, -6, -7, -8
+MKQ_F32, MKQ_F16, MKQ_BF16, MKQ_I4 = 0, 1, 2, 3
+MKQ_ACT_NONE, MKQ_ACT_GELU = 0, 1
+
+EXPORTS = [
+    "mkq_status_string", "mkq_version", "mkq_quantize", "mkq_absmax_scale",
+    "mkq_packed_weight_bytes", "mkq_pack_weights_int4", "mkq_pack_codes_int4",
+    "mkq_unpack_weights_int4", "mkq_linear_int4_workspace_bytes", "mkq_linear_int4",
+    "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
+    "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
+]
+
+
+class MkqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Epilogue(C.Structure):
+    _fields_ = [("act", C.c_int), ("residual", C.c_void_p), ("residual_dtype", C.c_int),
+                ("s_next", C.c_float), ("q_out", C.c_void_p), ("acc_out", C.c_void_p)]
+
+
+class BertLayerParams(C.Structure):
+    _fields_ = ([(n, C.c_int64) for n in ("batch", "seq", "hidden", "heads", "ffn")]
+                + [(n, C.c_void_p) for n in ("Wq_qkv", "Wq_ao", "Wq_up", "Wq_down",
+                                             "sw_qkv", "sw_ao", "sw_up", "sw_down",
+                                             "b_qkv", "b_ao", "b_up", "b_down")]
+                + [(n, C.c_float) for n in ("sx_qkv", "sx_ao", "sx_up", "sx_down")]
+                + [(n, C.c_void_p) for n in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")]
+                + [("ln_eps", C.c_float), ("s_out_next", C.c_float)])
+
+
+class BertLayerWorkspaceLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("c0", "qkv", "c1", "u", "h1", "c2", "c3", "d", "total")]
+
+
+class BertLayerParamsFp16(C.Structure):
+    _fields_ = ([(n, C.c_int64) for n in ("batch", "seq", "hidden", "heads", "ffn")]
+                + [(n, C.c_void_p) for n in ("W_qkv", "W_ao", "W_up", "W_down",
+                                             "b_qkv", "b_ao", "b_up", "b_down",
+                                             "ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")]
+                + [("ln_eps", C.c_float)])
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads libmkq.so (built by ``python -m paper_2203_13483_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           f"`python -m paper_2203_13483_amd.build` (there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    i64, vp, f32, ci, sz = C.c_int64, C.c_void_p, C.c_float, C.c_int, C.c_size_t
+    sig = {
+        "mkq_status_string": (C.c_char_p, [ci]),
+        "mkq_version": (ci, []),
+        "mkq_quantize": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
+        "mkq_absmax_scale": (ci, [vp, ci, i64, i64, i64, ci, vp, vp]),
+        "mkq_packed_weight_bytes": (sz, [i64, i64]),
+        "mkq_pack_weights_int4": (ci, [vp, i64, i64, vp, vp, vp, vp]),
+        "mkq_pack_codes_int4": (ci, [vp, i64, i64, vp, vp]),
+        "mkq_unpack_weights_int4": (ci, [vp, i64, i64, vp, vp]),
+        "mkq_linear_int4_workspace_bytes": (sz, [i64, i64, i64, ci]),
+        "mkq_linear_int4": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
+                                 C.POINTER(Epilogue), vp, sz, vp]),
+        "mkq_linear_fp16": (ci, [vp, vp, vp, i64, i64, i64, vp, ci, ci, vp, vp]),
+        "mkq_bert_layer_workspace": (ci, [C.POINTER(BertLayerParams), C.POINTER(BertLayerWorkspaceLayout)]),
+        "mkq_bert_layer_int4": (ci, [C.POINTER(BertLayerParams), vp, ci, vp, vp, vp, vp, sz, vp]),
+        "mkq_bert_layer_fp16_workspace_bytes": (sz, [C.POINTER(BertLayerParamsFp16)]),
+        "mkq_bert_layer_fp16": (ci, [C.POINTER(BertLayerParamsFp16), vp, vp, vp, sz, vp]),
+        "mkq_layernorm": (ci, [vp, i64, i64, vp, vp, f32, vp, f32, vp, vp]),
+        "mkq_attention": (ci, [vp, i64, i64, i64, i64, vp, f32, vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().mkq_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != MKQ_OK:
+        raise MkqError(status, where)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t):
+    torch = _torch()
+    return {torch.float32: MKQ_F32, torch.float16: MKQ_F16, torch.bfloat16: MKQ_BF16}[t.dtype]
+
+
+def _torch_dtype(code):
+    torch = _torch()
+    return {MKQ_F32: torch.float32, MKQ_F16: torch.float16, MKQ_BF16: torch.bfloat16}[code]
+
+
+# ----------------------------------------------------------------------------------
+# Same names as the C entry points.  Tensors are torch CUDA tensors; outputs are
+# allocated with torch when not passed in.
+
+def mkq_version() -> int:
+    return int(load().mkq_version())
+
+
+def mkq_quantize(x, s_x: float, q_out=None, stream=None):
+    """x [M,K] float32/float16 -> packed codes uint8 [M,K/2]."""
+    torch = _torch()
+    M, K = x.shape
+    if q_out is None:
+        q_out = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+    _check(load().mkq_quantize(_ptr(x), _dtype_code(x), M, K, x.stride(0), float(s_x), _ptr(q_out),
+                               _stream(stream)), "mkq_quantize")
+    return q_out
+
+
+def mkq_absmax_scale(x, per_row: bool = False, s_out=None, stream=None):
+    torch = _torch()
+    M, K = x.shape
+    if s_out is None:
+        s_out = torch.empty(M if per_row else 1, dtype=torch.float32, device=x.device)
+    _check(load().mkq_absmax_scale(_ptr(x), _dtype_code(x), M, K, x.stride(0), int(per_row),
+                                   _ptr(s_out), _stream(stream)), "mkq_absmax_scale")
+    return s_out
+
+
+def mkq_packed_weight_bytes(N: int, K: int) -> int:
+    return int(load().mkq_packed_weight_bytes(N, K))
+
+
+def mkq_pack_weights_int4(W, s_w_in=None, stream=None):
+    """W [N,K] float32 -> (Wq uint8 [packed bytes], s_w float32 [N])."""
+    torch = _torch()
+    N, K = W.shape
+    nbytes = mkq_packed_weight_bytes(N, K)
+    Wq = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=W.device)
+    s_w = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(load().mkq_pack_weights_int4(_ptr(W), N, K, _ptr(s_w_in), _ptr(s_w), _ptr(Wq),
+                                        _stream(stream)), "mkq_pack_weights_int4")
+    return Wq, s_w
+
+
+def mkq_pack_codes_int4(codes, stream=None):
+    torch = _torch()
+    rows, K = codes.shape
+    q = torch.empty((rows, K // 2), dtype=torch.uint8, device=codes.device)
+    _check(load().mkq_pack_codes_int4(_ptr(codes), rows, K, _ptr(q), _stream(stream)),
+           "mkq_pack_codes_int4")
+    return q
+
+
+def mkq_unpack_weights_int4(Wq, N: int, K: int, stream=None):
+    torch = _torch()
+    codes = torch.empty((N, K), dtype=torch.int8, device=Wq.device)
+    _check(load().mkq_unpack_weights_int4(_ptr(Wq), N, K, _ptr(codes), _stream(stream)),
+           "mkq_unpack_weights_int4")
+    return codes
+
+
+def mkq_linear_int4_workspace_bytes(M: int, N: int, K: int, a_dtype: int) -> int:
+    return int(load().mkq_linear_int4_workspace_bytes(M, N, K, a_dtype))
+
+
+def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int = MKQ_F32, *,
+                    a_is_codes: bool | None = None, act: int = MKQ_ACT_NONE, residual=None,
+                    s_next: float = 0.0, want_q: bool = False, want_acc: bool = False,
+                    out=None, workspace=None, stream=None):
+    """The quantized linear.  ``a`` is packed codes (uint8 [M,K/2]) or float [M,K].
+
+    Returns a dict with ``out`` (float tensor, or uint8 [M,N/2] for MKQ_I4) and
+    optionally ``q`` (packed codes under s_next) and ``acc`` (int32 [M,N]).
+    """
+    torch = _torch()
+    if a_is_codes is None:
+        a_is_codes = a.dtype == torch.uint8
+    M = a.shape[0]
+    a_dtype = MKQ_I4 if a_is_codes else _dtype_code(a)
+    dev = a.device
+    if out is None:
+        out = (torch.empty((M, N // 2), dtype=torch.uint8, device=dev) if out_dtype == MKQ_I4
+               else torch.empty((M, N), dtype=_torch_dtype(out_dtype), device=dev))
+    q = torch.empty((M, N // 2), dtype=torch.uint8, device=dev) if want_q else None
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
+                   residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
+                   s_next=float(s_next), q_out=q.data_ptr() if q is not None else None,
+                   acc_out=acc.data_ptr() if acc is not None else None)
+    need = mkq_linear_int4_workspace_bytes(M, N, K, a_dtype)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().mkq_linear_int4(_ptr(a), a_dtype, float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias),
+                                  M, N, K, _ptr(out), int(out_dtype), C.byref(epi), _ptr(workspace),
+                                  ws_bytes, _stream(stream)), "mkq_linear_int4")
+    return {"out": out, "q": q, "acc": acc}
+
+
+def mkq_linear_fp16(a, W, bias, out_dtype: int = MKQ_F16, act: int = MKQ_ACT_NONE, residual=None,
+                    out=None, stream=None):
+    torch = _torch()
+    M, K = a.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=_torch_dtype(out_dtype), device=a.device)
+    _check(load().mkq_linear_fp16(_ptr(a), _ptr(W), _ptr(bias), M, N, K, _ptr(out), int(out_dtype),
+                                  int(act), _ptr(residual), _stream(stream)), "mkq_linear_fp16")
+    return out
+
+
+def mkq_layernorm(x, gamma, beta, eps: float, s_next: float = 0.0, want_y: bool = True,
+                  want_q: bool = False, stream=None):
+    torch = _torch()
+    M, D = x.shape
+    y = torch.empty((M, D), dtype=torch.float16, device=x.device) if want_y else None
+    q = torch.empty((M, D // 2), dtype=torch.uint8, device=x.device) if want_q else None
+    _check(load().mkq_layernorm(_ptr(x), M, D, _ptr(gamma), _ptr(beta), float(eps), _ptr(y),
+                                float(s_next), _ptr(q), _stream(stream)), "mkq_layernorm")
+    return y, q
+
+
+def mkq_attention(qkv, batch: int, seq: int, hidden: int, heads: int, s_next: float = 0.0,
+                  want_ctx: bool = True, want_q: bool = False, stream=None):
+    torch = _torch()
+    M = batch * seq
+    ctx = torch.empty((M, hidden), dtype=torch.float16, device=qkv.device) if want_ctx else None
+    q = torch.empty((M, hidden // 2), dtype=torch.uint8, device=qkv.device) if want_q else None
+    _check(load().mkq_attention(_ptr(qkv), batch, seq, hidden, heads, _ptr(ctx), float(s_next),
+                                _ptr(q), _stream(stream)), "mkq_attention")
+    return ctx, q
+
+
+class BertLayerInt4:
+    """Holds the device tensors of one W4A4 encoder layer and its parameter struct."""
+
+    def __init__(self, batch, seq, hidden, heads, ffn, packed: dict, sx: dict, ln: dict, ln_eps: float,
+                 s_out_next: float = 0.0):
+        self._keep = (packed, ln)
+        p = BertLayerParams()
+        p.batch, p.seq, p.hidden, p.heads, p.ffn = batch, seq, hidden, heads, ffn
+        for nm in ("qkv", "ao", "up", "down"):
+            Wq, s_w, b = packed[nm]
+            setattr(p, "Wq_" + nm, Wq.data_ptr())
+            setattr(p, "sw_" + nm, s_w.data_ptr())
+            setattr(p, "b_" + nm, b.data_ptr())
+            setattr(p, "sx_" + nm, float(sx[nm]))
+        for nm in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta"):
+            setattr(p, nm, ln[nm].data_ptr())
+        p.ln_eps = float(ln_eps)
+        p.s_out_next = float(s_out_next)
+        self.params = p
+        self.layout = BertLayerWorkspaceLayout()
+        _check(load().mkq_bert_layer_workspace(C.byref(p), C.byref(self.layout)), "mkq_bert_layer_workspace")
+        self.M, self.hidden, self.ffn = batch * seq, hidden, ffn
+
+    def workspace_bytes(self) -> int:
+        return int(self.layout.total)
+
+    def __call__(self, h_in, workspace, h_out=None, q_in=None, q_out_next=None, stream=None):
+        torch = _torch()
+        if h_out is None:
+            h_out = torch.empty((self.M, self.hidden), dtype=torch.float16, device=h_in.device)
+        _check(load().mkq_bert_layer_int4(C.byref(self.params), _ptr(h_in), _dtype_code(h_in), _ptr(q_in),
+                                          _ptr(h_out), _ptr(q_out_next), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+               "mkq_bert_layer_int4")
+        return h_out
+
+
+class BertLayerFp16:
+    """The 16-bit float baseline layer."""
+
+    def __init__(self, batch, seq, hidden, heads, ffn, weights: dict, ln: dict, ln_eps: float):
+        self._keep = (weights, ln)
+        p = BertLayerParamsFp16()
+        p.batch, p.seq, p.hidden, p.heads, p.ffn = batch, seq, hidden, heads, ffn
+        for nm in ("qkv", "ao", "up", "down"):
+            W, b = weights[nm]
+            setattr(p, "W_" + nm, W.data_ptr())
+            setattr(p, "b_" + nm, b.data_ptr())
+        for nm in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta"):
+            setattr(p, nm, ln[nm].data_ptr())
+        p.ln_eps = float(ln_eps)
+        self.params = p
+        self.M, self.hidden = batch * seq, hidden
+
+    def workspace_bytes(self) -> int:
+        return int(load().mkq_bert_layer_fp16_workspace_bytes(C.byref(self.params)))
+
+    def __call__(self, h_in, workspace, h_out=None, stream=None):
+        torch = _torch()
+        if h_out is None:
+            h_out = torch.empty((self.M, self.hidden), dtype=torch.float16, device=h_in.device)
+        _check(load().mkq_bert_layer_fp16(C.byref(self.params), _ptr(h_in), _ptr(h_out), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+               "mkq_bert_layer_fp16")
+        return h_out

@@ -1,0 +1,76 @@
+// Internal helpers shared by the translation units of libmkq (host side checks,
+// launch plumbing, small device utilities).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "mkq.h"
+
+namespace mkq {
+
+constexpr int QMIN = -8;
+constexpr int QMAX = 7;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool scale_ok(float s) { return s > 0.0f && s < __builtin_inff(); }
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+inline int launch_status() { return hipGetLastError() == hipSuccess ? MKQ_OK : MKQ_ERR_HIP; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- device utilities ------------------------------------------------------
+
+// Eq. 1, integer part, for one value: binary32 divide, clamp to the signed
+// 4-bit range, round half to even.  NaN -> 0.
+__device__ __forceinline__ int quantize_code(float x, float s)
+{
+    float v = x / s;                    // correctly rounded (no fast-math)
+    v = (v != v) ? 0.0f : v;
+    v = fminf(fmaxf(v, (float)QMIN), (float)QMAX);
+    return (int)__builtin_rintf(v);     // v_rndne_f32
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h)
+{
+    return __half2float(__ushort_as_half(h));
+}
+
+__device__ __forceinline__ uint16_t float_to_half_bits(float f)
+{
+    return __half_as_ushort(__float2half_rn(f));
+}
+
+// binary32 -> bfloat16, round to nearest even (NaN kept quiet)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7F800000u) == 0x7F800000u) {
+        if (u & 0x007FFFFFu) u |= 0x00400000u;
+        return (uint16_t)(u >> 16);
+    }
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// GELU, erf form, binary32 (activation functions stay in float32, section 5).
+__device__ __forceinline__ float gelu_erf(float x)
+{
+    return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+
+}  // namespace mkq

@@ -1,0 +1,155 @@
+"""GPU parity: the W4A4 linear (int4 GEMM + dequantize epilogue + requantization)
+vs the CPU oracle.  Integer results bit-exact, floats within 1e-3 (binary32 out)
+or 1e-2 (16-bit out) by the rule |gpu-ref| <= rtol*|ref| + rtol*rms(ref)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2203_13483_amd import workloads as wl
+from helpers import RTOL, assert_codes_match_with_tie_band, assert_float_close, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mkq():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2203_13483_amd as m
+    m.load()
+    return m
+
+
+def _codes_case(M, N, K, seed):
+    A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, seed)
+    rng = np.random.default_rng(seed + 1000)
+    bias = rng.normal(0, 0.5, N).astype(np.float32)
+    return A, Wc, s_w, s_x, bias
+
+
+def _run(mkq, A, Wc, s_w, s_x, bias, out_dtype, **kw):
+    M, K = A.shape
+    N = Wc.shape[0]
+    a_d = mkq.mkq_pack_codes_int4(to_dev(A))
+    w_d = mkq.mkq_pack_codes_int4(to_dev(Wc)).reshape(-1)
+    return mkq.mkq_linear_int4(a_d, s_x, w_d, to_dev(s_w), None if bias is None else to_dev(bias), N, K,
+                               out_dtype, **kw)
+
+
+SHAPES = [(128, 768, 768), (1, 32, 32), (16, 16, 64), (200, 328, 800), (257, 130, 96),
+          (64, 2304, 768), (1024, 768, 3072), (300, 300, 2048), (129, 257, 160)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_accumulators_and_f32_output(mkq, M, N, K):
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M + N + K)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F32, want_acc=True)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert_float_close(to_np(r["out"]), ref["y"], RTOL[0], "f32 out")
+    # every op of the epilogue is a correctly rounded binary32 op on both sides
+    assert np.array_equal(to_np(r["out"]), ref["y"])
+
+
+@pytest.mark.parametrize("K", [64, 768, 4096, 8192])
+def test_accumulator_extremes(mkq, K):
+    M, N = 48, 80
+    lo = np.full((M, K), -8, np.int8)
+    hi = np.full((N, K), 7, np.int8)
+    ones = np.ones(N, np.float32)
+    r = _run(mkq, lo, np.full((N, K), -8, np.int8), ones, 1.0, None, mkq.MKQ_F32, want_acc=True)
+    assert np.all(to_np(r["acc"]) == 64 * K)
+    assert np.all(to_np(r["out"]) == 64.0 * K)
+    r = _run(mkq, lo, hi, ones, 1.0, None, mkq.MKQ_F32, want_acc=True)
+    assert np.all(to_np(r["acc"]) == -56 * K)
+
+
+@pytest.mark.parametrize("out_dtype", [1, 2])
+@pytest.mark.parametrize("M,N,K", [(128, 768, 768), (200, 328, 800), (77, 100, 96)])
+def test_narrow_outputs(mkq, M, N, K, out_dtype):
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=out_dtype + M)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, out_dtype)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=out_dtype)
+    got = to_np(r["out"]).astype(np.float32)
+    assert_float_close(got, ref["y"], RTOL[out_dtype], "narrow out")
+    assert np.array_equal(got, ref["y"])  # RNE narrowing of identical binary32 values
+
+
+@pytest.mark.parametrize("res_dtype", ["f32", "f16"])
+def test_residual_and_requant_without_gelu_is_bit_exact(mkq, res_dtype):
+    import torch
+    M, N, K = 200, 328, 800
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=5)
+    rng = np.random.default_rng(6)
+    res = rng.normal(0, 1, (M, N)).astype(np.float32)
+    if res_dtype == "f16":
+        res = res.astype(np.float16).astype(np.float32)
+    res_d = to_dev(res, torch.float16 if res_dtype == "f16" else None)
+    ref32 = oracle.linear_int4(A, s_x, Wc, s_w, bias, residual=res)
+    s_next = float(np.float32(np.abs(ref32["y"]).max() / 20))
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, residual=res, out_dtype=oracle.F16, s_next=s_next)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, residual=res_d, s_next=s_next, want_q=True)
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"]))
+    assert ref["q"].min() == -8 and ref["q"].max() == 7  # the clamp is exercised
+    r4 = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, residual=res_d, s_next=s_next)
+    assert np.array_equal(to_np(r4["out"]), oracle.pack_nibbles(ref["q"]))
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 3072, 768), (130, 202, 96)])
+def test_gelu_then_requant(mkq, M, N, K):
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=9)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, act=oracle.ACT_GELU)
+    s_next = float(np.float32(np.abs(ref["y"]).max() / 12))
+    refq = oracle.linear_int4(A, s_x, Wc, s_w, bias, act=oracle.ACT_GELU, s_next=s_next)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F32, act=mkq.MKQ_ACT_GELU, s_next=s_next, want_q=True)
+    assert_float_close(to_np(r["out"]), ref["y"], RTOL[0], "gelu out")
+    got_codes = oracle.unpack_nibbles(to_np(r["q"]), N)
+    assert_codes_match_with_tie_band(got_codes, refq["q"], ref["y"], s_next, what="gelu requant")
+
+
+def test_config1_single_linear_float_input(mkq):
+    # BASELINE config 1: X [128,768] ~N(0,1), s_x = max|X|/7, W ~N(0,0.02) per-channel abs-max, seed 0
+    X, W, b = wl.gaussian_linear(128, 768, 768, seed=0)
+    s_x = oracle.absmax_scale(X)
+    wc, s_w_ref = oracle.quantize_weights(W)
+    ref = oracle.linear_int4(oracle.quantize(X, s_x), s_x, wc, s_w_ref, b)
+    Wq, s_w = mkq.mkq_pack_weights_int4(to_dev(W))
+    s_x_gpu = float(to_np(mkq.mkq_absmax_scale(to_dev(X)))[0])
+    assert np.float32(s_x_gpu) == np.float32(s_x)
+    r = mkq.mkq_linear_int4(to_dev(X), s_x_gpu, Wq, s_w, to_dev(b), 768, 768, mkq.MKQ_F32, want_acc=True)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert_float_close(to_np(r["out"]), ref["y"], RTOL[0], "config 1")
+    assert np.abs(ref["acc"]).max() <= 64 * 768
+
+
+def test_half_precision_float_input_and_empty_batch(mkq):
+    import torch
+    X, W, b = wl.outlier_linear(96, 256, 64, seed=3)
+    Xh = X.astype(np.float16)
+    s_x = wl.LEARNED_STEP_UNIT_GAUSSIAN
+    wc, s_w = oracle.quantize_weights(W)
+    ref = oracle.linear_int4(oracle.quantize(Xh.astype(np.float32), s_x), s_x, wc, s_w, b, out_dtype=oracle.F16)
+    Wq, s_wd = mkq.mkq_pack_weights_int4(to_dev(W))
+    r = mkq.mkq_linear_int4(to_dev(Xh), s_x, Wq, s_wd, to_dev(b), 64, 256, mkq.MKQ_F16, want_acc=True)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    empty = torch.empty((0, 128), dtype=torch.uint8, device="cuda")
+    r = mkq.mkq_linear_int4(empty, s_x, Wq, s_wd, to_dev(b), 64, 256, mkq.MKQ_F32)
+    assert r["out"].shape == (0, 64)
+
+
+def test_deterministic_and_no_out_of_bounds_writes(mkq):
+    import torch
+    M, N, K = 200, 328, 800
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=21)
+    a_d = mkq.mkq_pack_codes_int4(to_dev(A))
+    w_d = mkq.mkq_pack_codes_int4(to_dev(Wc)).reshape(-1)
+    guard = 4096
+    buf = torch.full((M * N + 2 * guard,), 1234.5, dtype=torch.float32, device="cuda")
+    out = buf[guard: guard + M * N].view(M, N)
+    r1 = mkq.mkq_linear_int4(a_d, s_x, w_d, to_dev(s_w), to_dev(bias), N, K, mkq.MKQ_F32, out=out)
+    first = to_np(r1["out"]).copy()
+    assert torch.all(buf[:guard] == 1234.5) and torch.all(buf[guard + M * N:] == 1234.5)
+    r2 = mkq.mkq_linear_int4(a_d, s_x, w_d, to_dev(s_w), to_dev(bias), N, K, mkq.MKQ_F32)
+    assert np.array_equal(first, to_np(r2["out"]))
