@@ -100,6 +100,13 @@ def load() -> C.CDLL:
     return lib
 
 
+def debug_set_gemm_config(cfg: int) -> None:
+    """Tuning hook: force one tile configuration of the int4 GEMM (-1 = automatic)."""
+    fn = load().mkq_debug_set_gemm_config
+    fn.restype, fn.argtypes = None, [C.c_int]
+    fn(int(cfg))
+
+
 def status_string(status: int) -> str:
     return load().mkq_status_string(int(status)).decode()
 

@@ -153,3 +153,19 @@ def test_deterministic_and_no_out_of_bounds_writes(mkq):
     assert torch.all(buf[:guard] == 1234.5) and torch.all(buf[guard + M * N:] == 1234.5)
     r2 = mkq.mkq_linear_int4(a_d, s_x, w_d, to_dev(s_w), to_dev(bias), N, K, mkq.MKQ_F32)
     assert np.array_equal(first, to_np(r2["out"]))
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("M,N,K", [(300, 520, 1024), (257, 130, 96), (512, 256, 2048)])
+def test_every_tile_configuration(mkq, cfg, M, N, K):
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg + M)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.BF16, s_next=0.7)
+    mkq.debug_set_gemm_config(cfg)
+    try:
+        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16, want_acc=True, want_q=True, s_next=0.7)
+        acc, out, q = to_np(r["acc"]), to_np(r["out"]), to_np(r["q"])
+    finally:
+        mkq.debug_set_gemm_config(-1)
+    assert np.array_equal(acc, ref["acc"])
+    assert np.array_equal(out.astype(np.float32), ref["y"])
+    assert np.array_equal(q, oracle.pack_nibbles(ref["q"]))
