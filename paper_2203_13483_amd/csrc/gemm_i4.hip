@@ -140,6 +140,173 @@ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, i
     tn = in_group / rows;
 }
 
+// Compile-time description of an epilogue.  The fast kernels are instantiated for the
+// few combinations the encoder layer and the benchmarks use, so that the fully
+// unrolled per-tile epilogue stays a few KiB of code; EpiGeneric reads every option
+// from the parameter block at run time (and also handles N % 8 != 0, the raw
+// accumulator output and the extra code output).
+template <int OUT, bool RES16, bool GELU>
+struct EpiFixed {
+    static constexpr bool generic = false;
+    static constexpr int out = OUT;
+    static constexpr bool res16 = RES16, gelu = GELU;
+};
+struct EpiGeneric {
+    static constexpr bool generic = true;
+    static constexpr int out = MKQ_F32;
+    static constexpr bool res16 = false, gelu = false;
+};
+
+// Epilogue of one finished tile (m0, n0 = its first token / channel; wm, wn = the
+// wave's position in the workgroup; fr = lane % 32, fh = lane / 32).
+// Register v of a lane holds channel 16*(v/8) + 8*fh + v%8 of its 32-channel tile,
+// token fr of its 32-token tile.
+template <class Cfg, class Epi>
+__device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&acc)[Cfg::TM][Cfg::TN],
+                                                 int m0, int n0, int wm, int wn, int fr, int fh)
+{
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    const int out_dtype = Epi::generic ? p.out_dtype : Epi::out;
+    const bool has_res = Epi::generic ? (p.residual != nullptr) : Epi::res16;
+    const bool res_f32 = Epi::generic ? (p.residual_dtype == MKQ_F32) : false;
+    const bool gelu = Epi::generic ? (p.act == MKQ_ACT_GELU) : Epi::gelu;
+    const bool vec_ok = Epi::generic ? ((p.N % 8) == 0) : true;
+    int32_t *const acc_out = Epi::generic ? p.acc_out : nullptr;
+    uint8_t *const q_extra = Epi::generic ? p.q_out : nullptr;
+    const bool need_y = (out_dtype >= 0) || q_extra;
+    static_for<TN>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        static_for<2>([&](auto Gc) {
+            constexpr int G = decltype(Gc)::value;
+            const int nb = n0 + wn * Cfg::WTN + t * 32 + 16 * G + 8 * fh;
+            if (nb >= p.N) return;
+            const int nvalid = (p.N - nb) < 8 ? (p.N - nb) : 8;
+            float sc[8], bi[8];
+            if (vec_ok) {
+                const float4 s0 = *reinterpret_cast<const float4 *>(p.s_w + nb);
+                const float4 s1 = *reinterpret_cast<const float4 *>(p.s_w + nb + 4);
+                sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w;
+                sc[4] = s1.x; sc[5] = s1.y; sc[6] = s1.z; sc[7] = s1.w;
+                if (p.bias) {
+                    const float4 b0 = *reinterpret_cast<const float4 *>(p.bias + nb);
+                    const float4 b1 = *reinterpret_cast<const float4 *>(p.bias + nb + 4);
+                    bi[0] = b0.x; bi[1] = b0.y; bi[2] = b0.z; bi[3] = b0.w;
+                    bi[4] = b1.x; bi[5] = b1.y; bi[6] = b1.z; bi[7] = b1.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) bi[e] = 0.0f;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int n = (e < nvalid) ? nb + e : nb;
+                    sc[e] = p.s_w[n];
+                    bi[e] = p.bias ? p.bias[n] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sc[e] = (p.s_x * sc[e]) * 0.00390625f;  // * 2^-8, exact
+            static_for<TM>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                const int m = m0 + wm * Cfg::WTM + j * 32 + fr;
+                if (m >= p.M) return;
+                const int64_t o = (int64_t)m * p.N + nb;
+                int a[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a[e] = acc[j][t][8 * G + e];
+
+                if (acc_out) {
+                    if (vec_ok) {
+                        *reinterpret_cast<int4 *>(acc_out + o) = make_int4(a[0] >> 8, a[1] >> 8, a[2] >> 8, a[3] >> 8);
+                        *reinterpret_cast<int4 *>(acc_out + o + 4) = make_int4(a[4] >> 8, a[5] >> 8, a[6] >> 8, a[7] >> 8);
+                    } else {
+                        for (int e = 0; e < nvalid; ++e) acc_out[o + e] = a[e] >> 8;
+                    }
+                }
+                if (!need_y) return;
+
+                float y[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    y[e] = __fmaf_rn((float)a[e], sc[e], bi[e]);
+                    // keep the binary32 rounding: without this the compiler folds the fma and a
+                    // later narrowing into one v_fma_mixlo_f16, which rounds only once
+                    asm volatile("" : "+v"(y[e]));
+                }
+                if (has_res) {
+                    if (res_f32) {
+                        const float *r = (const float *)p.residual + o;
+                        if (vec_ok) {
+                            const float4 r0 = *reinterpret_cast<const float4 *>(r);
+                            const float4 r1 = *reinterpret_cast<const float4 *>(r + 4);
+                            y[0] += r0.x; y[1] += r0.y; y[2] += r0.z; y[3] += r0.w;
+                            y[4] += r1.x; y[5] += r1.y; y[6] += r1.z; y[7] += r1.w;
+                        } else {
+                            for (int e = 0; e < nvalid; ++e) y[e] += r[e];
+                        }
+                    } else {
+                        const uint16_t *r = (const uint16_t *)p.residual + o;
+                        if (vec_ok) {
+                            const uint4 rr = *reinterpret_cast<const uint4 *>(r);
+                            const uint32_t rwd[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                y[2 * e] += half_bits_to_float((uint16_t)(rwd[e] & 0xFFFFu));
+                                y[2 * e + 1] += half_bits_to_float((uint16_t)(rwd[e] >> 16));
+                            }
+                        } else {
+                            for (int e = 0; e < nvalid; ++e) y[e] += half_bits_to_float(r[e]);
+                        }
+                    }
+                }
+                if (gelu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) y[e] = gelu_erf(y[e]);
+                }
+
+                if (out_dtype == MKQ_F32) {
+                    float *dst = (float *)p.out + o;
+                    if (vec_ok) {
+                        *reinterpret_cast<float4 *>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(y[4], y[5], y[6], y[7]);
+                    } else {
+                        for (int e = 0; e < nvalid; ++e) dst[e] = y[e];
+                    }
+                } else if (out_dtype == MKQ_F16 || out_dtype == MKQ_BF16) {
+                    uint32_t h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t lo = (out_dtype == MKQ_F16) ? float_to_half_bits(y[2 * e])
+                                                                   : float_to_bf16_bits(y[2 * e]);
+                        const uint32_t hi = (out_dtype == MKQ_F16) ? float_to_half_bits(y[2 * e + 1])
+                                                                   : float_to_bf16_bits(y[2 * e + 1]);
+                        h[e] = lo | (hi << 16);
+                    }
+                    uint16_t *dst = (uint16_t *)p.out + o;
+                    if (vec_ok) {
+                        *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+                    } else {
+                        for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(h[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+                if (out_dtype == MKQ_I4 || q_extra) {
+                    // Eq. 1 on the binary32 value.  N is even and nb % 8 == 0, so o is even.
+                    uint32_t packed = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        packed |= ((uint32_t)quantize_code(y[e], p.s_next) & 0xFu) << (4 * e);
+                    uint8_t *qdst = (out_dtype == MKQ_I4 ? (uint8_t *)p.out : q_extra) + (o >> 1);
+                    if (vec_ok) {
+                        *reinterpret_cast<uint32_t *>(qdst) = packed;
+                    } else {
+                        for (int e = 0; e < nvalid / 2; ++e) qdst[e] = (uint8_t)(packed >> (8 * e));
+                    }
+                }
+            });
+        });
+    });
+}
+
 template <class Cfg, bool FULL_STAGES>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_kernel(const GemmI4Params p)
 {
@@ -157,47 +324,68 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_kernel(const GemmI4Param
     const int fh = lane >> 5;  // which 16-byte half of a 32-byte k slice
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    int tile_m, tile_n;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
+    const int total_tiles = tiles_m * tiles_n;
     const int row_bytes = p.K / 2;
     const int kt_count = (row_bytes + RB - 1) / RB;
 
+    // The workgroup is persistent: it owns tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+    // and runs ONE software pipeline over all their k stages, so the loads of a tile's
+    // first stages are already in flight while the previous tile's epilogue runs.
+    const int my_tiles = (total_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int steps = my_tiles * kt_count;
+
     // --- staging: which 16-byte chunks this thread copies each stage -------------
     uint4 ra[Cfg::A_PER_T], rw[Cfg::W_PER_T];
-    const uint8_t *ga[Cfg::A_PER_T];
-    const uint8_t *gw[Cfg::W_PER_T];
+    uint32_t ga[Cfg::A_PER_T], gw[Cfg::W_PER_T];  // byte offsets of the chunks at k = 0
     int sa[Cfg::A_PER_T], sw[Cfg::W_PER_T];
     const int my_c = (tid % CH) * 16;  // byte offset of this thread's chunk inside a stage row
 #pragma unroll
     for (int i = 0; i < Cfg::A_PER_T; ++i) {
         const int idx = tid + i * THREADS;
         const int row = idx / CH, c = idx % CH;
-        int gm = m0 + row;
-        gm = gm < p.M ? gm : p.M - 1;  // rows past the edge re-read the last row; never stored
-        ga[i] = p.A + (int64_t)gm * row_bytes + c * 16;
         sa[i] = row * RB + ((c ^ swz<CH>(row & 15)) * 16);
     }
 #pragma unroll
     for (int i = 0; i < Cfg::W_PER_T; ++i) {
         const int idx = tid + i * THREADS;
         const int row = idx / CH, c = idx % CH;
-        int gn = n0 + row;
-        gn = gn < p.N ? gn : p.N - 1;
-        gw[i] = p.W + (int64_t)gn * row_bytes + c * 16;
         sw[i] = BM * RB + row * RB + ((c ^ swz<CH>(row & 15)) * 16);
     }
+    auto set_tile = [&](int tile) {
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, tm, tn);
+#pragma unroll
+        for (int i = 0; i < Cfg::A_PER_T; ++i) {
+            const int idx = tid + i * THREADS;
+            int gm = tm * BM + idx / CH;
+            gm = gm < p.M ? gm : p.M - 1;  // rows past the edge re-read the last row; never stored
+            ga[i] = (uint32_t)gm * (uint32_t)row_bytes + my_c;
+        }
+#pragma unroll
+        for (int i = 0; i < Cfg::W_PER_T; ++i) {
+            const int idx = tid + i * THREADS;
+            int gn = tn * BN + idx / CH;
+            gn = gn < p.N ? gn : p.N - 1;
+            gw[i] = (uint32_t)gn * (uint32_t)row_bytes + my_c;
+        }
+    };
 
-    auto load_stage = [&](int kt) {
-        const int kb = kt * RB;
+    int lt = blockIdx.x, lk = 0;  // load cursor: tile and k stage of the next stage to fetch
+    set_tile(lt);
+    auto load_next = [&]() {
+        const int kb = lk * RB;
         const bool in = FULL_STAGES || (kb + my_c < row_bytes);
 #pragma unroll
         for (int i = 0; i < Cfg::A_PER_T; ++i)
-            ra[i] = in ? *reinterpret_cast<const uint4 *>(ga[i] + kb) : make_uint4(0, 0, 0, 0);
+            ra[i] = in ? *reinterpret_cast<const uint4 *>(p.A + ga[i] + kb) : make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int i = 0; i < Cfg::W_PER_T; ++i)
-            rw[i] = in ? *reinterpret_cast<const uint4 *>(gw[i] + kb) : make_uint4(0, 0, 0, 0);
+            rw[i] = in ? *reinterpret_cast<const uint4 *>(p.W + gw[i] + kb) : make_uint4(0, 0, 0, 0);
+        if (++lk == kt_count) {
+            lk = 0;
+            lt += gridDim.x;
+            if (lt < total_tiles) set_tile(lt);
+        }
     };
     auto store_stage = [&](int buf) {
         uint8_t *base = smem + buf * Cfg::STAGE_BYTES;
@@ -254,153 +442,321 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_kernel(const GemmI4Param
         }
     };
 
+    auto epilogue = [&](int tile) {
+        int tile_m, tile_n;
+        tile_coords(tile, tiles_m, tiles_n, tile_m, tile_n);
+        gemm_i4_epilogue<Cfg, EpiGeneric>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
+    };  // epilogue
+
     // --- main loop: LDS double buffer, registers hold the stage after next --------
-    load_stage(0);
+    load_next();
     store_stage(0);
-    if (kt_count > 1) load_stage(1);
+    if (steps > 1) load_next();
     lds_barrier();
 
-    for (int kt = 0; kt < kt_count; ++kt) {
-        const uint8_t *base = smem + (kt & 1) * Cfg::STAGE_BYTES;
+    int ct = blockIdx.x, ck = 0;  // compute cursor
+    for (int s = 0; s < steps; ++s) {
+        const uint8_t *base = smem + (s & 1) * Cfg::STAGE_BYTES;
 #pragma unroll
         for (int r = 0; r < ROUNDS; ++r) {
             compute_round(base, r);
             if (r == ROUNDS / 2 - 1) {
-                // the other buffer was last read in the previous iteration, before its barrier
-                if (kt + 1 < kt_count) store_stage((kt + 1) & 1);
-                if (kt + 2 < kt_count) load_stage(kt + 2);
+                // the other buffer was last read in the previous step, before its barrier
+                if (s + 1 < steps) store_stage((s + 1) & 1);
+                if (s + 2 < steps) load_next();
             }
         }
         lds_barrier();
+        if (++ck == kt_count) {
+            epilogue(ct);
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[j][t][v] = 0;
+            ck = 0;
+            ct += gridDim.x;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Fast path: direct global->LDS copies (global_load_lds_dwordx4) into a ring of S
+// stage buffers.  Needs whole stages (K/2 a multiple of RB) because the copy cannot
+// zero-fill.  A wave-level copy instruction writes 64 x 16 bytes to consecutive LDS
+// addresses (M0 + 16 * lane), i.e. 1024/RB whole tile rows; the XOR swizzle is
+// applied on the global side (a lane fetches chunk slot ^ swz(row) of its row), so
+// every row is still read as one contiguous RB-byte segment.  The copies bypass the
+// registers, which lets S-1 stages be in flight per wave -- several microseconds of
+// prefetch, enough to cover HBM latency even for small tiles -- and the compiler
+// does not see them, so waiting is explicit: s_waitcnt vmcnt(n) with n = the copies
+// issued after the stage that is about to be read, then one workgroup barrier.
+template <int BM_, int BN_, int WGM_, int WGN_, int RB_, int S_>
+struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
+    using Base = GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_>;
+    static constexpr int S = S_;
+    static constexpr int WAVES = WGM_ * WGN_;
+    static constexpr int ROWS_PER_COPY = 1024 / RB_;
+    static constexpr int COPIES = Base::STAGE_BYTES / 1024;  // per stage, whole workgroup
+    static constexpr int LPW = COPIES / WAVES;               // per stage, per wave
+    static constexpr int LDS_BYTES = S * Base::STAGE_BYTES;
+    static_assert(COPIES % WAVES == 0, "copies must divide evenly over the waves");
+    static_assert(BM_ % ROWS_PER_COPY == 0, "a copy must not straddle the A / W boundary");
+    static_assert(S >= 3 && (S - 2) * LPW <= 63, "vmcnt immediate is 6 bits");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
+};
+
+__device__ __forceinline__ void dma_copy16(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <class Cfg, class Epi>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4Params p)
+{
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, RB = Cfg::RB, CH = Cfg::CH;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int S = Cfg::S, LPW = Cfg::LPW;
+    static_assert(Cfg::ROUNDS == 2, "the software pipeline below is written for 64-byte stages");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
+    const int fr = lane & 31, fh = lane >> 5;
+
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const int total_tiles = tiles_m * tiles_n;
+    const int row_bytes = p.K / 2;
+    const int kt_count = row_bytes / RB;
+    // Persistent workgroup: tiles blockIdx.x, blockIdx.x + gridDim.x, ... run through ONE
+    // software pipeline, so a tile's first stages are in flight during the previous
+    // tile's epilogue.
+    const int my_tiles = (total_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int steps = my_tiles * kt_count;
+
+    // copy q of this wave fills stage bytes [(wave*LPW + q) * 1024, +1024)
+    uint32_t goff[LPW];  // byte offset (from A or W) of this lane's chunk at k = 0
+    const int c_row = lane / CH;   // row inside the copy
+    const int c_slot = lane % CH;  // 16-byte slot inside the row
+    auto set_tile = [&](int tile) {
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, tm, tn);
+#pragma unroll
+        for (int q = 0; q < LPW; ++q) {
+            const int row = (wave * LPW + q) * Cfg::ROWS_PER_COPY + c_row;  // stage row
+            const int chunk = c_slot ^ swz<CH>(row & 15);
+            int g;
+            if (row < BM) {
+                g = tm * BM + row;
+                g = g < p.M ? g : p.M - 1;  // rows past the edge re-read the last row; never stored
+            } else {
+                g = tn * BN + (row - BM);
+                g = g < p.N ? g : p.N - 1;
+            }
+            goff[q] = (uint32_t)g * (uint32_t)row_bytes + chunk * 16;
+        }
+    };
+    int lt = blockIdx.x, lk = 0;  // copy cursor
+    set_tile(lt);
+    // Always issues LPW copies, so the number in flight never depends on where the
+    // pipeline is: past the last stage it re-fetches the last tile's stages into
+    // slots that are never read again.
+    auto copy_next = [&](int slot) {
+        const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * (LPW * 1024);
+        const uint8_t *a_k = p.A + lk * RB;
+        const uint8_t *w_k = p.W + lk * RB;
+#pragma unroll
+        for (int q = 0; q < LPW; ++q) {
+            const bool is_a = (wave * LPW + q) * Cfg::ROWS_PER_COPY < BM;  // wave-uniform
+            dma_copy16(is_a ? a_k : w_k, goff[q], dst + q * 1024);
+        }
+        if (++lk == kt_count) {
+            lk = 0;
+            if (lt + (int)gridDim.x < total_tiles) {
+                lt += gridDim.x;
+                set_tile(lt);
+            }
+        }
+    };
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][t][v] = 0;
+
+    // Per-lane LDS read offsets of every fragment for the two 64-code rounds of a stage.
+    int rdW[TN][2], rdA[TM][2];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int row = wm * Cfg::WTM + j * 32 + fr;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) rdA[j][r] = row * RB + (((r * 2 + fh) ^ swz<CH>(row & 15)) * 16);
+    }
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        const int row = wn * Cfg::WTN + t * 32 + w_row_perm(fr);
+#pragma unroll
+        for (int r = 0; r < 2; ++r) rdW[t][r] = (BM + row) * RB + (((r * 2 + fh) ^ swz<CH>(row & 15)) * 16);
     }
 
-    // --- epilogue ---------------------------------------------------------------
-    // Register v of a lane holds channel 16*(v/8) + 8*fh + v%8 of its 32-channel tile,
-    // token fr of its 32-token tile.
-    const bool vec_ok = (p.N % 8) == 0;
-    const bool need_y = (p.out_dtype >= 0) || p.q_out;
-    static_for<TN>([&](auto tc) {
-        constexpr int t = decltype(tc)::value;
-        static_for<2>([&](auto Gc) {
-            constexpr int G = decltype(Gc)::value;
-            const int nb = n0 + wn * Cfg::WTN + t * 32 + 16 * G + 8 * fh;
-            if (nb >= p.N) return;
-            const int nvalid = (p.N - nb) < 8 ? (p.N - nb) : 8;
-            float sc[8], bi[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int n = (e < nvalid) ? nb + e : nb;
-                sc[e] = (p.s_x * p.s_w[n]) * 0.00390625f;  // exact: power of two
-                bi[e] = p.bias ? p.bias[n] : 0.0f;
-            }
-            static_for<TM>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                const int m = m0 + wm * Cfg::WTM + j * 32 + fr;
-                if (m >= p.M) return;
-                const int64_t o = (int64_t)m * p.N + nb;
-                int a[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) a[e] = acc[j][t][8 * G + e];
+    // Software pipeline over k steps of 32 codes (one MFMA per accumulator tile):
+    // while the matrix core works on step h, the VALU widens the operands of step h+1
+    // and, every other step, the LDS delivers the packed fragments of the next round.
+    // All three overlap inside one wave; a 32x32x32 MFMA hides about five VALU ops.
+    uint4 rawW[TN], rawA[TM];                        // packed fragments of one round
+    v4i widW0[TN], widA0[TM], widW1[TN], widA1[TM];  // widened operands, two k steps
 
-                if (p.acc_out) {
-                    if (vec_ok) {
-                        *reinterpret_cast<int4 *>(p.acc_out + o) = make_int4(a[0] >> 8, a[1] >> 8, a[2] >> 8, a[3] >> 8);
-                        *reinterpret_cast<int4 *>(p.acc_out + o + 4) = make_int4(a[4] >> 8, a[5] >> 8, a[6] >> 8, a[7] >> 8);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) p.acc_out[o + e] = a[e] >> 8;
-                    }
-                }
-                if (!need_y) return;
+    auto read_round = [&](int stage_off, auto rc) {
+        constexpr int r = decltype(rc)::value;
+#pragma unroll
+        for (int t = 0; t < TN; ++t) rawW[t] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdW[t][r]);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) rawA[j] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdA[j][r]);
+    };
+    auto widen_step = [&](auto ksc, v4i(&ww)[TN], v4i(&wa)[TM]) {
+        constexpr int ks = decltype(ksc)::value;
+#pragma unroll
+        for (int t = 0; t < TN; ++t) ww[t] = ks ? widen(rawW[t].z, rawW[t].w) : widen(rawW[t].x, rawW[t].y);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) wa[j] = ks ? widen(rawA[j].z, rawA[j].w) : widen(rawA[j].x, rawA[j].y);
+    };
+    auto mfma_step = [&](const v4i(&ww)[TN], const v4i(&wa)[TM]) {
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+                acc[j][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ww[t], wa[j], acc[j][t], 0, 0, 0);
+    };
+    constexpr int NMFMA = TM * TN;
+    constexpr int NFRAG = TM + TN;
+    constexpr int NWIDEN = NFRAG * 6;  // VALU ops to widen one k step
+    // Scheduling recipes (hints to the instruction scheduler).
+    // "a" step: MFMAs with the widening of the next step spread evenly between them.
+    auto sched_a = [&]() {
+        constexpr int per = (NWIDEN + NMFMA - 1) / NMFMA;
+#pragma unroll
+        for (int i = 0; i < NMFMA; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
+        }
+    };
+    // "b" step: the LDS reads of the next round go out under the first MFMAs, the
+    // widening of their data under the last ones.
+    auto sched_b = [&]() {
+        constexpr int late = NMFMA - NMFMA / 2;
+        constexpr int per = (NWIDEN + late - 1) / late;
+#pragma unroll
+        for (int i = 0; i < NMFMA; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < NFRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i >= NMFMA / 2) __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
+        }
+    };
 
-                float y[8];
+    // prologue: fill S-1 ring slots, wait for stage 0, prime the register pipeline
 #pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = __fmaf_rn((float)a[e], sc[e], bi[e]);
-                if (p.residual) {
-                    if (p.residual_dtype == MKQ_F32) {
-                        const float *r = (const float *)p.residual + o;
-                        if (vec_ok) {
-                            const float4 r0 = *reinterpret_cast<const float4 *>(r);
-                            const float4 r1 = *reinterpret_cast<const float4 *>(r + 4);
-                            y[0] += r0.x; y[1] += r0.y; y[2] += r0.z; y[3] += r0.w;
-                            y[4] += r1.x; y[5] += r1.y; y[6] += r1.z; y[7] += r1.w;
-                        } else {
-                            for (int e = 0; e < nvalid; ++e) y[e] += r[e];
-                        }
-                    } else {
-                        const uint16_t *r = (const uint16_t *)p.residual + o;
-                        if (vec_ok) {
-                            const uint4 rr = *reinterpret_cast<const uint4 *>(r);
-                            const uint32_t rwd[4] = {rr.x, rr.y, rr.z, rr.w};
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                y[2 * e] += half_bits_to_float((uint16_t)(rwd[e] & 0xFFFFu));
-                                y[2 * e + 1] += half_bits_to_float((uint16_t)(rwd[e] >> 16));
-                            }
-                        } else {
-                            for (int e = 0; e < nvalid; ++e) y[e] += half_bits_to_float(r[e]);
-                        }
-                    }
-                }
-                if (p.act == MKQ_ACT_GELU) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) y[e] = gelu_erf(y[e]);
-                }
+    for (int i = 0; i < S - 1; ++i) copy_next(i);
+    wait_vmcnt<(S - 2) * LPW>();
+    lds_barrier();
+    read_round(0, IntC<0>{});
+    widen_step(IntC<0>{}, widW0, widA0);
 
-                if (p.out_dtype == MKQ_F32) {
-                    float *dst = (float *)p.out + o;
-                    if (vec_ok) {
-                        *reinterpret_cast<float4 *>(dst) = make_float4(y[0], y[1], y[2], y[3]);
-                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(y[4], y[5], y[6], y[7]);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) dst[e] = y[e];
-                    }
-                } else if (p.out_dtype == MKQ_F16 || p.out_dtype == MKQ_BF16) {
-                    uint32_t h[4];
+    int ct = blockIdx.x, ck = 0;  // compute cursor
+    int buf = 0;                  // ring slot of the stage being computed
+    for (int s = 0; s < steps; ++s) {
+        const int stage_off = buf * Cfg::STAGE_BYTES;
+        const int nbuf = (buf + 1 == S) ? 0 : buf + 1;
+
+        // round 0, k step 0
+        mfma_step(widW0, widA0);
+        widen_step(IntC<1>{}, widW1, widA1);
+        sched_a();
+        // round 0, k step 1; fetch round 1
+        read_round(stage_off, IntC<1>{});
+        mfma_step(widW1, widA1);
+        widen_step(IntC<0>{}, widW0, widA0);
+        sched_b();
+        // round 1, k step 0
+        mfma_step(widW0, widA0);
+        widen_step(IntC<1>{}, widW1, widA1);
+        sched_a();
+
+        // Stage s+1 becomes readable (S-3 younger stages may stay in flight), and the
+        // slot of stage s-1, which every wave is done with once it is past this
+        // barrier, is refilled with stage s+S-1.
+        wait_vmcnt<(S - 3) * LPW>();
+        lds_barrier();
+        copy_next(buf == 0 ? S - 1 : buf - 1);
+
+        // round 1, k step 1; fetch round 0 of the next stage
+        read_round(nbuf * Cfg::STAGE_BYTES, IntC<0>{});
+        mfma_step(widW1, widA1);
+        widen_step(IntC<0>{}, widW0, widA0);
+        sched_b();
+        buf = nbuf;
+
+        if (++ck == kt_count) {
+            int tile_m, tile_n;
+            tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
+            gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const uint32_t lo = (p.out_dtype == MKQ_F16) ? float_to_half_bits(y[2 * e])
-                                                                     : float_to_bf16_bits(y[2 * e]);
-                        const uint32_t hi = (p.out_dtype == MKQ_F16) ? float_to_half_bits(y[2 * e + 1])
-                                                                     : float_to_bf16_bits(y[2 * e + 1]);
-                        h[e] = lo | (hi << 16);
-                    }
-                    uint16_t *dst = (uint16_t *)p.out + o;
-                    if (vec_ok) {
-                        *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(h[e >> 1] >> (16 * (e & 1)));
-                    }
-                }
-                if (p.out_dtype == MKQ_I4 || p.q_out) {
-                    // Eq. 1 on the binary32 value.  N is even and nb % 8 == 0, so o is even.
-                    uint32_t packed = 0;
+            for (int j = 0; j < TM; ++j)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        packed |= ((uint32_t)quantize_code(y[e], p.s_next) & 0xFu) << (4 * e);
-                    uint8_t *qdst = (p.out_dtype == MKQ_I4 ? (uint8_t *)p.out : p.q_out) + (o >> 1);
-                    if (vec_ok) {
-                        *reinterpret_cast<uint32_t *>(qdst) = packed;
-                    } else {
-                        for (int e = 0; e < nvalid / 2; ++e) qdst[e] = (uint8_t)(packed >> (8 * e));
-                    }
-                }
-            });
-        });
-    });
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[j][t][v] = 0;
+            ck = 0;
+            ct += gridDim.x;
+        }
+    }
+    wait_vmcnt<0>();  // the trailing dummy copies must land before the LDS is released
 }
+
+static int g_num_cus = 0;
 
 template <class Cfg, bool FULL>
 static int launch_one(const GemmI4Params &p, int64_t tiles, hipStream_t st)
 {
     const size_t lds = 2 * (size_t)Cfg::STAGE_BYTES;
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set && lds > 65536) {
-        if (hipFuncSetAttribute((const void *)gemm_i4_kernel<Cfg, FULL>,
+    static int wgs_per_cu = 0;  // per instantiation
+    if (wgs_per_cu == 0) {
+        if (lds > 65536 &&
+            hipFuncSetAttribute((const void *)gemm_i4_kernel<Cfg, FULL>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return MKQ_ERR_HIP;
-        attr_set = true;
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_kernel<Cfg, FULL>, Cfg::THREADS, lds) !=
+                hipSuccess || occ < 1)
+            return MKQ_ERR_HIP;
+        if (g_num_cus == 0) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+                return MKQ_ERR_HIP;
+            g_num_cus = cus;
+        }
+        wgs_per_cu = occ > 2 ? 2 : occ;
     }
-    gemm_i4_kernel<Cfg, FULL><<<(unsigned)tiles, Cfg::THREADS, lds, st>>>(p);
+    const int64_t resident = (int64_t)g_num_cus * wgs_per_cu;
+    const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
+    gemm_i4_kernel<Cfg, FULL><<<grid, Cfg::THREADS, lds, st>>>(p);
     return launch_status();
 }
 
@@ -413,26 +769,99 @@ static int launch_gemm_i4(const GemmI4Params &p, hipStream_t st)
     return full ? launch_one<Cfg, true>(p, tiles, st) : launch_one<Cfg, false>(p, tiles, st);
 }
 
+template <class Cfg, class Epi>
+static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
+{
+    const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
+    if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    const size_t lds = Cfg::LDS_BYTES;
+    static int wgs_per_cu = 0;  // per instantiation
+    if (wgs_per_cu == 0) {
+        if (lds > 65536 &&
+            hipFuncSetAttribute((const void *)gemm_i4_dma_kernel<Cfg, Epi>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return MKQ_ERR_HIP;
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_dma_kernel<Cfg, Epi>, Cfg::THREADS, lds) !=
+                hipSuccess || occ < 1)
+            return MKQ_ERR_HIP;
+        if (g_num_cus == 0) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+                return MKQ_ERR_HIP;
+            g_num_cus = cus;
+        }
+        wgs_per_cu = occ;
+    }
+    const int64_t resident = (int64_t)g_num_cus * wgs_per_cu;
+    const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
+    gemm_i4_dma_kernel<Cfg, Epi><<<grid, Cfg::THREADS, lds, st>>>(p);
+    return launch_status();
+}
+
+// Epilogue combinations with a dedicated instantiation of the fast kernels.
+enum { EPI_F16 = 0, EPI_BF16, EPI_F32, EPI_F16_RES16, EPI_I4_GELU, EPI_I4, EPI_GENERIC };
+
+static int classify_epilogue(const GemmI4Params &p)
+{
+    if ((p.N % 8) != 0 || p.acc_out || p.q_out) return EPI_GENERIC;
+    const bool res16 = p.residual && p.residual_dtype == MKQ_F16;
+    const bool gelu = p.act == MKQ_ACT_GELU;
+    if (p.residual && !res16) return EPI_GENERIC;
+    if (p.out_dtype == MKQ_F16 && !gelu) return res16 ? EPI_F16_RES16 : EPI_F16;
+    if (res16) return EPI_GENERIC;
+    if (p.out_dtype == MKQ_BF16 && !gelu) return EPI_BF16;
+    if (p.out_dtype == MKQ_F32 && !gelu) return EPI_F32;
+    if (p.out_dtype == MKQ_I4) return gelu ? EPI_I4_GELU : EPI_I4;
+    return EPI_GENERIC;
+}
+
+template <class Cfg>
+static int launch_dma_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
+{
+    switch (epi) {
+    case EPI_F16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, false, false>>(p, st);
+    case EPI_BF16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_BF16, false, false>>(p, st);
+    case EPI_F32: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F32, false, false>>(p, st);
+    case EPI_F16_RES16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, true, false>>(p, st);
+    case EPI_I4_GELU: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, true>>(p, st);
+    case EPI_I4: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, false>>(p, st);
+    default: return launch_gemm_i4_dma<Cfg, EpiGeneric>(p, st);
+    }
+}
+
 static int g_forced_cfg = -1;  // tuning hook, see mkq_debug_set_gemm_config
+
+using DmaBig = GemmI4DmaCfg<256, 256, 2, 2, 64, 4>;    // 1 wave per SIMD, 128x128 per wave
+using DmaBig8 = GemmI4DmaCfg<256, 256, 2, 4, 64, 4>;   // 2 waves per SIMD, 128x64 per wave
+using DmaMid = GemmI4DmaCfg<128, 128, 2, 2, 64, 4>;    // 64 KiB LDS: two workgroups per CU
+using DmaSmall = GemmI4DmaCfg<64, 64, 2, 2, 64, 8>;
 
 int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
 {
     int cfg = g_forced_cfg;
+    const bool dma_ok = (p.K % 128) == 0;  // whole 64-byte stages
+    const int epi = classify_epilogue(p);
     if (cfg < 0) {
-        const int64_t t256 = ceil_div(p.M, 256) * ceil_div(p.N, 256);
-        const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
-        if (t256 >= 512) cfg = 0;
-        else if (t128 >= 256) cfg = 2;
-        else cfg = 3;
+        if (!dma_ok) {
+            cfg = 3;
+        } else {
+            const int64_t t256 = ceil_div(p.M, 256) * ceil_div(p.N, 256);
+            const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
+            if (t256 >= 256 && epi != EPI_GENERIC) cfg = 10;
+            else if (t128 >= 256) cfg = 12;
+            else cfg = 14;
+        }
     }
+    if (cfg >= 10 && !dma_ok) return MKQ_ERR_UNSUPPORTED;
     switch (cfg) {
-    case 0: return launch_gemm_i4<GemmI4Cfg<256, 256, 2, 2, 64>>(p, st);
-    case 1: return launch_gemm_i4<GemmI4Cfg<256, 128, 2, 2, 64>>(p, st);
     case 2: return launch_gemm_i4<GemmI4Cfg<128, 128, 2, 2, 64>>(p, st);
     case 3: return launch_gemm_i4<GemmI4Cfg<64, 64, 2, 2, 64>>(p, st);
-    case 4: return launch_gemm_i4<GemmI4Cfg<256, 256, 2, 2, 128>>(p, st);
-    case 5: return launch_gemm_i4<GemmI4Cfg<256, 128, 2, 2, 128>>(p, st);
-    case 6: return launch_gemm_i4<GemmI4Cfg<128, 128, 2, 2, 128>>(p, st);
+    case 10: return launch_dma_by_epilogue<DmaBig>(p, epi, st);
+    case 11: return launch_dma_by_epilogue<DmaBig8>(p, epi, st);
+    case 12: return launch_dma_by_epilogue<DmaMid>(p, epi, st);
+    case 14: return launch_dma_by_epilogue<DmaSmall>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }
@@ -483,7 +912,10 @@ extern "C" int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint
         return MKQ_ERR_ALIGN;
     const size_t need = mkq_linear_int4_workspace_bytes(M, N, K, a_dtype);
     if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return MKQ_ERR_WORKSPACE;
-    if (K >= 131072 || M > 0x7FFFFFFF || N > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    // the kernel addresses operand bytes with 32-bit offsets
+    if (K >= 131072 || M > 0x7FFFFFFF || N > 0x7FFFFFFF || M * (K / 2) > 0xFFFFFFFFLL ||
+        N * (K / 2) > 0xFFFFFFFFLL)
+        return MKQ_ERR_UNSUPPORTED;
 
     const uint8_t *codes = (const uint8_t *)a;
     if (a_dtype != MKQ_I4) {
