@@ -275,13 +275,9 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                 } else if (out_dtype == MKQ_F16 || out_dtype == MKQ_BF16) {
                     uint32_t h[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const uint32_t lo = (out_dtype == MKQ_F16) ? float_to_half_bits(y[2 * e])
-                                                                   : float_to_bf16_bits(y[2 * e]);
-                        const uint32_t hi = (out_dtype == MKQ_F16) ? float_to_half_bits(y[2 * e + 1])
-                                                                   : float_to_bf16_bits(y[2 * e + 1]);
-                        h[e] = lo | (hi << 16);
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        h[e] = (out_dtype == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1])
+                                                      : pack2_bf16(y[2 * e], y[2 * e + 1]);
                     uint16_t *dst = (uint16_t *)p.out + o;
                     if (vec_ok) {
                         *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
@@ -678,6 +674,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
     read_round(0, IntC<0>{});
     widen_step(IntC<0>{}, widW0, widA0);
 
+    // Epilogue stores share the in-order vmcnt counter with the copies.  For the S-2
+    // wait points that follow an epilogue the wanted copies are older than those
+    // stores, so the stores may stay outstanding if the wait allows for their exact
+    // number; that number is only known at compile time for interior tiles of the
+    // fixed epilogues.
+    constexpr int STORES_PER_UNIT = Epi::generic ? 0 : (Epi::out == MKQ_F32 ? 2 : 1);
+    constexpr int EPI_STORES = TN * 2 * TM * STORES_PER_UNIT;
+    constexpr bool ASYNC_STORES = !Epi::generic && ((S - 3) * LPW + EPI_STORES <= 63);
+    int stores_pending = 0;  // wait points left that may leave the epilogue's stores in flight
+
     int ct = blockIdx.x, ck = 0;  // compute cursor
     int buf = 0;                  // ring slot of the stage being computed
     for (int s = 0; s < steps; ++s) {
@@ -701,7 +707,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
         // Stage s+1 becomes readable (S-3 younger stages may stay in flight), and the
         // slot of stage s-1, which every wave is done with once it is past this
         // barrier, is refilled with stage s+S-1.
-        wait_vmcnt<(S - 3) * LPW>();
+        if (ASYNC_STORES && stores_pending > 0) {
+            wait_vmcnt<ASYNC_STORES ? (S - 3) * LPW + EPI_STORES : 0>();
+            --stores_pending;
+        } else {
+            wait_vmcnt<(S - 3) * LPW>();
+        }
         lds_barrier();
         copy_next(buf == 0 ? S - 1 : buf - 1);
 
@@ -716,6 +727,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
             int tile_m, tile_n;
             tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
             gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
+            const bool interior = (tile_m + 1) * BM <= p.M && (tile_n + 1) * BN <= p.N;
+            stores_pending = (ASYNC_STORES && interior) ? S - 2 : 0;
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
@@ -834,7 +847,7 @@ static int launch_dma_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st
 static int g_forced_cfg = -1;  // tuning hook, see mkq_debug_set_gemm_config
 
 using DmaBig = GemmI4DmaCfg<256, 256, 2, 2, 64, 4>;    // 1 wave per SIMD, 128x128 per wave
-using DmaBig8 = GemmI4DmaCfg<256, 256, 2, 4, 64, 4>;   // 2 waves per SIMD, 128x64 per wave
+using DmaBig8 = GemmI4DmaCfg<256, 256, 2, 4, 64, 5>;   // 2 waves per SIMD, 128x64 per wave
 using DmaMid = GemmI4DmaCfg<128, 128, 2, 2, 64, 4>;    // 64 KiB LDS: two workgroups per CU
 using DmaSmall = GemmI4DmaCfg<64, 64, 2, 2, 64, 8>;
 
@@ -849,8 +862,8 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
         } else {
             const int64_t t256 = ceil_div(p.M, 256) * ceil_div(p.N, 256);
             const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
-            if (t256 >= 256 && epi != EPI_GENERIC) cfg = 10;
-            else if (t128 >= 256) cfg = 12;
+            (void)t256;
+            if (t128 >= 256) cfg = 12;
             else cfg = 14;
         }
     }

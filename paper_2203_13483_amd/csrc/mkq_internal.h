@@ -67,6 +67,22 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
+// Two binary32 values -> two 16-bit floats in one word (low half = a), round to
+// nearest even, one v_cvt_pk_* instruction each on gfx950.
+typedef float mkq_f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 mkq_bf2 __attribute__((ext_vector_type(2)));
+typedef _Float16 mkq_h2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b)
+{
+    const mkq_f2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, mkq_bf2));
+}
+__device__ __forceinline__ uint32_t pack2_f16(float a, float b)
+{
+    const mkq_f2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, mkq_h2));
+}
+
 // GELU, erf form, binary32 (activation functions stay in float32, section 5).
 __device__ __forceinline__ float gelu_erf(float x)
 {
