@@ -126,7 +126,7 @@ int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, co
 /* 16-bit float baseline linear (same epilogue, no quantizers):
  *   a [M, K] binary16, W [N, K] binary16, bias [N] binary32 or NULL, binary32
  *   accumulation, out [M, N] of out_dtype (F32 or F16), residual binary16 or NULL.
- * K % 32 == 0.  Errors: NULL, SHAPE, ALIGN, DTYPE, HIP. */
+ * K % 64 == 0.  Errors: NULL, SHAPE, ALIGN, DTYPE, UNSUPPORTED, HIP. */
 int mkq_linear_fp16(const void *a, const void *W, const float *bias, int64_t M, int64_t N,
                     int64_t K, void *out, int out_dtype, int act, const void *residual,
                     void *stream);
@@ -177,7 +177,8 @@ int mkq_bert_layer_workspace(const mkq_bert_layer_params *p_host,
  *   q_in   NULL, or packed codes of h_in under sx_qkv (skips the first quantizer)
  *   h_out  [M, hidden] binary16
  *   q_out_next  [M, hidden/2] bytes, required iff s_out_next > 0
- * hidden % 32 == 0, ffn % 32 == 0, hidden % heads == 0, d_k in {32, 64, 128}, seq <= 512.
+ * hidden % 64 == 0, ffn % 64 == 0, hidden % heads == 0; currently d_k == 64, seq % 32 == 0 and
+ * seq <= 128 (anything else: UNSUPPORTED).
  * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, WORKSPACE, UNSUPPORTED, HIP. */
 int mkq_bert_layer_int4(const mkq_bert_layer_params *p_host, const void *h_in, int h_dtype,
                         const uint8_t *q_in, void *h_out, uint8_t *q_out_next, void *workspace,
@@ -205,7 +206,8 @@ int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const
                   float eps, void *y, float s_next, uint8_t *q_out, void *stream);
 
 /* Attention core of section 3.2 on a fused binary16 qkv buffer [batch*seq, 3*hidden]:
- * ctx binary16 [batch*seq, hidden] (may be NULL) and/or q_out packed codes under s_next. */
+ * ctx binary16 [batch*seq, hidden] (may be NULL) and/or q_out packed codes under s_next.
+ * Currently d_k == 64, seq % 32 == 0, seq <= 128 (anything else: UNSUPPORTED). */
 int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
                   void *ctx, float s_next, uint8_t *q_out, void *stream);
 

@@ -23,12 +23,9 @@
 // W is the MFMA "A" operand and the activations the "B" operand; W rows are read
 // in a permuted order so that a lane ends up with runs of 8 consecutive output
 // channels of one token and stores them with one or two vector stores.
-#include "mkq_internal.h"
+#include "gemm_common.h"
 
 namespace mkq {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 struct GemmI4Params {
     const uint8_t *A;   // [M, K/2]
@@ -47,30 +44,6 @@ struct GemmI4Params {
     int32_t *acc_out;   // raw accumulators, or null
 };
 
-// Workgroup barrier that orders LDS traffic only: global loads issued before it
-// stay in flight across it (a full __syncthreads would drain them).
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// 16-byte-chunk swizzle for an LDS row of CH chunks; r = row % 16.  The slot of
-// chunk c in row r is c ^ swz(r).  As a linear map over GF(2) of the row bits it
-// is injective on every set of rows that 8 or 16 consecutive lanes touch together
-// (16 rows of one fragment in natural or permuted order; consecutive rows of a
-// staging write), so such lanes always land in distinct 16-byte bank groups.
-template <int CH>
-__device__ __forceinline__ int swz(int r);
-template <>
-__device__ __forceinline__ int swz<4>(int r)
-{
-    return ((r >> 3) & 1) ^ (((r >> 2) & 1) << 1) ^ (((r >> 1) & 1) * 3);
-}
-template <>
-__device__ __forceinline__ int swz<8>(int r) { return (r & 7) ^ (((r >> 3) & 1) * 7); }
-
 // Widen two packed words (16 codes) to four int8x4 words (values 16*code).
 __device__ __forceinline__ v4i widen(uint32_t w0, uint32_t w1)
 {
@@ -80,31 +53,6 @@ __device__ __forceinline__ v4i widen(uint32_t w0, uint32_t w1)
     r.z = (int)((w1 << 4) & 0xF0F0F0F0u);
     r.w = (int)(w1 & 0xF0F0F0F0u);
     return r;
-}
-
-// Order in which the 32 rows of a W fragment are read: MFMA row i = 8g + 4h + e
-// (g = i/8, h = (i/4)%2, e = i%4) reads tile row 16*(g/2) + 8h + 4*(g%2) + e.  The
-// 32x32 result keeps rows 8*(v/4) + 4*(lane/32) + v%4 in register v, so after the
-// permutation registers 0..7 / 8..15 of a lane are channels 8*(lane/32) + 0..7 of
-// the first / second half of the 32-channel tile.
-__device__ __forceinline__ int w_row_perm(int i)
-{
-    const int g = i >> 3, h = (i >> 2) & 1, e = i & 3;
-    return 16 * (g >> 1) + 8 * h + 4 * (g & 1) + e;
-}
-
-// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
-// Used where an index selects accumulator registers, which must never become a
-// run-time index (the array would be demoted to scratch memory).
-template <int I>
-struct IntC { static constexpr int value = I; };
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (N > 0) {
-        static_for<N - 1>(f);
-        f(IntC<N - 1>{});
-    }
 }
 
 template <int BM_, int BN_, int WGM_, int WGN_, int RB_>
@@ -120,25 +68,6 @@ struct GemmI4Cfg {
     static_assert((BM * CH) % THREADS == 0 && (BN * CH) % THREADS == 0, "tile/threads mismatch");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32");
 };
-
-// XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with
-// its own L2; consecutive logical tiles are therefore given to the same XCD, and
-// logical tiles walk GROUP_M token tiles before moving to the next channel tile, so
-// the tiles resident on one XCD at a time share a few A and W row panels.
-__device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
-{
-    constexpr int XCDS = 8, GROUP_M = 8;
-    const int total = tiles_m * tiles_n;
-    int L = bid;
-    if (total % XCDS == 0) L = (bid % XCDS) * (total / XCDS) + bid / XCDS;
-    const int per_group = GROUP_M * tiles_n;
-    const int group = L / per_group;
-    const int first_m = group * GROUP_M;
-    const int rows = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
-    const int in_group = L - group * per_group;
-    tm = first_m + in_group % rows;
-    tn = in_group / rows;
-}
 
 // Compile-time description of an epilogue.  The fast kernels are instantiated for the
 // few combinations the encoder layer and the benchmarks use, so that the fully
@@ -502,20 +431,6 @@ struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
     static_assert(S >= 3 && (S - 2) * LPW <= 63, "vmcnt immediate is 6 bits");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
 };
-
-__device__ __forceinline__ void dma_copy16(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory", "m0");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
 
 template <class Cfg, class Epi>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4Params p)

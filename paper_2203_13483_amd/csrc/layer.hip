@@ -1,15 +1,393 @@
-// Encoder-layer entry points (placeholders until the kernels land).
-#include "mkq_internal.h"
+// The glue of the encoder layer (section 3.2; float32 islands of section 5):
+// LayerNorm and the attention core, each with a fused re-quantization of its
+// result for the next W4A4 linear, and the host-side sequencing of one post-LN
+// BERT layer in the int4 and in the binary16 baseline flavour.
+#include "gemm_common.h"
 
-extern "C" int mkq_linear_fp16(const void *, const void *, const float *, int64_t, int64_t, int64_t,
-                               void *, int, int, const void *, void *) { return MKQ_ERR_UNSUPPORTED; }
-extern "C" int mkq_bert_layer_workspace(const mkq_bert_layer_params *, mkq_bert_layer_workspace_layout *) { return MKQ_ERR_UNSUPPORTED; }
-extern "C" int mkq_bert_layer_int4(const mkq_bert_layer_params *, const void *, int, const uint8_t *, void *,
-                                   uint8_t *, void *, size_t, void *) { return MKQ_ERR_UNSUPPORTED; }
-extern "C" size_t mkq_bert_layer_fp16_workspace_bytes(const mkq_bert_layer_params_fp16 *) { return 0; }
-extern "C" int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *, const void *, void *, void *, size_t,
-                                   void *) { return MKQ_ERR_UNSUPPORTED; }
-extern "C" int mkq_layernorm(const void *, int64_t, int64_t, const float *, const float *, float, void *,
-                             float, uint8_t *, void *) { return MKQ_ERR_UNSUPPORTED; }
-extern "C" int mkq_attention(const void *, int64_t, int64_t, int64_t, int64_t, void *, float, uint8_t *,
-                             void *) { return MKQ_ERR_UNSUPPORTED; }
+namespace mkq {
+
+// ---------------------------------------------------------------------------------
+// LayerNorm over the last dimension: one wavefront per row, the row lives in
+// registers (binary32), two passes for mean and variance, wave-level reductions.
+// Writes the binary16 result and / or its 4-bit codes (Eq. 1 on the binary32 value).
+template <int MAXC>
+__global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restrict__ x, int M, int D,
+                                                        const float *__restrict__ gamma,
+                                                        const float *__restrict__ beta, float eps,
+                                                        uint16_t *__restrict__ y, float s_next,
+                                                        uint32_t *__restrict__ q)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const int chunks = D / 8;  // 16-byte chunks of 8 elements
+    float v[MAXC][8];
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = lane + i * 64;
+        if (c < chunks) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(x + (int64_t)row * D + c * 8);
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[i][2 * e] = half_bits_to_float((uint16_t)(w[e] & 0xFFFFu));
+                v[i][2 * e + 1] = half_bits_to_float((uint16_t)(w[e] >> 16));
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += v[i][e];
+        }
+    }
+    const float mean = wave_sum(sum) / (float)D;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        if (lane + i * 64 < chunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float d = v[i][e] - mean;
+                sq += d * d;
+            }
+        }
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + eps);
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = lane + i * 64;
+        if (c < chunks) {
+            float o[8];
+            const float4 g0 = gamma ? *reinterpret_cast<const float4 *>(gamma + c * 8) : make_float4(1, 1, 1, 1);
+            const float4 g1 = gamma ? *reinterpret_cast<const float4 *>(gamma + c * 8 + 4) : make_float4(1, 1, 1, 1);
+            const float4 b0 = beta ? *reinterpret_cast<const float4 *>(beta + c * 8) : make_float4(0, 0, 0, 0);
+            const float4 b1 = beta ? *reinterpret_cast<const float4 *>(beta + c * 8 + 4) : make_float4(0, 0, 0, 0);
+            const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+            const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (v[i][e] - mean) * rstd * gg[e] + bb[e];
+            if (y)
+                *reinterpret_cast<uint4 *>(y + (int64_t)row * D + c * 8) =
+                    make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
+            if (q) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
+                q[(int64_t)row * chunks + c] = packed;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Attention core for one (sequence, head) per workgroup: d_k = 64, seq = 32*KT <= 128.
+//   S^T = K Q^T / sqrt(d_k)   (MFMA "A" = keys in permuted row order, "B" = queries)
+//   P   = softmax over keys   (binary32; a query's 32*KT scores sit in two lanes)
+//   O^T = V^T P^T             ("A" = V^T from a transposed LDS copy, "B" = P, which is
+//                              already in operand layout thanks to the key permutation)
+// Each of the four waves owns 32 queries.  A lane ends with 8 consecutive head
+// dimensions of one query, stored as binary16 and / or as 4-bit codes.
+template <int KT>
+__global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restrict__ qkv, int seq, int hidden,
+                                                        int heads, uint16_t *__restrict__ ctx, float s_next,
+                                                        uint8_t *__restrict__ qout)
+{
+    constexpr int DK = 64, SMAX = 32 * KT;
+    __shared__ __attribute__((aligned(16))) uint8_t sQ[SMAX * 128];
+    __shared__ __attribute__((aligned(16))) uint8_t sK[SMAX * 128];
+    // V^T as [d][key]; a row is VCHP 16-byte chunks (power of two, so the XOR swizzle stays inside it)
+    constexpr int VCHP = (KT == 1) ? 4 : (KT == 2) ? 8 : 16;
+    constexpr int VROW = VCHP * 16;
+    __shared__ __attribute__((aligned(16))) uint8_t sVt[DK * VROW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 31, fh = lane >> 5;
+    const int b = blockIdx.x / heads, head = blockIdx.x % heads;
+    const int64_t row0 = (int64_t)b * seq;
+    const int ld = 3 * hidden;
+
+    // stage Q, K (row-major, swizzled chunks) and V (transposed)
+    for (int idx = tid; idx < SMAX * 8; idx += 256) {
+        const int r = idx >> 3, c = idx & 7;
+        const uint16_t *src = qkv + (row0 + r) * ld + head * DK + c * 8;
+        const uint4 qv = *reinterpret_cast<const uint4 *>(src);
+        const uint4 kv = *reinterpret_cast<const uint4 *>(src + hidden);
+        const uint4 vv = *reinterpret_cast<const uint4 *>(src + 2 * hidden);
+        const int slot = (c ^ swz<8>(r & 15)) * 16;
+        *reinterpret_cast<uint4 *>(sQ + r * 128 + slot) = qv;
+        *reinterpret_cast<uint4 *>(sK + r * 128 + slot) = kv;
+        const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int d = c * 8 + e;
+            const uint16_t val = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            const int vslot = ((r >> 3) ^ (d & (VCHP - 1))) * 16;
+            *reinterpret_cast<uint16_t *>(sVt + d * VROW + vslot + (r & 7) * 2) = val;
+        }
+    }
+    __syncthreads();
+    if (wave * 32 >= seq) return;  // no queries for this wave (seq < 128)
+
+    // scores (transposed): sc[kt] rows = keys of tile kt (permuted), column = query fr
+    v16f sc[KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sc[kt][v] = 0.0f;
+    const int qrow = wave * 32 + fr;
+#pragma unroll
+    for (int ds = 0; ds < DK / 16; ++ds) {
+        const int c = ds * 2 + fh;
+        const v8h qf = *reinterpret_cast<const v8h *>(sQ + qrow * 128 + ((c ^ swz<8>(qrow & 15)) * 16));
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            const int krow = kt * 32 + w_row_perm(fr);
+            const v8h kf = *reinterpret_cast<const v8h *>(sK + krow * 128 + ((c ^ swz<8>(krow & 15)) * 16));
+            sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf, sc[kt], 0, 0, 0);
+        }
+    }
+    // register v of tile kt is key kt*32 + 16*(v/8) + 8*fh + v%8; keys >= seq do not exist
+    const float scale = 0.125f;  // 1/sqrt(64)
+    float mx = -3.0e38f;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int key = kt * 32 + 16 * (v / 8) + 8 * fh + (v % 8);
+            sc[kt][v] = (key < seq) ? sc[kt][v] * scale : -3.0e38f;
+            mx = fmaxf(mx, sc[kt][v]);
+        }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float den = 0.0f;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            sc[kt][v] = exp2f((sc[kt][v] - mx) * 1.4426950408889634f);
+            den += sc[kt][v];
+        }
+    den += __shfl_xor(den, 32, 64);
+    const float inv = 1.0f / den;
+
+    // O^T = V^T P^T
+    v16f ot[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ot[dt][v] = 0.0f;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            v8h pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = (_Float16)(sc[kt][8 * st + e] * inv);
+            const int kc = (2 * kt + st) * 2 + fh;  // chunk of 8 keys
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                const int d = dt * 32 + w_row_perm(fr);
+                const v8h vf = *reinterpret_cast<const v8h *>(sVt + d * VROW + ((kc ^ (d & (VCHP - 1))) * 16));
+                ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, ot[dt], 0, 0, 0);
+            }
+        }
+
+    if (qrow >= seq) return;
+    const int64_t orow = row0 + qrow;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+            const int d0 = dt * 32 + 16 * G + 8 * fh;
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = ot[dt][8 * G + e];
+            const int64_t off = orow * hidden + head * DK + d0;
+            if (ctx)
+                *reinterpret_cast<uint4 *>(ctx + off) =
+                    make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
+            if (qout) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
+                *reinterpret_cast<uint32_t *>(qout + (off >> 1)) = packed;
+            }
+        }
+}
+
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace mkq
+
+using namespace mkq;
+
+extern "C" int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                             float eps, void *y, float s_next, uint8_t *q_out, void *stream)
+{
+    if (M < 0 || D <= 0 || (D % 8) != 0) return MKQ_ERR_SHAPE;
+    if (D > 8192) return MKQ_ERR_UNSUPPORTED;
+    if (q_out && !scale_ok(s_next)) return MKQ_ERR_SCALE;
+    if (!(eps >= 0.0f)) return MKQ_ERR_SCALE;
+    if (M == 0) return MKQ_OK;
+    if (!x || (!y && !q_out)) return MKQ_ERR_NULL;
+    if (!aligned16(x) || (y && !aligned16(y)) || (q_out && !aligned16(q_out)) || (gamma && !aligned16(gamma)) ||
+        (beta && !aligned16(beta)))
+        return MKQ_ERR_ALIGN;
+    if (M > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    const unsigned grid = (unsigned)ceil_div(M, 4);
+    hipStream_t st = as_stream(stream);
+#define MKQ_LN(C)                                                                                       \
+    layernorm_kernel<C><<<grid, 256, 0, st>>>((const uint16_t *)x, (int)M, (int)D, gamma, beta, eps, \
+                                              (uint16_t *)y, s_next, (uint32_t *)q_out)
+    if (D <= 1024) MKQ_LN(2);
+    else if (D <= 2048) MKQ_LN(4);
+    else if (D <= 4096) MKQ_LN(8);
+    else MKQ_LN(16);
+#undef MKQ_LN
+    return launch_status();
+}
+
+extern "C" int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
+                             void *ctx, float s_next, uint8_t *q_out, void *stream)
+{
+    if (batch < 0 || seq <= 0 || hidden <= 0 || heads <= 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
+    if (q_out && !scale_ok(s_next)) return MKQ_ERR_SCALE;
+    if (hidden / heads != 64 || (seq % 32) != 0 || seq > 128 || batch * heads > 0x7FFFFFFF)
+        return MKQ_ERR_UNSUPPORTED;
+    if (batch == 0) return MKQ_OK;
+    if (!qkv || (!ctx && !q_out)) return MKQ_ERR_NULL;
+    if (!aligned16(qkv) || (ctx && !aligned16(ctx)) || (q_out && !aligned16(q_out))) return MKQ_ERR_ALIGN;
+    const unsigned grid = (unsigned)(batch * heads);
+    hipStream_t st = as_stream(stream);
+    const uint16_t *in = (const uint16_t *)qkv;
+    switch (seq / 32) {
+    case 1: attention_kernel<1><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
+    case 2: attention_kernel<2><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
+    case 3: attention_kernel<3><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
+    default: attention_kernel<4><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
+    }
+    return launch_status();
+}
+
+// ---------------------------------------------------------------------------------
+static int check_layer_dims(int64_t batch, int64_t seq, int64_t hidden, int64_t heads, int64_t ffn)
+{
+    if (batch < 0 || seq <= 0 || hidden <= 0 || heads <= 0 || ffn <= 0) return MKQ_ERR_SHAPE;
+    if ((hidden % 64) != 0 || (ffn % 64) != 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
+    if (hidden / heads != 64 || (seq % 32) != 0 || seq > 128 || hidden > 8192) return MKQ_ERR_UNSUPPORTED;
+    return MKQ_OK;
+}
+
+extern "C" int mkq_bert_layer_workspace(const mkq_bert_layer_params *p, mkq_bert_layer_workspace_layout *L)
+{
+    if (!p || !L) return MKQ_ERR_NULL;
+    const int rc = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn);
+    if (rc != MKQ_OK) return rc;
+    const size_t M = (size_t)(p->batch * p->seq), H = (size_t)p->hidden, F = (size_t)p->ffn;
+    size_t o = 0;
+    L->c0 = o;  o += align256(M * H / 2);
+    L->qkv = o; o += align256(M * 3 * H * 2);
+    L->c1 = o;  o += align256(M * H / 2);
+    L->u = o;   o += align256(M * H * 2);
+    L->h1 = o;  o += align256(M * H * 2);
+    L->c2 = o;  o += align256(M * H / 2);
+    L->c3 = o;  o += align256(M * F / 2);
+    L->d = o;   o += align256(M * H * 2);
+    L->total = o;
+    return MKQ_OK;
+}
+
+extern "C" int mkq_bert_layer_int4(const mkq_bert_layer_params *p, const void *h_in, int h_dtype,
+                                   const uint8_t *q_in, void *h_out, uint8_t *q_out_next, void *workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    if (!p) return MKQ_ERR_NULL;
+    mkq_bert_layer_workspace_layout L;
+    int rc = mkq_bert_layer_workspace(p, &L);
+    if (rc != MKQ_OK) return rc;
+    if (h_dtype != MKQ_F16 && h_dtype != MKQ_F32) return MKQ_ERR_DTYPE;
+    if (!scale_ok(p->sx_qkv) || !scale_ok(p->sx_ao) || !scale_ok(p->sx_up) || !scale_ok(p->sx_down))
+        return MKQ_ERR_SCALE;
+    const bool want_next = p->s_out_next > 0.0f;
+    if (want_next && !scale_ok(p->s_out_next)) return MKQ_ERR_SCALE;
+    if (p->batch == 0) return MKQ_OK;
+    if (!h_in || !h_out || (want_next && !q_out_next)) return MKQ_ERR_NULL;
+    if (!p->Wq_qkv || !p->Wq_ao || !p->Wq_up || !p->Wq_down || !p->sw_qkv || !p->sw_ao || !p->sw_up ||
+        !p->sw_down)
+        return MKQ_ERR_NULL;
+    if (!workspace || workspace_bytes < L.total || !aligned16(workspace)) return MKQ_ERR_WORKSPACE;
+
+    const int64_t M = p->batch * p->seq, H = p->hidden, F = p->ffn;
+    uint8_t *ws = (uint8_t *)workspace;
+    const uint8_t *c0 = q_in;
+    if (!c0) {
+        rc = mkq_quantize(h_in, h_dtype, M, H, H, p->sx_qkv, ws + L.c0, stream);
+        if (rc != MKQ_OK) return rc;
+        c0 = ws + L.c0;
+    }
+    // q | k | v
+    rc = mkq_linear_int4(c0, MKQ_I4, p->sx_qkv, p->Wq_qkv, p->sw_qkv, p->b_qkv, M, 3 * H, H, ws + L.qkv,
+                         MKQ_F16, nullptr, nullptr, 0, stream);
+    if (rc != MKQ_OK) return rc;
+    // attention context, re-quantized for the output projection
+    rc = mkq_attention(ws + L.qkv, p->batch, p->seq, H, p->heads, nullptr, p->sx_ao, ws + L.c1, stream);
+    if (rc != MKQ_OK) return rc;
+    mkq_epilogue e;
+    e.act = MKQ_ACT_NONE; e.residual = h_in; e.residual_dtype = h_dtype; e.s_next = 0.0f;
+    e.q_out = nullptr; e.acc_out = nullptr;
+    rc = mkq_linear_int4(ws + L.c1, MKQ_I4, p->sx_ao, p->Wq_ao, p->sw_ao, p->b_ao, M, H, H, ws + L.u, MKQ_F16,
+                         &e, nullptr, 0, stream);
+    if (rc != MKQ_OK) return rc;
+    rc = mkq_layernorm(ws + L.u, M, H, p->ln1_gamma, p->ln1_beta, p->ln_eps, ws + L.h1, p->sx_up, ws + L.c2,
+                       stream);
+    if (rc != MKQ_OK) return rc;
+    // FFN up: GELU and re-quantization fused, only codes leave the kernel
+    e.act = MKQ_ACT_GELU; e.residual = nullptr; e.s_next = p->sx_down;
+    rc = mkq_linear_int4(ws + L.c2, MKQ_I4, p->sx_up, p->Wq_up, p->sw_up, p->b_up, M, F, H, ws + L.c3, MKQ_I4,
+                         &e, nullptr, 0, stream);
+    if (rc != MKQ_OK) return rc;
+    e.act = MKQ_ACT_NONE; e.residual = ws + L.h1; e.residual_dtype = MKQ_F16; e.s_next = 0.0f;
+    rc = mkq_linear_int4(ws + L.c3, MKQ_I4, p->sx_down, p->Wq_down, p->sw_down, p->b_down, M, H, F, ws + L.d,
+                         MKQ_F16, &e, nullptr, 0, stream);
+    if (rc != MKQ_OK) return rc;
+    return mkq_layernorm(ws + L.d, M, H, p->ln2_gamma, p->ln2_beta, p->ln_eps, h_out,
+                         want_next ? p->s_out_next : 1.0f, want_next ? q_out_next : nullptr, stream);
+}
+
+extern "C" size_t mkq_bert_layer_fp16_workspace_bytes(const mkq_bert_layer_params_fp16 *p)
+{
+    if (!p || check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn) != MKQ_OK) return 0;
+    const size_t M = (size_t)(p->batch * p->seq), H = (size_t)p->hidden, F = (size_t)p->ffn;
+    return align256(M * 3 * H * 2) + 4 * align256(M * H * 2) + align256(M * F * 2);
+}
+
+extern "C" int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *p, const void *h_in, void *h_out,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!p) return MKQ_ERR_NULL;
+    const int rc0 = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn);
+    if (rc0 != MKQ_OK) return rc0;
+    if (p->batch == 0) return MKQ_OK;
+    if (!h_in || !h_out || !p->W_qkv || !p->W_ao || !p->W_up || !p->W_down) return MKQ_ERR_NULL;
+    const size_t need = mkq_bert_layer_fp16_workspace_bytes(p);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return MKQ_ERR_WORKSPACE;
+    const int64_t M = p->batch * p->seq, H = p->hidden, F = p->ffn;
+    uint8_t *ws = (uint8_t *)workspace;
+    size_t o = 0;
+    uint8_t *qkv = ws + o; o += align256((size_t)M * 3 * H * 2);
+    uint8_t *ctx = ws + o; o += align256((size_t)M * H * 2);
+    uint8_t *u = ws + o;   o += align256((size_t)M * H * 2);
+    uint8_t *h1 = ws + o;  o += align256((size_t)M * H * 2);
+    uint8_t *d = ws + o;   o += align256((size_t)M * H * 2);
+    uint8_t *g = ws + o;
+    int rc = mkq_linear_fp16(h_in, p->W_qkv, p->b_qkv, M, 3 * H, H, qkv, MKQ_F16, MKQ_ACT_NONE, nullptr, stream);
+    if (rc != MKQ_OK) return rc;
+    rc = mkq_attention(qkv, p->batch, p->seq, H, p->heads, ctx, 1.0f, nullptr, stream);
+    if (rc != MKQ_OK) return rc;
+    rc = mkq_linear_fp16(ctx, p->W_ao, p->b_ao, M, H, H, u, MKQ_F16, MKQ_ACT_NONE, h_in, stream);
+    if (rc != MKQ_OK) return rc;
+    rc = mkq_layernorm(u, M, H, p->ln1_gamma, p->ln1_beta, p->ln_eps, h1, 1.0f, nullptr, stream);
+    if (rc != MKQ_OK) return rc;
+    rc = mkq_linear_fp16(h1, p->W_up, p->b_up, M, F, H, g, MKQ_F16, MKQ_ACT_GELU, nullptr, stream);
+    if (rc != MKQ_OK) return rc;
+    rc = mkq_linear_fp16(g, p->W_down, p->b_down, M, H, F, d, MKQ_F16, MKQ_ACT_NONE, h1, stream);
+    if (rc != MKQ_OK) return rc;
+    return mkq_layernorm(d, M, H, p->ln2_gamma, p->ln2_beta, p->ln_eps, h_out, 1.0f, nullptr, stream);
+}

@@ -1,0 +1,115 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol the
+public header declares, and rejects bad arguments with the documented status codes
+before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2203_13483_amd as mkq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = C.c_void_p(0x1000)      # 16-byte aligned, never dereferenced: validation fails first
+ODD = C.c_void_p(0x1004)    # misaligned
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(mkq.LIB_PATH):
+        from paper_2203_13483_amd import build
+        build.build()
+    return mkq.load()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "mkq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(mkq_[a-z0-9_]+)\s*\(", text)))
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in mkq.h but not exported"
+    assert sorted(mkq.EXPORTS) == names
+
+
+def test_status_strings(lib):
+    assert mkq.status_string(0) == "ok"
+    for code in range(-8, 0):
+        assert mkq.status_string(code) not in ("ok", "unknown status")
+    assert mkq.status_string(-99) == "unknown status"
+    assert mkq.mkq_version() >= 100
+
+
+def test_quantize_argument_errors(lib):
+    q = lib.mkq_quantize
+    assert q(None, mkq.MKQ_F32, 4, 64, 64, 1.0, P, None) == mkq.MKQ_ERR_NULL
+    assert q(P, mkq.MKQ_F32, 4, 64, 64, 1.0, None, None) == mkq.MKQ_ERR_NULL
+    assert q(P, 7, 4, 64, 64, 1.0, P, None) == mkq.MKQ_ERR_DTYPE
+    assert q(P, mkq.MKQ_BF16, 4, 64, 64, 1.0, P, None) == mkq.MKQ_ERR_DTYPE
+    assert q(P, mkq.MKQ_F32, -1, 64, 64, 1.0, P, None) == mkq.MKQ_ERR_SHAPE
+    assert q(P, mkq.MKQ_F32, 4, 48, 48, 1.0, P, None) == mkq.MKQ_ERR_SHAPE   # K % 32
+    assert q(P, mkq.MKQ_F32, 4, 64, 32, 1.0, P, None) == mkq.MKQ_ERR_SHAPE   # ldx < K
+    assert q(ODD, mkq.MKQ_F32, 4, 64, 64, 1.0, P, None) == mkq.MKQ_ERR_ALIGN
+    for s in (0.0, -1.0, float("inf"), float("nan")):
+        assert q(P, mkq.MKQ_F32, 4, 64, 64, s, P, None) == mkq.MKQ_ERR_SCALE
+    assert q(None, mkq.MKQ_F32, 0, 64, 64, 1.0, None, None) == mkq.MKQ_OK    # empty: no-op
+
+
+def test_pack_and_scale_argument_errors(lib):
+    assert lib.mkq_absmax_scale(None, 0, 4, 64, 64, 0, P, None) == mkq.MKQ_ERR_NULL
+    assert lib.mkq_absmax_scale(P, 3, 4, 64, 64, 0, P, None) == mkq.MKQ_ERR_DTYPE
+    assert lib.mkq_absmax_scale(P, 0, 0, 64, 64, 0, P, None) == mkq.MKQ_ERR_SHAPE
+    assert lib.mkq_pack_weights_int4(None, 8, 64, None, P, P, None) == mkq.MKQ_ERR_NULL
+    assert lib.mkq_pack_weights_int4(P, 8, 40, None, P, P, None) == mkq.MKQ_ERR_SHAPE
+    assert lib.mkq_pack_weights_int4(P, 8, 64, None, P, ODD, None) == mkq.MKQ_ERR_ALIGN
+    assert lib.mkq_packed_weight_bytes(768, 768) == 768 * 768 // 2
+    assert lib.mkq_packed_weight_bytes(768, 100) == 0
+    assert lib.mkq_pack_codes_int4(None, 4, 64, P, None) == mkq.MKQ_ERR_NULL
+    assert lib.mkq_unpack_weights_int4(P, 4, 33, P, None) == mkq.MKQ_ERR_SHAPE
+
+
+def _linear(lib, a=P, a_dtype=mkq.MKQ_I4, s_x=0.1, Wq=P, s_w=P, bias=P, M=8, N=64, K=64, out=P,
+            out_dtype=mkq.MKQ_F32, epi=None, ws=None, ws_bytes=0):
+    return lib.mkq_linear_int4(a, a_dtype, s_x, Wq, s_w, bias, M, N, K, out, out_dtype,
+                               C.byref(epi) if epi is not None else None, ws, ws_bytes, None)
+
+
+def test_linear_argument_errors(lib):
+    assert _linear(lib, a=None) == mkq.MKQ_ERR_NULL
+    assert _linear(lib, Wq=None) == mkq.MKQ_ERR_NULL
+    assert _linear(lib, s_w=None) == mkq.MKQ_ERR_NULL
+    assert _linear(lib, out=None) == mkq.MKQ_ERR_NULL
+    assert _linear(lib, a_dtype=9) == mkq.MKQ_ERR_DTYPE
+    assert _linear(lib, a_dtype=mkq.MKQ_BF16) == mkq.MKQ_ERR_DTYPE
+    assert _linear(lib, out_dtype=11) == mkq.MKQ_ERR_DTYPE
+    assert _linear(lib, K=48) == mkq.MKQ_ERR_SHAPE
+    assert _linear(lib, N=0) == mkq.MKQ_ERR_SHAPE
+    assert _linear(lib, M=-2) == mkq.MKQ_ERR_SHAPE
+    assert _linear(lib, a=ODD) == mkq.MKQ_ERR_ALIGN
+    assert _linear(lib, out=ODD) == mkq.MKQ_ERR_ALIGN
+    assert _linear(lib, s_x=0.0) == mkq.MKQ_ERR_SCALE
+    assert _linear(lib, s_x=float("nan")) == mkq.MKQ_ERR_SCALE
+    assert _linear(lib, K=131072) == mkq.MKQ_ERR_UNSUPPORTED
+    assert _linear(lib, M=0, a=None, out=None) == mkq.MKQ_OK
+    # codes out: N must be even and s_next valid
+    e = mkq.Epilogue(act=0, residual=None, residual_dtype=0, s_next=0.0, q_out=None, acc_out=None)
+    assert _linear(lib, out_dtype=mkq.MKQ_I4, epi=e) == mkq.MKQ_ERR_SCALE
+    e.s_next = 0.5
+    assert _linear(lib, out_dtype=mkq.MKQ_I4, N=63, epi=e) == mkq.MKQ_ERR_SHAPE
+    e.act = 5
+    assert _linear(lib, epi=e) == mkq.MKQ_ERR_DTYPE
+    e.act = 0
+    e.residual, e.residual_dtype = 0x1000, mkq.MKQ_BF16
+    assert _linear(lib, epi=e) == mkq.MKQ_ERR_DTYPE
+    # float activations need a workspace of the advertised size
+    need = lib.mkq_linear_int4_workspace_bytes(8, 64, 64, mkq.MKQ_F16)
+    assert need >= 8 * 32 and lib.mkq_linear_int4_workspace_bytes(8, 64, 64, mkq.MKQ_I4) == 0
+    assert _linear(lib, a_dtype=mkq.MKQ_F16) == mkq.MKQ_ERR_WORKSPACE
+    assert _linear(lib, a_dtype=mkq.MKQ_F16, ws=P, ws_bytes=need - 1) == mkq.MKQ_ERR_WORKSPACE
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(mkq, "_lib", None)
+    monkeypatch.setattr(mkq, "LIB_PATH", "/nonexistent/libmkq.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        mkq.load()

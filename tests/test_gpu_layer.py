@@ -1,0 +1,198 @@
+"""GPU parity: LayerNorm, attention core, binary16 baseline linear, and the W4A4 /
+binary16 encoder layers vs the CPU oracle.  Integer stages are checked
+"teacher-forced": the oracle is fed the GPU's own upstream codes, so accumulators
+and binary16 outputs must match bit for bit regardless of upstream float wobble;
+codes decided from LayerNorm / softmax / GELU outputs may differ by one step only
+inside a narrow band around a rounding boundary."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2203_13483_amd import workloads as wl
+from helpers import RTOL, assert_codes_match_with_tie_band, assert_float_close, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mkq():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2203_13483_amd as m
+    m.load()
+    return m
+
+
+def _f16(a):
+    return np.asarray(a, np.float32).astype(np.float16)
+
+
+@pytest.mark.parametrize("M,D", [(128, 768), (37, 1024), (5, 64), (64, 3072), (16, 8192)])
+def test_layernorm(mkq, M, D):
+    rng = np.random.default_rng(D + M)
+    x = _f16(rng.normal(0.2, 1.5, (M, D)))
+    g = rng.normal(1, 0.2, D).astype(np.float32)
+    b = rng.normal(0, 0.2, D).astype(np.float32)
+    s_next = 0.3
+    y, q = mkq.mkq_layernorm(to_dev(x), to_dev(g), to_dev(b), 1e-12, s_next=s_next, want_q=True)
+    ref = oracle.layernorm(x.astype(np.float32), g, b, 1e-12)
+    assert_float_close(to_np(y).astype(np.float32), oracle.round_storage(ref, oracle.F16), RTOL[1], "layernorm")
+    got = oracle.unpack_nibbles(to_np(q), D)
+    assert_codes_match_with_tie_band(got, oracle.quantize(ref, s_next), ref, s_next, what="layernorm codes")
+    # gamma = beta = None means 1 and 0
+    y0, _ = mkq.mkq_layernorm(to_dev(x), None, None, 1e-5)
+    assert_float_close(to_np(y0).astype(np.float32), oracle.layernorm(x.astype(np.float32), eps=1e-5), RTOL[1], "ln plain")
+
+
+@pytest.mark.parametrize("B,S,heads", [(2, 128, 12), (3, 64, 2), (1, 32, 1), (2, 96, 4)])
+def test_attention(mkq, B, S, heads):
+    H = heads * 64
+    rng = np.random.default_rng(S + heads)
+    qkv = _f16(rng.normal(0, 1.0, (B * S, 3 * H)))
+    s_next = 0.05
+    ctx, q = mkq.mkq_attention(to_dev(qkv), B, S, H, heads, s_next=s_next, want_q=True)
+    ref = oracle.attention(qkv.astype(np.float32), B, S, H, heads, p_dtype=oracle.F16)
+    assert_float_close(to_np(ctx).astype(np.float32), ref, RTOL[1], "attention")
+    got = oracle.unpack_nibbles(to_np(q), H)
+    assert_codes_match_with_tie_band(got, oracle.quantize(ref, s_next), ref, s_next, band=2.0 ** -6,
+                                     max_frac=2e-3, what="attention codes")
+    # the probabilities of one query sum to one: with v = 1 the context is 1
+    ones = qkv.copy()
+    ones[:, 2 * H:] = 1.0
+    ctx1, _ = mkq.mkq_attention(to_dev(ones), B, S, H, heads)
+    assert np.abs(to_np(ctx1).astype(np.float32) - 1.0).max() < 2e-3
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 768, 768), (200, 328, 192), (1024, 2304, 768), (77, 64, 3072)])
+@pytest.mark.parametrize("variant", ["plain", "gelu", "residual_f32out"])
+def test_linear_fp16_baseline(mkq, M, N, K, variant):
+    import torch
+    rng = np.random.default_rng(M + N)
+    a = _f16(rng.normal(0, 1, (M, K)))
+    W = _f16(rng.normal(0, 0.05, (N, K)))
+    b = rng.normal(0, 0.1, N).astype(np.float32)
+    res = _f16(rng.normal(0, 1, (M, N)))
+    act = mkq.MKQ_ACT_GELU if variant == "gelu" else mkq.MKQ_ACT_NONE
+    use_res = variant == "residual_f32out"
+    out_dtype = mkq.MKQ_F32 if use_res else mkq.MKQ_F16
+    y = mkq.mkq_linear_fp16(to_dev(a), to_dev(W), to_dev(b), out_dtype, act, to_dev(res) if use_res else None)
+    ref = oracle.linear_float(a.astype(np.float32), W.astype(np.float32), b,
+                              residual=res.astype(np.float32) if use_res else None,
+                              act=oracle.ACT_GELU if variant == "gelu" else oracle.ACT_NONE,
+                              out_dtype=oracle.F32 if use_res else oracle.F16)
+    assert_float_close(to_np(y).astype(np.float32), ref, RTOL[0] if use_res else RTOL[1], "fp16 linear")
+
+
+def _layer_case(seed, B, S, hidden, heads, ffn):
+    p = wl.bert_layer_weights(hidden, heads, ffn, seed)
+    rng = np.random.default_rng(seed + 7)
+    for ln in ("ln1", "ln2"):
+        p[ln + "_gamma"] = rng.normal(1, 0.1, hidden).astype(np.float32)
+        p[ln + "_beta"] = rng.normal(0, 0.1, hidden).astype(np.float32)
+    h = _f16(wl.hidden_states(B, S, hidden, seed + 1))
+    return p, h
+
+
+def _quantized_params(p, h, B, S):
+    """Oracle-side weight codes and activation steps (calibrated on the float layer)."""
+    H, F, heads = p["hidden"], p["ffn"], p["heads"]
+    hf = h.astype(np.float32)
+    qkv = oracle.linear_float(hf, p["W_qkv"], p["b_qkv"])
+    ctx = oracle.attention(qkv, B, S, H, heads)
+    u = oracle.linear_float(ctx, p["W_ao"], p["b_ao"], residual=hf)
+    h1 = oracle.layernorm(u, p["ln1_gamma"], p["ln1_beta"], p["ln_eps"])
+    g = oracle.linear_float(h1, p["W_up"], p["b_up"], act=oracle.ACT_GELU)
+    q = {k: p[k] for k in ("hidden", "heads", "ffn", "ln_eps", "ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    q["batch"], q["seq"] = B, S
+    for nm, act_in in (("qkv", hf), ("ao", ctx), ("up", h1), ("down", g)):
+        q["w_" + nm], q["sw_" + nm] = oracle.quantize_weights(p["W_" + nm])
+        q["b_" + nm] = p["b_" + nm]
+        q["sx_" + nm] = float(np.float32(oracle.absmax_scale(act_in) * 0.5))  # a learned step clips the tails
+    return q
+
+
+@pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 64, 128, 2, 256), (2, 128, 768, 12, 3072)])
+def test_bert_layer_int4_stagewise_and_end_to_end(mkq, B, S, hidden, heads, ffn):
+    import torch
+    p, h = _layer_case(31, B, S, hidden, heads, ffn)
+    q = _quantized_params(p, h, B, S)
+    M = B * S
+    packed, sx = {}, {}
+    for nm in ("qkv", "ao", "up", "down"):
+        Wq, s_w = mkq.mkq_pack_weights_int4(to_dev(p["W_" + nm]))
+        assert np.array_equal(to_np(s_w), q["sw_" + nm])
+        packed[nm] = (Wq, s_w, to_dev(p["b_" + nm]))
+        sx[nm] = q["sx_" + nm]
+    ln = {k: to_dev(p[k]) for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    s_out_next = 0.4
+    layer = mkq.BertLayerInt4(B, S, hidden, heads, ffn, packed, sx, ln, p["ln_eps"], s_out_next)
+    ws = torch.zeros(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    q_next = torch.empty((M, hidden // 2), dtype=torch.uint8, device="cuda")
+    h_out = layer(to_dev(h), ws, q_out_next=q_next)
+    torch.cuda.synchronize()
+
+    L = layer.layout
+    wsn = to_np(ws)
+
+    def codes(off, cols):
+        return oracle.unpack_nibbles(wsn[off: off + M * cols // 2], cols)
+
+    def f16buf(off, cols):
+        return wsn[off: off + M * cols * 2].view(np.float16).reshape(M, cols).astype(np.float32)
+
+    hf = h.astype(np.float32)
+    c0, c1, c2, c3 = codes(L.c0, hidden), codes(L.c1, hidden), codes(L.c2, hidden), codes(L.c3, ffn)
+    qkv, u, h1, d = f16buf(L.qkv, 3 * hidden), f16buf(L.u, hidden), f16buf(L.h1, hidden), f16buf(L.d, hidden)
+
+    # stage by stage, each fed the GPU's own inputs
+    assert np.array_equal(c0, oracle.quantize(hf, q["sx_qkv"]))
+    r = oracle.linear_int4(c0, q["sx_qkv"], q["w_qkv"], q["sw_qkv"], q["b_qkv"], out_dtype=oracle.F16)
+    assert np.array_equal(qkv, r["y"])
+    ctx_ref = oracle.attention(qkv, B, S, hidden, heads, p_dtype=oracle.F16)
+    assert_codes_match_with_tie_band(c1, oracle.quantize(ctx_ref, q["sx_ao"]), ctx_ref, q["sx_ao"], band=2.0 ** -6,
+                                     max_frac=2e-3, what="context codes")
+    r = oracle.linear_int4(c1, q["sx_ao"], q["w_ao"], q["sw_ao"], q["b_ao"], residual=hf, out_dtype=oracle.F16)
+    assert np.array_equal(u, r["y"])
+    h1_ref = oracle.layernorm(u, p["ln1_gamma"], p["ln1_beta"], p["ln_eps"])
+    assert_float_close(h1, oracle.round_storage(h1_ref, oracle.F16), RTOL[1], "h1")
+    assert_codes_match_with_tie_band(c2, oracle.quantize(h1_ref, q["sx_up"]), h1_ref, q["sx_up"], what="h1 codes")
+    r = oracle.linear_int4(c2, q["sx_up"], q["w_up"], q["sw_up"], q["b_up"], act=oracle.ACT_GELU, s_next=q["sx_down"])
+    assert_codes_match_with_tie_band(c3, r["q"], r["y"], q["sx_down"], what="ffn codes")
+    r = oracle.linear_int4(c3, q["sx_down"], q["w_down"], q["sw_down"], q["b_down"], residual=h1, out_dtype=oracle.F16)
+    assert np.array_equal(d, r["y"])
+    out_ref = oracle.layernorm(d, p["ln2_gamma"], p["ln2_beta"], p["ln_eps"])
+    got_out = to_np(h_out).astype(np.float32)
+    assert_float_close(got_out, oracle.round_storage(out_ref, oracle.F16), RTOL[1], "layer out (teacher-forced)")
+    assert_codes_match_with_tie_band(oracle.unpack_nibbles(to_np(q_next), hidden), oracle.quantize(out_ref, s_out_next),
+                                     out_ref, s_out_next, what="next-layer codes")
+
+    # end to end against the oracle's own layer: codes may flip near boundaries upstream,
+    # so only closeness is asked, and most codes must agree
+    ref_out, it = oracle.bert_layer_int4(q, hf, act_dtype=oracle.F16)
+    assert (c3 != it["c3"]).mean() < 0.02
+    err = np.abs(got_out - ref_out)
+    assert np.sqrt((err ** 2).mean()) < 0.03 * np.sqrt((ref_out ** 2).mean())
+
+    # the caller may hand in the input codes instead of having them computed
+    h_out2 = layer(to_dev(h), ws, q_in=to_dev(oracle.pack_nibbles(c0)), q_out_next=q_next)
+    assert np.array_equal(to_np(h_out2), to_np(h_out))
+
+
+@pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 64, 128, 2, 256), (2, 128, 768, 12, 3072)])
+def test_bert_layer_fp16_baseline(mkq, B, S, hidden, heads, ffn):
+    import torch
+    p, h = _layer_case(41, B, S, hidden, heads, ffn)
+    weights, ref_params = {}, {k: p[k] for k in ("hidden", "heads", "ffn", "ln_eps", "ln1_gamma", "ln1_beta",
+                                                  "ln2_gamma", "ln2_beta")}
+    ref_params["batch"], ref_params["seq"] = B, S
+    for nm in ("qkv", "ao", "up", "down"):
+        W16 = _f16(p["W_" + nm])
+        weights[nm] = (to_dev(W16), to_dev(p["b_" + nm]))
+        ref_params["w_" + nm] = W16.astype(np.float32)
+        ref_params["b_" + nm] = p["b_" + nm]
+    ln = {k: to_dev(p[k]) for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    layer = mkq.BertLayerFp16(B, S, hidden, heads, ffn, weights, ln, p["ln_eps"])
+    ws = torch.empty(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    out = to_np(layer(to_dev(h), ws)).astype(np.float32)
+    ref = oracle.bert_layer_float(ref_params, h.astype(np.float32), act_dtype=oracle.F16)
+    assert_float_close(out, oracle.round_storage(ref, oracle.F16), RTOL[1], "fp16 layer")
