@@ -107,11 +107,17 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
         constexpr int t = decltype(tc)::value;
         static_for<2>([&](auto Gc) {
             constexpr int G = decltype(Gc)::value;
+            // keep the scheduler from hoisting every unit's loads to the top (register spills)
+            __builtin_amdgcn_sched_barrier(0);
             const int nb = n0 + wn * Cfg::WTN + t * 32 + 16 * G + 8 * fh;
             if (nb >= p.N) return;
             const int nvalid = (p.N - nb) < 8 ? (p.N - nb) : 8;
             float sc[8], bi[8];
+#ifdef MKQ_EXP_NO_SWLOAD
+            if (p.M < 0) {
+#else
             if (vec_ok) {
+#endif
                 const float4 s0 = *reinterpret_cast<const float4 *>(p.s_w + nb);
                 const float4 s1 = *reinterpret_cast<const float4 *>(p.s_w + nb + 4);
                 sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w;
@@ -126,17 +132,22 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                     for (int e = 0; e < 8; ++e) bi[e] = 0.0f;
                 }
             } else {
+#ifdef MKQ_EXP_NO_SWLOAD
+                for (int e = 0; e < 8; ++e) { sc[e] = 0.5f; bi[e] = 0.25f; }
+#else
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int n = (e < nvalid) ? nb + e : nb;
                     sc[e] = p.s_w[n];
                     bi[e] = p.bias ? p.bias[n] : 0.0f;
                 }
+#endif
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) sc[e] = (p.s_x * sc[e]) * 0.00390625f;  // * 2^-8, exact
             static_for<TM>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;
+                __builtin_amdgcn_sched_barrier(0);
                 const int m = m0 + wm * Cfg::WTM + j * 32 + fr;
                 if (m >= p.M) return;
                 const int64_t o = (int64_t)m * p.N + nb;
@@ -529,24 +540,25 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
 
     // Software pipeline over k steps of 32 codes (one MFMA per accumulator tile):
     // while the matrix core works on step h, the VALU widens the operands of step h+1
-    // and, every other step, the LDS delivers the packed fragments of the next round.
-    // All three overlap inside one wave; a 32x32x32 MFMA hides about five VALU ops.
-    uint4 rawW[TN], rawA[TM];                        // packed fragments of one round
-    v4i widW0[TN], widA0[TM], widW1[TN], widA1[TM];  // widened operands, two k steps
+    // (from fragments that were fetched a whole step earlier) and, every other step,
+    // the LDS reads of the next 64-code round are issued.  All three overlap inside one
+    // wave; a 32x32x32 MFMA hides about five VALU ops.
+    uint4 rawW0[TN], rawA0[TM], rawW1[TN], rawA1[TM];  // packed fragments of two rounds
+    v4i widW0[TN], widA0[TM], widW1[TN], widA1[TM];    // widened operands, two k steps
 
-    auto read_round = [&](int stage_off, auto rc) {
+    auto read_round = [&](int stage_off, auto rc, uint4(&rw)[TN], uint4(&ra)[TM]) {
         constexpr int r = decltype(rc)::value;
 #pragma unroll
-        for (int t = 0; t < TN; ++t) rawW[t] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdW[t][r]);
+        for (int t = 0; t < TN; ++t) rw[t] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdW[t][r]);
 #pragma unroll
-        for (int j = 0; j < TM; ++j) rawA[j] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdA[j][r]);
+        for (int j = 0; j < TM; ++j) ra[j] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdA[j][r]);
     };
-    auto widen_step = [&](auto ksc, v4i(&ww)[TN], v4i(&wa)[TM]) {
+    auto widen_step = [&](const uint4(&rw)[TN], const uint4(&ra)[TM], auto ksc, v4i(&ww)[TN], v4i(&wa)[TM]) {
         constexpr int ks = decltype(ksc)::value;
 #pragma unroll
-        for (int t = 0; t < TN; ++t) ww[t] = ks ? widen(rawW[t].z, rawW[t].w) : widen(rawW[t].x, rawW[t].y);
+        for (int t = 0; t < TN; ++t) ww[t] = ks ? widen(rw[t].z, rw[t].w) : widen(rw[t].x, rw[t].y);
 #pragma unroll
-        for (int j = 0; j < TM; ++j) wa[j] = ks ? widen(rawA[j].z, rawA[j].w) : widen(rawA[j].x, rawA[j].y);
+        for (int j = 0; j < TM; ++j) wa[j] = ks ? widen(ra[j].z, ra[j].w) : widen(ra[j].x, ra[j].y);
     };
     auto mfma_step = [&](const v4i(&ww)[TN], const v4i(&wa)[TM]) {
 #pragma unroll
@@ -558,26 +570,17 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
     constexpr int NMFMA = TM * TN;
     constexpr int NFRAG = TM + TN;
     constexpr int NWIDEN = NFRAG * 6;  // VALU ops to widen one k step
-    // Scheduling recipes (hints to the instruction scheduler).
-    // "a" step: MFMAs with the widening of the next step spread evenly between them.
-    auto sched_a = [&]() {
+    // Scheduling recipe (a hint to the instruction scheduler) for one k step: MFMAs with
+    // the widening of the next step spread evenly between them and, in "a" steps, the
+    // LDS reads of the next round slotted in as well.
+    auto sched_step = [&](auto with_reads) {
+        constexpr bool reads = decltype(with_reads)::value != 0;
         constexpr int per = (NWIDEN + NMFMA - 1) / NMFMA;
 #pragma unroll
         for (int i = 0; i < NMFMA; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (reads && i < NFRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
-        }
-    };
-    // "b" step: the LDS reads of the next round go out under the first MFMAs, the
-    // widening of their data under the last ones.
-    auto sched_b = [&]() {
-        constexpr int late = NMFMA - NMFMA / 2;
-        constexpr int per = (NWIDEN + late - 1) / late;
-#pragma unroll
-        for (int i = 0; i < NMFMA; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < NFRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (i >= NMFMA / 2) __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
         }
     };
 
@@ -586,8 +589,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
     for (int i = 0; i < S - 1; ++i) copy_next(i);
     wait_vmcnt<(S - 2) * LPW>();
     lds_barrier();
-    read_round(0, IntC<0>{});
-    widen_step(IntC<0>{}, widW0, widA0);
+    read_round(0, IntC<0>{}, rawW0, rawA0);
+    widen_step(rawW0, rawA0, IntC<0>{}, widW0, widA0);
 
     // Epilogue stores share the in-order vmcnt counter with the copies.  For the S-2
     // wait points that follow an epilogue the wanted copies are older than those
@@ -605,22 +608,17 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
         const int stage_off = buf * Cfg::STAGE_BYTES;
         const int nbuf = (buf + 1 == S) ? 0 : buf + 1;
 
-        // round 0, k step 0
+        // round 0: k steps 0 and 1; the fragments of round 1 are fetched meanwhile
+        read_round(stage_off, IntC<1>{}, rawW1, rawA1);
         mfma_step(widW0, widA0);
-        widen_step(IntC<1>{}, widW1, widA1);
-        sched_a();
-        // round 0, k step 1; fetch round 1
-        read_round(stage_off, IntC<1>{});
+        widen_step(rawW0, rawA0, IntC<1>{}, widW1, widA1);
+        sched_step(IntC<1>{});
         mfma_step(widW1, widA1);
-        widen_step(IntC<0>{}, widW0, widA0);
-        sched_b();
-        // round 1, k step 0
-        mfma_step(widW0, widA0);
-        widen_step(IntC<1>{}, widW1, widA1);
-        sched_a();
+        widen_step(rawW1, rawA1, IntC<0>{}, widW0, widA0);
+        sched_step(IntC<0>{});
 
-        // Stage s+1 becomes readable (S-3 younger stages may stay in flight), and the
-        // slot of stage s-1, which every wave is done with once it is past this
+        // Mid-stage: stage s+1 becomes readable (S-3 younger stages may stay in flight),
+        // and the slot of stage s-1, which every wave is done with once it is past this
         // barrier, is refilled with stage s+S-1.
         if (ASYNC_STORES && stores_pending > 0) {
             wait_vmcnt<ASYNC_STORES ? (S - 3) * LPW + EPI_STORES : 0>();
@@ -631,11 +629,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
         lds_barrier();
         copy_next(buf == 0 ? S - 1 : buf - 1);
 
-        // round 1, k step 1; fetch round 0 of the next stage
-        read_round(nbuf * Cfg::STAGE_BYTES, IntC<0>{});
+        // round 1: k steps 2 and 3; the fragments of the next stage's round 0 are fetched
+        read_round(nbuf * Cfg::STAGE_BYTES, IntC<0>{}, rawW0, rawA0);
+        mfma_step(widW0, widA0);
+        widen_step(rawW1, rawA1, IntC<1>{}, widW1, widA1);
+        sched_step(IntC<1>{});
         mfma_step(widW1, widA1);
-        widen_step(IntC<0>{}, widW0, widA0);
-        sched_b();
+        widen_step(rawW0, rawA0, IntC<0>{}, widW0, widA0);
+        sched_step(IntC<0>{});
         buf = nbuf;
 
         if (++ck == kt_count) {
@@ -790,6 +791,8 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     case 11: return launch_dma_by_epilogue<DmaBig8>(p, epi, st);
     case 12: return launch_dma_by_epilogue<DmaMid>(p, epi, st);
     case 14: return launch_dma_by_epilogue<DmaSmall>(p, epi, st);
+    case 16: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 5>>(p, epi, st);
+    case 17: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 8>>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }
