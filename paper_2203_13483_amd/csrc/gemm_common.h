@@ -34,6 +34,8 @@ __device__ __forceinline__ int swz<4>(int r)
     return ((r >> 3) & 1) ^ (((r >> 2) & 1) << 1) ^ (((r >> 1) & 1) * 3);
 }
 template <>
+__device__ __forceinline__ int swz<2>(int r) { return ((r >> 2) ^ (r >> 3)) & 1; }
+template <>
 __device__ __forceinline__ int swz<8>(int r) { return (r & 7) ^ (((r >> 3) & 1) * 7); }
 
 // Order in which the 32 rows of a W fragment are read: MFMA row i = 8g + 4h + e

@@ -113,7 +113,7 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
             if (nb >= p.N) return;
             const int nvalid = (p.N - nb) < 8 ? (p.N - nb) : 8;
             float sc[8], bi[8];
-#ifdef MKQ_EXP_NO_SWLOAD
+#ifdef MKQ_ABL_NOSWLOAD
             if (p.M < 0) {
 #else
             if (vec_ok) {
@@ -132,7 +132,7 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                     for (int e = 0; e < 8; ++e) bi[e] = 0.0f;
                 }
             } else {
-#ifdef MKQ_EXP_NO_SWLOAD
+#ifdef MKQ_ABL_NOSWLOAD
                 for (int e = 0; e < 8; ++e) { sc[e] = 0.5f; bi[e] = 0.25f; }
 #else
 #pragma unroll
@@ -220,6 +220,9 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                                                       : pack2_bf16(y[2 * e], y[2 * e + 1]);
                     uint16_t *dst = (uint16_t *)p.out + o;
                     if (vec_ok) {
+#ifdef MKQ_ABL_NOSTORE
+                        if (h[0] == 0x12345678u && h[1] == 0x9abcdef0u && h[2] == 0x0fedcba9u)
+#endif
                         *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
                     } else {
                         for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(h[e >> 1] >> (16 * (e & 1)));
@@ -437,19 +440,29 @@ struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
     static constexpr int COPIES = Base::STAGE_BYTES / 1024;  // per stage, whole workgroup
     static constexpr int LPW = COPIES / WAVES;               // per stage, per wave
     static constexpr int LDS_BYTES = S * Base::STAGE_BYTES;
+    // resident waves per SIMD the kernel is compiled for: as many workgroups as the LDS
+    // holds (at most 2 are useful), one wave of each per SIMD per WAVES / 4
+    static constexpr int WGS_PER_CU = (160 * 1024 / LDS_BYTES) >= 2 ? 2 : 1;
+    static constexpr int WAVES_PER_EU = WGS_PER_CU * WAVES / 4;
     static_assert(COPIES % WAVES == 0, "copies must divide evenly over the waves");
     static_assert(BM_ % ROWS_PER_COPY == 0, "a copy must not straddle the A / W boundary");
-    static_assert(S >= 3 && (S - 2) * LPW <= 63, "vmcnt immediate is 6 bits");
+    // Stages in flight right after a stage's copies are issued.  With one 64-code round
+    // per stage a stage is entirely in registers before its own k steps start, so its
+    // slot is refilled one stage earlier than with two rounds per stage.
+    static constexpr int INFLIGHT = (RB_ == 64) ? S - 2 : S - 1;
+    static_assert(RB_ == 32 || RB_ == 64, "a stage is one or two 64-code rounds");
+    static_assert(S >= 3 && INFLIGHT * LPW <= 63, "vmcnt immediate is 6 bits");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
 };
 
 template <class Cfg, class Epi>
-__global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4Params p)
+__global__ __launch_bounds__(Cfg::THREADS) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_EU, Cfg::WAVES_PER_EU)))
+void gemm_i4_dma_kernel(const GemmI4Params p)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, RB = Cfg::RB, CH = Cfg::CH;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     constexpr int S = Cfg::S, LPW = Cfg::LPW;
-    static_assert(Cfg::ROUNDS == 2, "the software pipeline below is written for 64-byte stages");
+    constexpr int ROUNDS = Cfg::ROUNDS, INFLIGHT = Cfg::INFLIGHT;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
@@ -492,29 +505,6 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
             goff[q] = (uint32_t)g * (uint32_t)row_bytes + chunk * 16;
         }
     };
-    int lt = blockIdx.x, lk = 0;  // copy cursor
-    set_tile(lt);
-    // Always issues LPW copies, so the number in flight never depends on where the
-    // pipeline is: past the last stage it re-fetches the last tile's stages into
-    // slots that are never read again.
-    auto copy_next = [&](int slot) {
-        const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * (LPW * 1024);
-        const uint8_t *a_k = p.A + lk * RB;
-        const uint8_t *w_k = p.W + lk * RB;
-#pragma unroll
-        for (int q = 0; q < LPW; ++q) {
-            const bool is_a = (wave * LPW + q) * Cfg::ROWS_PER_COPY < BM;  // wave-uniform
-            dma_copy16(is_a ? a_k : w_k, goff[q], dst + q * 1024);
-        }
-        if (++lk == kt_count) {
-            lk = 0;
-            if (lt + (int)gridDim.x < total_tiles) {
-                lt += gridDim.x;
-                set_tile(lt);
-            }
-        }
-    };
-
     v16i acc[TM][TN];
 #pragma unroll
     for (int j = 0; j < TM; ++j)
@@ -524,127 +514,193 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_dma_kernel(const GemmI4P
             for (int v = 0; v < 16; ++v) acc[j][t][v] = 0;
 
     // Per-lane LDS read offsets of every fragment for the two 64-code rounds of a stage.
-    int rdW[TN][2], rdA[TM][2];
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int row = wm * Cfg::WTM + j * 32 + fr;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) rdA[j][r] = row * RB + (((r * 2 + fh) ^ swz<CH>(row & 15)) * 16);
-    }
+    // Fragments are numbered W first (0 .. TN-1), then activations (TN .. TN+TM-1).
+    constexpr int NF = TN + TM;
+    constexpr int NMFMA = TM * TN;
+    int rd[NF][ROUNDS];
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int row = wn * Cfg::WTN + t * 32 + w_row_perm(fr);
 #pragma unroll
-        for (int r = 0; r < 2; ++r) rdW[t][r] = (BM + row) * RB + (((r * 2 + fh) ^ swz<CH>(row & 15)) * 16);
+        for (int r = 0; r < ROUNDS; ++r) rd[t][r] = (BM + row) * RB + (((r * 2 + fh) ^ swz<CH>(row & 15)) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int row = wm * Cfg::WTM + j * 32 + fr;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) rd[TN + j][r] = row * RB + (((r * 2 + fh) ^ swz<CH>(row & 15)) * 16);
     }
 
-    // Software pipeline over k steps of 32 codes (one MFMA per accumulator tile):
-    // while the matrix core works on step h, the VALU widens the operands of step h+1
-    // (from fragments that were fetched a whole step earlier) and, every other step,
-    // the LDS reads of the next 64-code round are issued.  All three overlap inside one
-    // wave; a 32x32x32 MFMA hides about five VALU ops.
-    uint4 rawW0[TN], rawA0[TM], rawW1[TN], rawA1[TM];  // packed fragments of two rounds
-    v4i widW0[TN], widA0[TM], widW1[TN], widA1[TM];    // widened operands, two k steps
+    // Software pipeline over k steps of 32 codes, four per 64-byte stage.  A k step is
+    // NMFMA "slots": one MFMA each, followed by its share of the VALU widening of the
+    // NEXT step's operands and, in steps 0 and 2, one LDS fragment read of the next
+    // 64-code round (consumed a whole step later) and, in step 2, one global->LDS copy.
+    // Slots are fenced with scheduling barriers so the matrix pipe always has the next
+    // MFMA queued while the wave's VALU work runs in the shadow of the current one.
+    uint32_t raw[2][NF][4];  // packed fragments of two rounds
+    v4i wid[2][NF];          // widened operands of two k steps
 
-    auto read_round = [&](int stage_off, auto rc, uint4(&rw)[TN], uint4(&ra)[TM]) {
-        constexpr int r = decltype(rc)::value;
-#pragma unroll
-        for (int t = 0; t < TN; ++t) rw[t] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdW[t][r]);
-#pragma unroll
-        for (int j = 0; j < TM; ++j) ra[j] = *reinterpret_cast<const uint4 *>(smem + stage_off + rdA[j][r]);
+    auto read_frag = [&](int stage_off, auto fc, auto rc, uint32_t(&dst)[4]) {
+        constexpr int f = decltype(fc)::value, r = decltype(rc)::value;
+        const uint4 v = *reinterpret_cast<const uint4 *>(smem + stage_off + rd[f][r]);
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     };
-    auto widen_step = [&](const uint4(&rw)[TN], const uint4(&ra)[TM], auto ksc, v4i(&ww)[TN], v4i(&wa)[TM]) {
-        constexpr int ks = decltype(ksc)::value;
-#pragma unroll
-        for (int t = 0; t < TN; ++t) ww[t] = ks ? widen(rw[t].z, rw[t].w) : widen(rw[t].x, rw[t].y);
-#pragma unroll
-        for (int j = 0; j < TM; ++j) wa[j] = ks ? widen(ra[j].z, ra[j].w) : widen(ra[j].x, ra[j].y);
+    // register q of the widened operand: codes of word 2*ks + q/2, even (q even) or odd nibbles
+    auto widen_reg = [&](const uint32_t(&src)[4], auto ksc, auto qc) -> int {
+        constexpr int ks = decltype(ksc)::value, q = decltype(qc)::value;
+        const uint32_t w = src[2 * ks + q / 2];
+        return (int)(((q & 1) ? w : (w << 4)) & 0xF0F0F0F0u);
     };
-    auto mfma_step = [&](const v4i(&ww)[TN], const v4i(&wa)[TM]) {
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int t = 0; t < TN; ++t)
-                acc[j][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ww[t], wa[j], acc[j][t], 0, 0, 0);
+
+    int lt = blockIdx.x, lk = 0;  // copy cursor
+    set_tile(lt);
+    auto copy_one = [&](int slot, auto qc) {
+        constexpr int q = decltype(qc)::value;
+        const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * (LPW * 1024) + q * 1024;
+        const bool is_a = (wave * LPW + q) * Cfg::ROWS_PER_COPY < BM;  // wave-uniform
+        dma_copy16((is_a ? p.A : p.W) + lk * RB, goff[q], dst);
     };
-    constexpr int NMFMA = TM * TN;
-    constexpr int NFRAG = TM + TN;
-    constexpr int NWIDEN = NFRAG * 6;  // VALU ops to widen one k step
-    // Scheduling recipe (a hint to the instruction scheduler) for one k step: MFMAs with
-    // the widening of the next step spread evenly between them and, in "a" steps, the
-    // LDS reads of the next round slotted in as well.
-    auto sched_step = [&](auto with_reads) {
-        constexpr bool reads = decltype(with_reads)::value != 0;
-        constexpr int per = (NWIDEN + NMFMA - 1) / NMFMA;
-#pragma unroll
-        for (int i = 0; i < NMFMA; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (reads && i < NFRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, per, 0);
+    // Always issues LPW copies per stage, so the number in flight never depends on where
+    // the pipeline is: past the last stage it re-fetches the last tile's stages into
+    // slots that are never read again.
+    auto copy_advance = [&]() {
+        if (++lk == kt_count) {
+            lk = 0;
+            if (lt + (int)gridDim.x < total_tiles) {
+                lt += gridDim.x;
+                set_tile(lt);
+            }
         }
     };
 
-    // prologue: fill S-1 ring slots, wait for stage 0, prime the register pipeline
-#pragma unroll
-    for (int i = 0; i < S - 1; ++i) copy_next(i);
-    wait_vmcnt<(S - 2) * LPW>();
-    lds_barrier();
-    read_round(0, IntC<0>{}, rawW0, rawA0);
-    widen_step(rawW0, rawA0, IntC<0>{}, widW0, widA0);
+    // One k step.  H = step inside the stage.  Operands: wid[H & 1]; widens the next
+    // step's into wid[(H + 1) & 1] from raw[SRC] half KS; READ: fetch round RR of the
+    // stage at rd_off into raw[RB_]; COPY: issue this wave's copies into ring slot cslot.
+    auto k_step = [&](auto hc, int rd_off, int cslot) {
+        constexpr int H = decltype(hc)::value;
+        constexpr int cb = H & 1, nb = cb ^ 1;
+        constexpr int SRC = (H == 1 || H == 2) ? 1 : 0;   // raw buffer the next step is widened from
+        constexpr int KS = (H == 0 || H == 2) ? 1 : 0;    // which half of it
+        constexpr bool READ = (H == 0 || H == 2);
+        constexpr int RDST = (H == 0) ? 1 : 0;            // raw buffer the reads fill
+        constexpr int RR = (H == 0 && ROUNDS == 2) ? 1 : 0;  // round they fetch
+        constexpr bool COPY = (H == 2) || (H == 0 && ROUNDS == 1);  // reads cross into the next stage
+        static_for<NMFMA>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            constexpr int j = i / TN, t = i % TN;
+            acc[j][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wid[cb][t], wid[cb][TN + j], acc[j][t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#ifndef MKQ_ABL_NOLDS
+            if constexpr (READ) {
+                constexpr int f0 = i * NF / NMFMA, f1 = (i + 1) * NF / NMFMA;
+                static_for<f1 - f0>([&](auto fc) {
+                    constexpr int f = f0 + decltype(fc)::value;
+                    read_frag(rd_off, IntC<f>{}, IntC<RR>{}, raw[RDST][f]);
+                });
+            }
+#endif
+#ifndef MKQ_ABL_NODMA
+            if constexpr (COPY) {
+                constexpr int q0 = i * LPW / NMFMA, q1 = (i + 1) * LPW / NMFMA;
+                static_for<q1 - q0>([&](auto qc) { copy_one(cslot, IntC<q0 + decltype(qc)::value>{}); });
+            }
+#endif
+#ifndef MKQ_ABL_NOWIDEN
+            constexpr int m0 = i * 4 * NF / NMFMA, m1 = (i + 1) * 4 * NF / NMFMA;
+            static_for<m1 - m0>([&](auto mc) {
+                constexpr int m = m0 + decltype(mc)::value;
+                int w = widen_reg(raw[SRC][m / 4], IntC<KS>{}, IntC<m % 4>{});
+                // pin the op to this slot: without a use here the optimizer sinks it to the
+                // operand's first use, a whole k step (and possibly a branch) later
+                asm volatile("" : "+v"(w));
+                wid[nb][m / 4][m % 4] = w;
+            });
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
 
-    // Epilogue stores share the in-order vmcnt counter with the copies.  For the S-2
-    // wait points that follow an epilogue the wanted copies are older than those
-    // stores, so the stores may stay outstanding if the wait allows for their exact
-    // number; that number is only known at compile time for interior tiles of the
+    // prologue: put INFLIGHT + 1 stages in flight, wait for stage 0, prime the register pipeline
+#pragma unroll
+    for (int i = 0; i < INFLIGHT + 1; ++i) {
+        static_for<LPW>([&](auto qc) { copy_one(i, qc); });
+        copy_advance();
+    }
+    wait_vmcnt<INFLIGHT * LPW>();
+    lds_barrier();
+    static_for<NF>([&](auto fc) { read_frag(0, fc, IntC<0>{}, raw[0][decltype(fc)::value]); });
+    static_for<4 * NF>([&](auto mc) {
+        constexpr int m = decltype(mc)::value;
+        wid[0][m / 4][m % 4] = widen_reg(raw[0][m / 4], IntC<0>{}, IntC<m % 4>{});
+    });
+
+    // Epilogue stores share the in-order vmcnt counter with the copies.  For the
+    // INFLIGHT stage boundaries that follow an epilogue the wanted copies are older than
+    // those stores, so the stores may stay outstanding if the wait allows for their
+    // exact number; that number is only known at compile time for interior tiles of the
     // fixed epilogues.
     constexpr int STORES_PER_UNIT = Epi::generic ? 0 : (Epi::out == MKQ_F32 ? 2 : 1);
     constexpr int EPI_STORES = TN * 2 * TM * STORES_PER_UNIT;
-    constexpr bool ASYNC_STORES = !Epi::generic && ((S - 3) * LPW + EPI_STORES <= 63);
-    int stores_pending = 0;  // wait points left that may leave the epilogue's stores in flight
+    constexpr bool ASYNC_STORES = !Epi::generic && ((INFLIGHT - 1) * LPW + EPI_STORES <= 63);
+    int stores_pending = 0;  // boundaries left that may leave the epilogue's stores in flight
+
+    // Stage boundary: the next stage becomes readable (INFLIGHT-1 younger stages may stay
+    // in flight); past the barrier every wave is done with the slot that is refilled next.
+    auto stage_boundary = [&]() {
+        if (ASYNC_STORES && stores_pending > 0) {
+            wait_vmcnt<ASYNC_STORES ? (INFLIGHT - 1) * LPW + EPI_STORES : 0>();
+            --stores_pending;
+        } else {
+            wait_vmcnt<(INFLIGHT - 1) * LPW>();
+        }
+#ifndef MKQ_ABL_NOBAR
+        lds_barrier();
+#endif
+    };
+    auto next_slot = [&](int b) { return (b + 1 == S) ? 0 : b + 1; };
 
     int ct = blockIdx.x, ck = 0;  // compute cursor
     int buf = 0;                  // ring slot of the stage being computed
-    for (int s = 0; s < steps; ++s) {
-        const int stage_off = buf * Cfg::STAGE_BYTES;
-        const int nbuf = (buf + 1 == S) ? 0 : buf + 1;
-
-        // round 0: k steps 0 and 1; the fragments of round 1 are fetched meanwhile
-        read_round(stage_off, IntC<1>{}, rawW1, rawA1);
-        mfma_step(widW0, widA0);
-        widen_step(rawW0, rawA0, IntC<1>{}, widW1, widA1);
-        sched_step(IntC<1>{});
-        mfma_step(widW1, widA1);
-        widen_step(rawW1, rawA1, IntC<0>{}, widW0, widA0);
-        sched_step(IntC<0>{});
-
-        // Mid-stage: stage s+1 becomes readable (S-3 younger stages may stay in flight),
-        // and the slot of stage s-1, which every wave is done with once it is past this
-        // barrier, is refilled with stage s+S-1.
-        if (ASYNC_STORES && stores_pending > 0) {
-            wait_vmcnt<ASYNC_STORES ? (S - 3) * LPW + EPI_STORES : 0>();
-            --stores_pending;
+    for (int s = 0; s < steps; s += 3 - ROUNDS) {
+        if constexpr (ROUNDS == 2) {
+            // one 128-code stage: round 1 is fetched from the same stage, then the boundary,
+            // then round 0 of the next stage while the slot of the previous one is refilled
+            const int nbuf = next_slot(buf);
+            k_step(IntC<0>{}, buf * Cfg::STAGE_BYTES, 0);
+            k_step(IntC<1>{}, 0, 0);
+            stage_boundary();
+            k_step(IntC<2>{}, nbuf * Cfg::STAGE_BYTES, buf == 0 ? S - 1 : buf - 1);
+            copy_advance();
+            k_step(IntC<3>{}, 0, 0);
+            buf = nbuf;
+            ck += 1;
         } else {
-            wait_vmcnt<(S - 3) * LPW>();
+            // two 64-code stages (the raw / wid register buffers alternate, so the body is
+            // unrolled twice); each stage's own slot is refilled at its boundary
+            int nbuf = next_slot(buf);
+            stage_boundary();
+            k_step(IntC<0>{}, nbuf * Cfg::STAGE_BYTES, buf);
+            copy_advance();
+            k_step(IntC<1>{}, 0, 0);
+            buf = nbuf;
+            nbuf = next_slot(buf);
+            stage_boundary();
+            k_step(IntC<2>{}, nbuf * Cfg::STAGE_BYTES, buf);
+            copy_advance();
+            k_step(IntC<3>{}, 0, 0);
+            buf = nbuf;
+            ck += 2;
         }
-        lds_barrier();
-        copy_next(buf == 0 ? S - 1 : buf - 1);
 
-        // round 1: k steps 2 and 3; the fragments of the next stage's round 0 are fetched
-        read_round(nbuf * Cfg::STAGE_BYTES, IntC<0>{}, rawW0, rawA0);
-        mfma_step(widW0, widA0);
-        widen_step(rawW1, rawA1, IntC<1>{}, widW1, widA1);
-        sched_step(IntC<1>{});
-        mfma_step(widW1, widA1);
-        widen_step(rawW0, rawA0, IntC<0>{}, widW0, widA0);
-        sched_step(IntC<0>{});
-        buf = nbuf;
-
-        if (++ck == kt_count) {
+        if (ck == kt_count) {
             int tile_m, tile_n;
             tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
+#ifdef MKQ_ABL_NOEPI
+            if (p.M < 0)
+#endif
             gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
             const bool interior = (tile_m + 1) * BM <= p.M && (tile_n + 1) * BN <= p.N;
-            stores_pending = (ASYNC_STORES && interior) ? S - 2 : 0;
+            stores_pending = (ASYNC_STORES && interior) ? INFLIGHT : 0;
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
@@ -762,7 +818,6 @@ static int launch_dma_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st
 
 static int g_forced_cfg = -1;  // tuning hook, see mkq_debug_set_gemm_config
 
-using DmaBig = GemmI4DmaCfg<256, 256, 2, 2, 64, 4>;    // 1 wave per SIMD, 128x128 per wave
 using DmaBig8 = GemmI4DmaCfg<256, 256, 2, 4, 64, 5>;   // 2 waves per SIMD, 128x64 per wave
 using DmaMid = GemmI4DmaCfg<128, 128, 2, 2, 64, 4>;    // 64 KiB LDS: two workgroups per CU
 using DmaSmall = GemmI4DmaCfg<64, 64, 2, 2, 64, 8>;
@@ -787,12 +842,14 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     switch (cfg) {
     case 2: return launch_gemm_i4<GemmI4Cfg<128, 128, 2, 2, 64>>(p, st);
     case 3: return launch_gemm_i4<GemmI4Cfg<64, 64, 2, 2, 64>>(p, st);
-    case 10: return launch_dma_by_epilogue<DmaBig>(p, epi, st);
     case 11: return launch_dma_by_epilogue<DmaBig8>(p, epi, st);
     case 12: return launch_dma_by_epilogue<DmaMid>(p, epi, st);
     case 14: return launch_dma_by_epilogue<DmaSmall>(p, epi, st);
-    case 16: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 5>>(p, epi, st);
-    case 17: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 8>>(p, epi, st);
+    case 18: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
+    case 19: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 256, 2, 2, 64, 3>>(p, epi, st);
+    case 20: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 32, 6>>(p, epi, st);
+    case 21: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 256, 2, 2, 32, 6>>(p, epi, st);
+    case 22: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 32, 8>>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }

@@ -155,7 +155,10 @@ def test_deterministic_and_no_out_of_bounds_writes(mkq):
     assert np.array_equal(first, to_np(r2["out"]))
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 10, 11, 12, 14])
+ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 21, 22]
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS)
 @pytest.mark.parametrize("M,N,K", [(300, 520, 1024), (257, 130, 96), (512, 256, 2048), (1500, 1100, 384)])
 def test_every_tile_configuration(mkq, cfg, M, N, K):
     if cfg >= 10 and K % 128:
@@ -171,3 +174,26 @@ def test_every_tile_configuration(mkq, cfg, M, N, K):
     assert np.array_equal(acc, ref["acc"])
     assert np.array_equal(out.astype(np.float32), ref["y"])
     assert np.array_equal(q, oracle.pack_nibbles(ref["q"]))
+
+
+@pytest.mark.parametrize("cfg", [c for c in ALL_CFGS if c >= 10])
+@pytest.mark.parametrize("out_name", ["bf16", "i4"])
+def test_persistent_pipeline_over_many_tiles(mkq, cfg, out_name):
+    """More tiles than resident workgroups, ragged edges, the compile-time epilogues:
+    the ring pipeline carries on across tiles and epilogue stores stay in flight."""
+    M, N, K = 8200, 2312, 256
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg)
+    if out_name == "bf16":
+        ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.BF16)
+    else:
+        ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, s_next=0.9)
+    mkq.debug_set_gemm_config(cfg)
+    try:
+        if out_name == "bf16":
+            r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16)
+            assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+        else:
+            r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=0.9)
+            assert np.array_equal(to_np(r["out"]), oracle.pack_nibbles(ref["q"]))
+    finally:
+        mkq.debug_set_gemm_config(-1)
