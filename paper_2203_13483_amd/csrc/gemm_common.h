@@ -82,12 +82,15 @@ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, i
     tn = in_group / rows;
 }
 
-__device__ __forceinline__ void dma_copy16(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+// One wave-level global->LDS copy: lane l fetches 16 bytes at base + voff and they
+// land at LDS address lds_base + LDS_IMM + 16 * l.
+template <int LDS_IMM>
+__device__ __forceinline__ void dma_copy16(const uint8_t *base, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory", "m0");
+                 : "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_IMM)
+                 : "memory", "m0", "scc");
 }
 
 template <int N>

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_f16_kernel(const GemmF16Par
 #pragma unroll
         for (int q = 0; q < LPW; ++q) {
             const bool is_a = (wave * LPW + q) * Cfg::ROWS_PER_COPY < BM;
-            dma_copy16(is_a ? a_k : w_k, goff[q], dst + q * 1024);
+            dma_copy16<0>(is_a ? a_k : w_k, goff[q], dst + q * 1024);
         }
         if (++lk == kt_count) {
             lk = 0;

@@ -42,7 +42,17 @@ struct GemmI4Params {
     float s_next;
     uint8_t *q_out;     // extra packed codes, or null
     int32_t *acc_out;   // raw accumulators, or null
+#ifdef MKQ_TRACE
+    unsigned long long *dbg;
+#endif
 };
+#ifdef MKQ_TRACE
+static unsigned long long *g_trace_buf = nullptr;
+#define MKQ_TR(tag) do { if (tron && tri < 500) { tr[tri++] = ((unsigned long long)clock64() << 4) | (tag); } } while (0)
+#define MKQ_TRW(tag) do { if (tron && tri < 500) { tr[tri++] = ((unsigned long long)wall_clock64() << 4) | (tag); } } while (0)
+#else
+#define MKQ_TR(tag) do { } while (0)
+#endif
 
 // Widen two packed words (16 codes) to four int8x4 words (values 16*code).
 __device__ __forceinline__ v4i widen(uint32_t w0, uint32_t w1)
@@ -472,6 +482,13 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
     const int fr = lane & 31, fh = lane >> 5;
+#ifdef MKQ_TRACE
+    unsigned long long *tr = (unsigned long long *)(smem + Cfg::LDS_BYTES);
+    int tri = 0;
+    const bool tron = (tid == 0);
+    MKQ_TRW(6);
+    MKQ_TR(0);
+#endif
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const int total_tiles = tiles_m * tiles_n;
@@ -554,18 +571,25 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
 
     int lt = blockIdx.x, lk = 0;  // copy cursor
     set_tile(lt);
+    // Per copy: one SALU op (M0 = LDS destination) and the copy itself.  The k offset
+    // of the stage is folded into two base pointers that are advanced once per stage.
+    const uint8_t *a_k = p.A, *w_k = p.W;
+    const uint32_t lds_wave = lds0 + wave * (LPW * 1024);
     auto copy_one = [&](int slot, auto qc) {
         constexpr int q = decltype(qc)::value;
-        const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * (LPW * 1024) + q * 1024;
         const bool is_a = (wave * LPW + q) * Cfg::ROWS_PER_COPY < BM;  // wave-uniform
-        dma_copy16((is_a ? p.A : p.W) + lk * RB, goff[q], dst);
+        dma_copy16<q * 1024>(is_a ? a_k : w_k, goff[q], lds_wave + slot * Cfg::STAGE_BYTES);
     };
     // Always issues LPW copies per stage, so the number in flight never depends on where
     // the pipeline is: past the last stage it re-fetches the last tile's stages into
     // slots that are never read again.
     auto copy_advance = [&]() {
+        a_k += RB;
+        w_k += RB;
         if (++lk == kt_count) {
             lk = 0;
+            a_k = p.A;
+            w_k = p.W;
             if (lt + (int)gridDim.x < total_tiles) {
                 lt += gridDim.x;
                 set_tile(lt);
@@ -588,7 +612,14 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         static_for<NMFMA>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             constexpr int j = i / TN, t = i % TN;
-            acc[j][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wid[cb][t], wid[cb][TN + j], acc[j][t], 0, 0, 0);
+            if constexpr (Cfg::WAVES_PER_EU == 1) {
+                // a single wave owns the SIMD's 512 registers: keep the accumulators in the
+                // AGPR half by construction
+                asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0"
+                             : "+a"(acc[j][t]) : "v"(wid[cb][t]), "v"(wid[cb][TN + j]));
+            } else {
+                acc[j][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wid[cb][t], wid[cb][TN + j], acc[j][t], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #ifndef MKQ_ABL_NOLDS
             if constexpr (READ) {
@@ -647,15 +678,18 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     // Stage boundary: the next stage becomes readable (INFLIGHT-1 younger stages may stay
     // in flight); past the barrier every wave is done with the slot that is refilled next.
     auto stage_boundary = [&]() {
+        MKQ_TR(1);
         if (ASYNC_STORES && stores_pending > 0) {
             wait_vmcnt<ASYNC_STORES ? (INFLIGHT - 1) * LPW + EPI_STORES : 0>();
             --stores_pending;
         } else {
             wait_vmcnt<(INFLIGHT - 1) * LPW>();
         }
+        MKQ_TR(2);
 #ifndef MKQ_ABL_NOBAR
         lds_barrier();
 #endif
+        MKQ_TR(3);
     };
     auto next_slot = [&](int b) { return (b + 1 == S) ? 0 : b + 1; };
 
@@ -695,6 +729,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         if (ck == kt_count) {
             int tile_m, tile_n;
             tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
+            MKQ_TR(4);
 #ifdef MKQ_ABL_NOEPI
             if (p.M < 0)
 #endif
@@ -709,9 +744,18 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
                     for (int v = 0; v < 16; ++v) acc[j][t][v] = 0;
             ck = 0;
             ct += gridDim.x;
+            MKQ_TR(5);
         }
     }
     wait_vmcnt<0>();  // the trailing dummy copies must land before the LDS is released
+#ifdef MKQ_TRACE
+    MKQ_TR(8);
+    MKQ_TRW(7);
+    if (tron && p.dbg && blockIdx.x < 1024) {
+        p.dbg[blockIdx.x * 512] = tri;
+        for (int i = 0; i < tri; ++i) p.dbg[blockIdx.x * 512 + 1 + i] = tr[i];
+    }
+#endif
 }
 
 static int g_num_cus = 0;
@@ -759,7 +803,12 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+#ifdef MKQ_TRACE
+    const size_t lds = Cfg::LDS_BYTES + 4096;
+    const_cast<GemmI4Params &>(p).dbg = g_trace_buf;
+#else
     const size_t lds = Cfg::LDS_BYTES;
+#endif
     static int wgs_per_cu = 0;  // per instantiation
     if (wgs_per_cu == 0) {
         if (lds > 65536 &&
@@ -850,6 +899,7 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     case 20: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 32, 6>>(p, epi, st);
     case 21: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 256, 2, 2, 32, 6>>(p, epi, st);
     case 22: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 32, 8>>(p, epi, st);
+    case 23: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 256, 2, 2, 64, 4>>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }
@@ -861,6 +911,9 @@ using namespace mkq;
 // Tuning hook (not part of the public header): force one tile configuration of the
 // int4 GEMM (-1 = automatic choice).
 extern "C" void mkq_debug_set_gemm_config(int cfg) { mkq::g_forced_cfg = cfg; }
+#ifdef MKQ_TRACE
+extern "C" void mkq_debug_set_trace(unsigned long long *buf) { mkq::g_trace_buf = buf; }
+#endif
 
 extern "C" size_t mkq_linear_int4_workspace_bytes(int64_t M, int64_t N, int64_t K, int a_dtype)
 {
