@@ -93,6 +93,16 @@ __device__ __forceinline__ void dma_copy16(const uint8_t *base, uint32_t voff, u
                  : "memory", "m0", "scc");
 }
 
+// Same with 4 bytes per lane: lane l's dword lands at lds_base + LDS_IMM + 4 * l.
+template <int LDS_IMM>
+__device__ __forceinline__ void dma_copy4(const uint8_t *base, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_IMM)
+                 : "memory", "m0", "scc");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {

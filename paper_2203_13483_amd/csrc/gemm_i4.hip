@@ -256,6 +256,112 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
     });
 }
 
+// Epilogue with row-contiguous stores, for the 16-bit float outputs of the ring
+// kernel.  In the MFMA result layout a lane owns 8 consecutive channels of one token,
+// so a direct store instruction writes 32 rows x 32 bytes; here the finished values
+// go through a wave-private LDS area instead (rows of CW channels, 16-byte pieces
+// XOR-swizzled so that both the writes and the read-back are bank-conflict free) and
+// are stored as whole CW*2-byte row segments, 64 / (CW / 8) rows per instruction.
+// The per-channel scales and biases of the wave's WTN channels are copied to LDS
+// (sc_lds, wave-private, beyond the ring) while the tile's last k stage runs, so the
+// epilogue issues no global loads of its own: vector memory operations retire in
+// order, and a load issued here would first wait for every copy in flight.
+// scr: wave-private LDS, 32 * ROWB bytes, not in use by the ring.
+template <class Cfg>
+struct EpiShuffle {
+    static constexpr int REGION = Cfg::STAGE_BYTES / Cfg::WAVES;   // a wave's share of an idle ring slot
+    // per wave, beyond the ring: s_w then bias, each a whole number of 64-lane copies
+    static constexpr int NSL = (Cfg::WTN + 63) / 64;
+    static constexpr int BIAS_AT = NSL * 64;                       // in floats
+    static constexpr int SCALE_BYTES = 2 * BIAS_AT * 4;
+    static constexpr int EXTRA_LDS = Cfg::WAVES * SCALE_BYTES;
+    static constexpr int CW = (Cfg::WTN >= 64 && 32 * 128 <= REGION) ? 64 : (32 * 64 <= REGION) ? 32 : 0;
+    static constexpr bool usable = CW != 0 && Cfg::RB == 64 &&
+                                   (Cfg::LDS_BYTES + EXTRA_LDS) * Cfg::WGS_PER_CU <= 160 * 1024;
+    static constexpr int ROWB = CW * 2;     // bytes per staged row (16-bit values)
+    static constexpr int PPR = CW / 8;      // 16-byte pieces per row
+    // piece p of row r sits in slot p ^ key(r)
+    __device__ static __forceinline__ int key(int r) { return PPR == 8 ? (r & 7) : ((r >> 1) & 3); }
+};
+
+template <class Cfg, class Epi>
+__device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16i (&acc)[Cfg::TM][Cfg::TN],
+                                                      int m0, int n0, int wm, int wn, int lane, uint8_t *scr,
+                                                      float *sc_lds)
+{
+    using Sh = EpiShuffle<Cfg>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, WTN = Cfg::WTN;
+    constexpr int CW = Sh::CW, ROWB = Sh::ROWB, PPR = Sh::PPR;
+    constexpr int TPP = CW / 32;    // 32-channel MFMA tiles per pass
+    constexpr int NTH = WTN / CW;   // passes across the wave's channels
+    static_assert(Epi::out == MKQ_F16 || Epi::out == MKQ_BF16, "row epilogue is for 16-bit float outputs");
+    const int fr = lane & 31, fh = lane >> 5;
+    const int nw = n0 + wn * WTN;  // first channel of the wave
+
+    // sc_lds holds s_w then bias of the wave's WTN channels, copied there during the
+    // tile's last k stage.  Fold s_x * 2^-8 (exact) into the scales once; no bias -> zeros.
+#pragma unroll
+    for (int c = lane; c < WTN; c += 64) {
+        sc_lds[c] = (p.s_x * sc_lds[c]) * 0.00390625f;
+        if (!p.bias) sc_lds[Sh::BIAS_AT + c] = 0.0f;
+    }
+
+    static_for<NTH>([&](auto thc) {
+        constexpr int th = decltype(thc)::value;
+        static_for<TM>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            __builtin_amdgcn_sched_barrier(0);
+            const int mrow = m0 + wm * Cfg::WTM + j * 32;
+            static_for<TPP * 2>([&](auto uc) {
+                constexpr int tl = decltype(uc)::value / 2, G = decltype(uc)::value % 2;
+                constexpr int t = th * TPP + tl;
+                const int c0 = t * 32 + 16 * G + 8 * fh;  // first of the lane's 8 channels, wave-relative
+                const float4 s0 = *reinterpret_cast<const float4 *>(sc_lds + c0);
+                const float4 s1 = *reinterpret_cast<const float4 *>(sc_lds + c0 + 4);
+                const float4 b0 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0);
+                const float4 b1 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0 + 4);
+                const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+                const float bi[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+                float y[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    y[e] = __fmaf_rn((float)acc[j][t][8 * G + e], sc[e], bi[e]);
+                    asm volatile("" : "+v"(y[e]));  // keep the binary32 rounding (no fused narrowing)
+                }
+                if (Epi::res16) {
+                    const int m = mrow + fr, n = nw + c0;
+                    if (m < p.M && n < p.N) {
+                        const uint4 rr = *reinterpret_cast<const uint4 *>((const uint16_t *)p.residual +
+                                                                          (int64_t)m * p.N + n);
+                        const uint32_t rwd[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            y[2 * e] += half_bits_to_float((uint16_t)(rwd[e] & 0xFFFFu));
+                            y[2 * e + 1] += half_bits_to_float((uint16_t)(rwd[e] >> 16));
+                        }
+                    }
+                }
+                uint32_t h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    h[e] = (Epi::out == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1]) : pack2_bf16(y[2 * e], y[2 * e + 1]);
+                constexpr int piece = tl * 4 + 2 * G;  // + fh
+                *reinterpret_cast<uint4 *>(scr + fr * ROWB + (((piece + fh) ^ Sh::key(fr)) * 16)) =
+                    make_uint4(h[0], h[1], h[2], h[3]);
+            });
+            // read back whole rows and store them
+#pragma unroll
+            for (int i = 0; i < (32 * PPR) / 64; ++i) {
+                const int r = lane / PPR + (64 / PPR) * i, pc = lane % PPR;
+                const uint4 v = *reinterpret_cast<const uint4 *>(scr + r * ROWB + ((pc ^ Sh::key(r)) * 16));
+                const int m = mrow + r, n = nw + th * CW + pc * 8;
+                if (m < p.M && n < p.N)
+                    *reinterpret_cast<uint4 *>((uint16_t *)p.out + (int64_t)m * p.N + n) = v;
+            }
+        });
+    });
+}
+
 template <class Cfg, bool FULL_STAGES>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_kernel(const GemmI4Params p)
 {
@@ -483,7 +589,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
     const int fr = lane & 31, fh = lane >> 5;
 #ifdef MKQ_TRACE
-    unsigned long long *tr = (unsigned long long *)(smem + Cfg::LDS_BYTES);
+    unsigned long long *tr = (unsigned long long *)(smem + Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS);
     int tri = 0;
     const bool tron = (tid == 0);
     MKQ_TRW(6);
@@ -670,6 +776,9 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     // those stores, so the stores may stay outstanding if the wait allows for their
     // exact number; that number is only known at compile time for interior tiles of the
     // fixed epilogues.
+    // (the row epilogue issues the same number of 16-byte-per-lane stores as the direct one,
+    // and with a 16-bit residual its loads are all older than its first store only for the
+    // direct path, so that variant waits for everything)
     constexpr int STORES_PER_UNIT = Epi::generic ? 0 : (Epi::out == MKQ_F32 ? 2 : 1);
     constexpr int EPI_STORES = TN * 2 * TM * STORES_PER_UNIT;
     constexpr bool ASYNC_STORES = !Epi::generic && ((INFLIGHT - 1) * LPW + EPI_STORES <= 63);
@@ -693,9 +802,35 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     };
     auto next_slot = [&](int b) { return (b + 1 == S) ? 0 : b + 1; };
 
+    constexpr bool ROWS_EPI = !Epi::generic && (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16) &&
+                              EpiShuffle<Cfg>::usable;
+    float *const sc_lds = reinterpret_cast<float *>(smem + Cfg::LDS_BYTES + wave * EpiShuffle<Cfg>::SCALE_BYTES);
+    // copies s_w / bias of this wave's channels of tile `tile` to sc_lds
+    auto stage_scales = [&](int tile) {
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, tm, tn);
+        const uint32_t dst = lds0 + Cfg::LDS_BYTES + wave * EpiShuffle<Cfg>::SCALE_BYTES;
+        static_for<EpiShuffle<Cfg>::NSL>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            int n = tn * BN + wn * Cfg::WTN + 64 * i + lane;
+            n = n < p.N ? n : p.N - 1;
+            dma_copy4<256 * i>(reinterpret_cast<const uint8_t *>(p.s_w), (uint32_t)n * 4u, dst);
+            if (p.bias)
+                dma_copy4<EpiShuffle<Cfg>::BIAS_AT * 4 + 256 * i>(reinterpret_cast<const uint8_t *>(p.bias),
+                                                                  (uint32_t)n * 4u, dst);
+        });
+    };
+
+    // The copies are issued INFLIGHT stages before the tile ends (or at its first stage):
+    // by the epilogue every vector memory operation still in flight is then younger.
+    const int scale_stage = kt_count > INFLIGHT ? kt_count - INFLIGHT : 0;
+
     int ct = blockIdx.x, ck = 0;  // compute cursor
     int buf = 0;                  // ring slot of the stage being computed
     for (int s = 0; s < steps; s += 3 - ROUNDS) {
+        if constexpr (ROWS_EPI) {
+            if (ck == scale_stage) stage_scales(ct);
+        }
         if constexpr (ROUNDS == 2) {
             // one 128-code stage: round 1 is fetched from the same stage, then the boundary,
             // then round 0 of the next stage while the slot of the previous one is refilled
@@ -733,7 +868,20 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
 #ifdef MKQ_ABL_NOEPI
             if (p.M < 0)
 #endif
-            gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
+            if constexpr (ROWS_EPI) {
+                // the slot of the stage just finished is idle until every wave has passed
+                // the next stage boundary: each wave shuffles through its share of it
+                const int done_slot = (buf == 0) ? S - 1 : buf - 1;
+                // the scale / bias copies have landed: only the stage copies issued after
+                // them (INFLIGHT stages, or one per stage of a shorter tile) may be in flight
+                if (kt_count >= INFLIGHT) wait_vmcnt<INFLIGHT * LPW>();
+                else wait_vmcnt<LPW>();
+                gemm_i4_epilogue_rows<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, lane,
+                                                smem + done_slot * Cfg::STAGE_BYTES +
+                                                    wave * EpiShuffle<Cfg>::REGION, sc_lds);
+            } else {
+                gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
+            }
             const bool interior = (tile_m + 1) * BM <= p.M && (tile_n + 1) * BN <= p.N;
             stores_pending = (ASYNC_STORES && interior) ? INFLIGHT : 0;
 #pragma unroll
@@ -803,11 +951,14 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    constexpr bool rows_epi = !Epi::generic && (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16) &&
+                              EpiShuffle<Cfg>::usable;
+    constexpr size_t lds_kernel = Cfg::LDS_BYTES + (rows_epi ? EpiShuffle<Cfg>::EXTRA_LDS : 0);
 #ifdef MKQ_TRACE
-    const size_t lds = Cfg::LDS_BYTES + 4096;
+    const size_t lds = lds_kernel + 4096;
     const_cast<GemmI4Params &>(p).dbg = g_trace_buf;
 #else
-    const size_t lds = Cfg::LDS_BYTES;
+    const size_t lds = lds_kernel;
 #endif
     static int wgs_per_cu = 0;  // per instantiation
     if (wgs_per_cu == 0) {
@@ -897,9 +1048,6 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     case 18: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
     case 19: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 256, 2, 2, 64, 3>>(p, epi, st);
     case 20: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 32, 6>>(p, epi, st);
-    case 21: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 256, 2, 2, 32, 6>>(p, epi, st);
-    case 22: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 32, 8>>(p, epi, st);
-    case 23: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 256, 2, 2, 64, 4>>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }
