@@ -906,6 +906,142 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
 #endif
 }
 
+// ---------------------------------------------------------------------------------
+// Few tokens (M <= 128): the linear is a stream of the weight matrix, bound by HBM.
+// One workgroup of 8 waves owns 32 output channels; the waves split K between them,
+// each fetching its packed fragments straight from global memory into registers (no
+// reuse between waves, so no LDS staging) with every load of its slice in flight at
+// once, and the partial accumulators meet in LDS.  The activations ([M, K/2] bytes,
+// resident in L2) are read the same way.  Waves 0 .. TB-1 then each sum one 32-token
+// block over the 8 partials and run the generic epilogue on it.
+struct SkinnyCfg {
+    static constexpr int BM = 32, BN = 32, WGM = 1, WGN = 1, RB = 64;
+    static constexpr int THREADS = 512, WAVES = 8;
+    static constexpr int WTM = 32, WTN = 32, TM = 1, TN = 1;
+};
+
+template <int TB, int UG>
+__global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(const GemmI4Params p)
+{
+    __shared__ __attribute__((aligned(16))) int red[2][SkinnyCfg::WAVES][4][64][4];  // 64 KiB
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int fr = lane & 31, fh = lane >> 5;
+    const int n0 = blockIdx.x * 32;
+    const int row_bytes = p.K / 2;
+    // A row is cut into groups of 128 bytes (256 codes), one cache line; a lane fetches
+    // 64 contiguous bytes of its row per group (four 16-byte loads = eight k steps), so the
+    // four loads of a group touch the same 32 lines.  Which codes a lane holds does not
+    // matter to the dot product as long as weights and activations agree.
+    const int groups = row_bytes / 128;
+    const int gpw = (groups + SkinnyCfg::WAVES - 1) / SkinnyCfg::WAVES;
+    const int g_begin = wave * gpw;
+    const int g_end = (g_begin + gpw) < groups ? (g_begin + gpw) : groups;
+
+    int wrow = n0 + w_row_perm(fr);
+    wrow = wrow < p.N ? wrow : p.N - 1;  // rows past the edge are never stored
+    const uint8_t *wp = p.W + (size_t)wrow * row_bytes + fh * 64;
+    const uint8_t *ap[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        int tok = tb * 32 + fr;
+        tok = tok < p.M ? tok : p.M - 1;
+        ap[tb] = p.A + (size_t)tok * row_bytes + fh * 64;
+    }
+
+    v16i acc[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[tb][v] = 0;
+
+    // chunks of UG groups, the next chunk's loads in flight while this one is multiplied
+    constexpr int NL = 4 * UG;  // 16-byte loads per chunk per operand row
+    uint4 fw[2][NL], fa[2][TB][NL];
+    auto fetch = [&](int buf, int g0) {
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            int g = g0 + u / 4;
+            g = g < g_end ? g : g_end - 1;  // tail: fetched again, not used
+            g = g < 0 ? 0 : g;
+            const int off = g * 128 + (u % 4) * 16;
+            fw[buf][u] = *reinterpret_cast<const uint4 *>(wp + off);
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) fa[buf][tb][u] = *reinterpret_cast<const uint4 *>(ap[tb] + off);
+        }
+    };
+    auto multiply = [&](int buf, int g0) {
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            if (g0 + u / 4 < g_end) {
+                const v4i w0 = widen(fw[buf][u].x, fw[buf][u].y), w1 = widen(fw[buf][u].z, fw[buf][u].w);
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) {
+                    acc[tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w0, widen(fa[buf][tb][u].x, fa[buf][tb][u].y), acc[tb], 0, 0, 0);
+                    acc[tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, widen(fa[buf][tb][u].z, fa[buf][tb][u].w), acc[tb], 0, 0, 0);
+                }
+            }
+        }
+    };
+    if (g_begin < g_end) {
+        fetch(0, g_begin);
+        for (int g0 = g_begin; g0 < g_end; g0 += 2 * UG) {
+            if (g0 + UG < g_end) fetch(1, g0 + UG);
+            multiply(0, g0);
+            if (g0 + 2 * UG < g_end) fetch(0, g0 + 2 * UG);
+            if (g0 + UG < g_end) multiply(1, g0 + UG);
+        }
+    }
+
+    // reduce over the 8 waves, two token blocks per pass through LDS
+#pragma unroll
+    for (int pass = 0; pass < (TB + 1) / 2; ++pass) {
+        if (pass) __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int tb = 2 * pass + h;
+            if (tb < TB) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<int4 *>(&red[h][wave][q][lane][0]) =
+                        make_int4(acc[tb][4 * q], acc[tb][4 * q + 1], acc[tb][4 * q + 2], acc[tb][4 * q + 3]);
+            }
+        }
+        __syncthreads();
+        if (wave < 2 && 2 * pass + wave < TB) {
+            v16i sum[1][1];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum[0][0][v] = 0;
+#pragma unroll
+            for (int w = 0; w < SkinnyCfg::WAVES; ++w)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int4 t = *reinterpret_cast<const int4 *>(&red[wave][w][q][lane][0]);
+                    sum[0][0][4 * q] += t.x; sum[0][0][4 * q + 1] += t.y;
+                    sum[0][0][4 * q + 2] += t.z; sum[0][0][4 * q + 3] += t.w;
+                }
+            gemm_i4_epilogue<SkinnyCfg, EpiGeneric>(p, sum, (2 * pass + wave) * 32, n0, 0, 0, fr, fh);
+        }
+    }
+}
+
+template <int TB, int UG>
+static int launch_skinny(const GemmI4Params &p, hipStream_t st)
+{
+    gemm_i4_skinny_kernel<TB, UG><<<(unsigned)ceil_div(p.N, 32), SkinnyCfg::THREADS, 0, st>>>(p);
+    return launch_status();
+}
+
+static int run_gemm_i4_skinny(const GemmI4Params &p, hipStream_t st)
+{
+    if (p.M <= 32) return launch_skinny<1, 2>(p, st);
+    if (p.M <= 64) return launch_skinny<2, 2>(p, st);
+    if (p.M <= 96) return launch_skinny<3, 1>(p, st);
+    return launch_skinny<4, 1>(p, st);
+}
+
 static int g_num_cus = 0;
 
 template <class Cfg, bool FULL>
@@ -1027,6 +1163,8 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     int cfg = g_forced_cfg;
     const bool dma_ok = (p.K % 128) == 0;  // whole 64-byte stages
     const int epi = classify_epilogue(p);
+    if (cfg < 0 && p.M <= 64 && (p.K % 256) == 0) return run_gemm_i4_skinny(p, st);
+    if (cfg == 30) return (p.M <= 128 && (p.K % 256) == 0) ? run_gemm_i4_skinny(p, st) : MKQ_ERR_UNSUPPORTED;
     if (cfg < 0) {
         if (!dma_ok) {
             cfg = 3;
@@ -1034,7 +1172,9 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
             const int64_t t256 = ceil_div(p.M, 256) * ceil_div(p.N, 256);
             const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
             (void)t256;
-            if (t128 >= 256) cfg = 12;
+            const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
+            if (t256x128 >= 512) cfg = 18;       // two resident workgroups per CU have a tile each
+            else if (t128 >= 256) cfg = 12;
             else cfg = 14;
         }
     }

@@ -197,3 +197,19 @@ def test_persistent_pipeline_over_many_tiles(mkq, cfg, out_name):
             assert np.array_equal(to_np(r["out"]), oracle.pack_nibbles(ref["q"]))
     finally:
         mkq.debug_set_gemm_config(-1)
+
+
+@pytest.mark.parametrize("M", [1, 16, 33, 64, 100, 128])
+@pytest.mark.parametrize("N,K", [(200, 256), (40, 512), (768, 768), (328, 4096), (96, 2304)])
+def test_few_token_streaming_path(mkq, M, N, K):
+    """M <= 128 takes the weight-streaming kernel (K split over 8 waves, reduced in LDS)."""
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M * 7 + N)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.F16, s_next=0.8)
+    mkq.debug_set_gemm_config(30)
+    try:
+        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, want_acc=True, want_q=True, s_next=0.8)
+    finally:
+        mkq.debug_set_gemm_config(-1)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"]))
