@@ -123,11 +123,7 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
             if (nb >= p.N) return;
             const int nvalid = (p.N - nb) < 8 ? (p.N - nb) : 8;
             float sc[8], bi[8];
-#ifdef MKQ_ABL_NOSWLOAD
-            if (p.M < 0) {
-#else
             if (vec_ok) {
-#endif
                 const float4 s0 = *reinterpret_cast<const float4 *>(p.s_w + nb);
                 const float4 s1 = *reinterpret_cast<const float4 *>(p.s_w + nb + 4);
                 sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w;
@@ -142,16 +138,12 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                     for (int e = 0; e < 8; ++e) bi[e] = 0.0f;
                 }
             } else {
-#ifdef MKQ_ABL_NOSWLOAD
-                for (int e = 0; e < 8; ++e) { sc[e] = 0.5f; bi[e] = 0.25f; }
-#else
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int n = (e < nvalid) ? nb + e : nb;
                     sc[e] = p.s_w[n];
                     bi[e] = p.bias ? p.bias[n] : 0.0f;
                 }
-#endif
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) sc[e] = (p.s_x * sc[e]) * 0.00390625f;  // * 2^-8, exact
@@ -230,9 +222,6 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                                                       : pack2_bf16(y[2 * e], y[2 * e + 1]);
                     uint16_t *dst = (uint16_t *)p.out + o;
                     if (vec_ok) {
-#ifdef MKQ_ABL_NOSTORE
-                        if (h[0] == 0x12345678u && h[1] == 0x9abcdef0u && h[2] == 0x0fedcba9u)
-#endif
                         *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
                     } else {
                         for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(h[e >> 1] >> (16 * (e & 1)));
@@ -256,17 +245,20 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
     });
 }
 
-// Epilogue with row-contiguous stores, for the 16-bit float outputs of the ring
-// kernel.  In the MFMA result layout a lane owns 8 consecutive channels of one token,
-// so a direct store instruction writes 32 rows x 32 bytes; here the finished values
-// go through a wave-private LDS area instead (rows of CW channels, 16-byte pieces
-// XOR-swizzled so that both the writes and the read-back are bank-conflict free) and
-// are stored as whole CW*2-byte row segments, 64 / (CW / 8) rows per instruction.
-// The per-channel scales and biases of the wave's WTN channels are copied to LDS
-// (sc_lds, wave-private, beyond the ring) while the tile's last k stage runs, so the
-// epilogue issues no global loads of its own: vector memory operations retire in
-// order, and a load issued here would first wait for every copy in flight.
-// scr: wave-private LDS, 32 * ROWB bytes, not in use by the ring.
+// Epilogue of the ring kernel through LDS, for the compile-time epilogues.  In the MFMA
+// result layout a lane owns 8 consecutive channels of one token, so a direct store
+// instruction writes 32 rows x 32 bytes and every lane needs the scales of its own
+// channels for each 8-value unit.  Here a wave instead drops one 32-token x 32-channel
+// accumulator tile at a time, as raw int32, into a wave-private LDS area (rows of 128
+// bytes, 16-byte pieces XOR-swizzled so that writes and reads are bank-conflict free)
+// and reads it back transposed: lane l then owns channels 8*(l%4) .. +7 of rows l/4
+// and l/4 + 16, i.e. the same 8 channels for the whole pass, dequantizes (and adds the
+// residual, applies GELU, re-quantizes) and stores 16 rows x 64 contiguous bytes per
+// instruction (128 for binary32, 16 for codes).  The per-channel scales and biases of
+// the wave's WTN channels are copied to LDS (sc_lds, wave-private, beyond the ring)
+// while the tile's last k stages run, so the epilogue issues no global loads that
+// would have to wait, in order, behind every copy in flight.
+// scr: wave-private LDS, 4 KiB, not in use by the ring.
 template <class Cfg>
 struct EpiShuffle {
     static constexpr int REGION = Cfg::STAGE_BYTES / Cfg::WAVES;   // a wave's share of an idle ring slot
@@ -275,13 +267,8 @@ struct EpiShuffle {
     static constexpr int BIAS_AT = NSL * 64;                       // in floats
     static constexpr int SCALE_BYTES = 2 * BIAS_AT * 4;
     static constexpr int EXTRA_LDS = Cfg::WAVES * SCALE_BYTES;
-    static constexpr int CW = (Cfg::WTN >= 64 && 32 * 128 <= REGION) ? 64 : (32 * 64 <= REGION) ? 32 : 0;
-    static constexpr bool usable = CW != 0 && Cfg::RB == 64 &&
+    static constexpr bool usable = REGION >= 4096 && Cfg::RB == 64 &&
                                    (Cfg::LDS_BYTES + EXTRA_LDS) * Cfg::WGS_PER_CU <= 160 * 1024;
-    static constexpr int ROWB = CW * 2;     // bytes per staged row (16-bit values)
-    static constexpr int PPR = CW / 8;      // 16-byte pieces per row
-    // piece p of row r sits in slot p ^ key(r)
-    __device__ static __forceinline__ int key(int r) { return PPR == 8 ? (r & 7) : ((r >> 1) & 3); }
 };
 
 template <class Cfg, class Epi>
@@ -291,72 +278,112 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
 {
     using Sh = EpiShuffle<Cfg>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, WTN = Cfg::WTN;
-    constexpr int CW = Sh::CW, ROWB = Sh::ROWB, PPR = Sh::PPR;
-    constexpr int TPP = CW / 32;    // 32-channel MFMA tiles per pass
-    constexpr int NTH = WTN / CW;   // passes across the wave's channels
-    static_assert(Epi::out == MKQ_F16 || Epi::out == MKQ_BF16, "row epilogue is for 16-bit float outputs");
     const int fr = lane & 31, fh = lane >> 5;
-    const int nw = n0 + wn * WTN;  // first channel of the wave
+    const int nw = n0 + wn * WTN;      // first channel of the wave
+    const int rrow = lane >> 2;        // reader: rows rrow and rrow + 16
+    const int pc = lane & 3;           // reader: channels 8 * pc .. + 7 of the 32-channel tile
 
-    // sc_lds holds s_w then bias of the wave's WTN channels, copied there during the
-    // tile's last k stage.  Fold s_x * 2^-8 (exact) into the scales once; no bias -> zeros.
+    // sc_lds holds s_w then bias of the wave's WTN channels.  Fold s_x * 2^-8 (exact) into
+    // the scales once; no bias -> zeros.
 #pragma unroll
     for (int c = lane; c < WTN; c += 64) {
         sc_lds[c] = (p.s_x * sc_lds[c]) * 0.00390625f;
         if (!p.bias) sc_lds[Sh::BIAS_AT + c] = 0.0f;
     }
+    // writer: the lane's 8 values of unit G are pieces 4G + 2fh, 4G + 2fh + 1 of row fr
+    const int wr_base = fr * 128;
+    const int wr_key = fr & 7;
+    // reader: pieces 2pc, 2pc + 1 of its two rows
+    int rd_off[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = rrow + 16 * i;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) rd_off[i][h] = r * 128 + (((2 * pc + h) ^ (r & 7)) * 16);
+    }
 
-    static_for<NTH>([&](auto thc) {
-        constexpr int th = decltype(thc)::value;
+    static_for<TN>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        const int c0 = t * 32 + 8 * pc;  // first of the reader lane's channels, wave-relative
+        const int n = nw + c0;
+        const float4 s0 = *reinterpret_cast<const float4 *>(sc_lds + c0);
+        const float4 s1 = *reinterpret_cast<const float4 *>(sc_lds + c0 + 4);
+        const float4 b0 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0);
+        const float4 b1 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0 + 4);
+        const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        const float bi[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
         static_for<TM>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             __builtin_amdgcn_sched_barrier(0);
-            const int mrow = m0 + wm * Cfg::WTM + j * 32;
-            static_for<TPP * 2>([&](auto uc) {
-                constexpr int tl = decltype(uc)::value / 2, G = decltype(uc)::value % 2;
-                constexpr int t = th * TPP + tl;
-                const int c0 = t * 32 + 16 * G + 8 * fh;  // first of the lane's 8 channels, wave-relative
-                const float4 s0 = *reinterpret_cast<const float4 *>(sc_lds + c0);
-                const float4 s1 = *reinterpret_cast<const float4 *>(sc_lds + c0 + 4);
-                const float4 b0 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0);
-                const float4 b1 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0 + 4);
-                const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-                const float bi[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+            // write the raw tile
+#pragma unroll
+            for (int G = 0; G < 2; ++G)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    *reinterpret_cast<int4 *>(scr + wr_base + (((4 * G + 2 * fh + h) ^ wr_key) * 16)) =
+                        make_int4(acc[j][t][8 * G + 4 * h], acc[j][t][8 * G + 4 * h + 1],
+                                  acc[j][t][8 * G + 4 * h + 2], acc[j][t][8 * G + 4 * h + 3]);
+            // read it back row-wise
+            int4 raw[2][2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) raw[i][h] = *reinterpret_cast<const int4 *>(scr + rd_off[i][h]);
+            const int mbase = m0 + wm * Cfg::WTM + j * 32 + rrow;
+            uint4 res[2];
+            if (Epi::res16) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int m = mbase + 16 * i;
+                    res[i] = (m < p.M && n < p.N)
+                                 ? *reinterpret_cast<const uint4 *>((const uint16_t *)p.residual + (int64_t)m * p.N + n)
+                                 : make_uint4(0, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int a[8] = {raw[i][0].x, raw[i][0].y, raw[i][0].z, raw[i][0].w,
+                                  raw[i][1].x, raw[i][1].y, raw[i][1].z, raw[i][1].w};
                 float y[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    y[e] = __fmaf_rn((float)acc[j][t][8 * G + e], sc[e], bi[e]);
+                    y[e] = __fmaf_rn((float)a[e], sc[e], bi[e]);
                     asm volatile("" : "+v"(y[e]));  // keep the binary32 rounding (no fused narrowing)
                 }
                 if (Epi::res16) {
-                    const int m = mrow + fr, n = nw + c0;
-                    if (m < p.M && n < p.N) {
-                        const uint4 rr = *reinterpret_cast<const uint4 *>((const uint16_t *)p.residual +
-                                                                          (int64_t)m * p.N + n);
-                        const uint32_t rwd[4] = {rr.x, rr.y, rr.z, rr.w};
+                    const uint32_t rwd[4] = {res[i].x, res[i].y, res[i].z, res[i].w};
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            y[2 * e] += half_bits_to_float((uint16_t)(rwd[e] & 0xFFFFu));
-                            y[2 * e + 1] += half_bits_to_float((uint16_t)(rwd[e] >> 16));
-                        }
+                    for (int e = 0; e < 4; ++e) {
+                        y[2 * e] += half_bits_to_float((uint16_t)(rwd[e] & 0xFFFFu));
+                        y[2 * e + 1] += half_bits_to_float((uint16_t)(rwd[e] >> 16));
                     }
                 }
-                uint32_t h[4];
+                if (Epi::gelu) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    h[e] = (Epi::out == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1]) : pack2_bf16(y[2 * e], y[2 * e + 1]);
-                constexpr int piece = tl * 4 + 2 * G;  // + fh
-                *reinterpret_cast<uint4 *>(scr + fr * ROWB + (((piece + fh) ^ Sh::key(fr)) * 16)) =
-                    make_uint4(h[0], h[1], h[2], h[3]);
-            });
-            // read back whole rows and store them
+                    for (int e = 0; e < 8; ++e) y[e] = gelu_erf(y[e]);
+                }
+                const int m = mbase + 16 * i;
+                const bool ok = m < p.M && n < p.N;  // N % 8 == 0: a lane's 8 channels are all in or all out
+                const int64_t o = (int64_t)m * p.N + n;
+                if (Epi::out == MKQ_F32) {
+                    if (ok) {
+                        float *dst = (float *)p.out + o;
+                        *reinterpret_cast<float4 *>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(y[4], y[5], y[6], y[7]);
+                    }
+                } else if (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16) {
+                    uint32_t hw[4];
 #pragma unroll
-            for (int i = 0; i < (32 * PPR) / 64; ++i) {
-                const int r = lane / PPR + (64 / PPR) * i, pc = lane % PPR;
-                const uint4 v = *reinterpret_cast<const uint4 *>(scr + r * ROWB + ((pc ^ Sh::key(r)) * 16));
-                const int m = mrow + r, n = nw + th * CW + pc * 8;
-                if (m < p.M && n < p.N)
-                    *reinterpret_cast<uint4 *>((uint16_t *)p.out + (int64_t)m * p.N + n) = v;
+                    for (int e = 0; e < 4; ++e)
+                        hw[e] = (Epi::out == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1]) : pack2_bf16(y[2 * e], y[2 * e + 1]);
+                    if (ok) *reinterpret_cast<uint4 *>((uint16_t *)p.out + o) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                } else {
+                    uint32_t packed = 0;  // Eq. 1 on the binary32 value
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        packed |= ((uint32_t)quantize_code(y[e], p.s_next) & 0xFu) << (4 * e);
+                    if (ok) *reinterpret_cast<uint32_t *>((uint8_t *)p.out + (o >> 1)) = packed;
+                }
             }
         });
     });
@@ -727,7 +754,6 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
                 acc[j][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wid[cb][t], wid[cb][TN + j], acc[j][t], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-#ifndef MKQ_ABL_NOLDS
             if constexpr (READ) {
                 constexpr int f0 = i * NF / NMFMA, f1 = (i + 1) * NF / NMFMA;
                 static_for<f1 - f0>([&](auto fc) {
@@ -735,14 +761,10 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
                     read_frag(rd_off, IntC<f>{}, IntC<RR>{}, raw[RDST][f]);
                 });
             }
-#endif
-#ifndef MKQ_ABL_NODMA
             if constexpr (COPY) {
                 constexpr int q0 = i * LPW / NMFMA, q1 = (i + 1) * LPW / NMFMA;
                 static_for<q1 - q0>([&](auto qc) { copy_one(cslot, IntC<q0 + decltype(qc)::value>{}); });
             }
-#endif
-#ifndef MKQ_ABL_NOWIDEN
             constexpr int m0 = i * 4 * NF / NMFMA, m1 = (i + 1) * 4 * NF / NMFMA;
             static_for<m1 - m0>([&](auto mc) {
                 constexpr int m = m0 + decltype(mc)::value;
@@ -752,7 +774,6 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
                 asm volatile("" : "+v"(w));
                 wid[nb][m / 4][m % 4] = w;
             });
-#endif
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -795,15 +816,12 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
             wait_vmcnt<(INFLIGHT - 1) * LPW>();
         }
         MKQ_TR(2);
-#ifndef MKQ_ABL_NOBAR
         lds_barrier();
-#endif
         MKQ_TR(3);
     };
     auto next_slot = [&](int b) { return (b + 1 == S) ? 0 : b + 1; };
 
-    constexpr bool ROWS_EPI = !Epi::generic && (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16) &&
-                              EpiShuffle<Cfg>::usable;
+    constexpr bool ROWS_EPI = !Epi::generic && EpiShuffle<Cfg>::usable;
     float *const sc_lds = reinterpret_cast<float *>(smem + Cfg::LDS_BYTES + wave * EpiShuffle<Cfg>::SCALE_BYTES);
     // copies s_w / bias of this wave's channels of tile `tile` to sc_lds
     auto stage_scales = [&](int tile) {
@@ -865,9 +883,6 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
             int tile_m, tile_n;
             tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
             MKQ_TR(4);
-#ifdef MKQ_ABL_NOEPI
-            if (p.M < 0)
-#endif
             if constexpr (ROWS_EPI) {
                 // the slot of the stage just finished is idle until every wave has passed
                 // the next stage boundary: each wave shuffles through its share of it
@@ -1087,8 +1102,7 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
-    constexpr bool rows_epi = !Epi::generic && (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16) &&
-                              EpiShuffle<Cfg>::usable;
+    constexpr bool rows_epi = !Epi::generic && EpiShuffle<Cfg>::usable;
     constexpr size_t lds_kernel = Cfg::LDS_BYTES + (rows_epi ? EpiShuffle<Cfg>::EXTRA_LDS : 0);
 #ifdef MKQ_TRACE
     const size_t lds = lds_kernel + 4096;
