@@ -38,6 +38,20 @@ def parse():
     return ap.parse_args()
 
 
+def graph_time(fn, rep=20, repeats=7, inner=5):
+    """Median seconds per call of fn(): a HIP graph of `rep` back-to-back calls, replayed
+    `inner` times per sample, `repeats` samples (clocks settle during the first ones)."""
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(rep):
+            fn()
+    ts = sorted(event_time(g.replay, inner, warm=2) / rep for _ in range(repeats))
+    return ts[len(ts) // 2]
+
+
 def event_time(fn, iters, warm=3):
     """Average seconds per call of fn(), HIP events on the current stream."""
     import torch
@@ -204,7 +218,7 @@ def main():
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(line.split(":")[1])
     roofline = {
-        "bound": "mfma", "kernel": "gemm_i4_dma_kernel (64x64 tiles, binary16-out epilogue)",
+        "bound": "mfma", "kernel": "gemm_i4_dma_kernel (64x64 / 128x128 tiles chosen per shape, binary16-out epilogue)",
         "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS,
         "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
         "algorithmic_bytes_per_launch": sum(c.gemm_bytes for c in cases) / len(cases),
@@ -245,38 +259,39 @@ def side_measurements(mkq, event_time):
         w = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
         sw = torch.rand(N, device="cuda") * 0.049 + 0.001
         out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-        t = event_time(lambda: mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_BF16, out=out), 30)
+        t = graph_time(lambda: mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_BF16, out=out))
         tops = 2.0 * M * N * K / t / 1e12
         res["large_m"].append({"M": M, "K": K, "N": N, "out": "bf16", "us": t * 1e6, "TOPS": tops,
-                               "frac_int8_peak": tops / INT8_MFMA_PEAK_TOPS})
+                               "frac_int8_peak": tops / INT8_MFMA_PEAK_TOPS,
+                               "protocol": "HIP graph of 20 back-to-back launches, median of 7 samples"})
         del a, w, out
 
     # small M: every call reads a different weight matrix from a pool larger than the
     # 256 MB last-level cache, so the weights always come from HBM
-    K = N = 4096
-    pool = 80  # x 8 MiB of packed weights = 640 MiB
-    ws = [torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda") for _ in range(pool)]
-    sw = torch.rand(N, device="cuda") * 0.049 + 0.001
-    for M in (16, 128, 512):
-        a = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
-        out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    for (K, N, pool, Ms) in ((4096, 4096, 80, (1, 16, 64, 128, 512)), (8192, 8192, 24, (16, 64))):
+        ws = [torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda") for _ in range(pool)]
+        sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+        for M in Ms:
+            a = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
 
-        def sweep():
-            for w in ws:
-                mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_F16, out=out)
+            def sweep():
+                for w in ws:
+                    mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_F16, out=out)
 
-        sweep()
-        torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
             sweep()
-        t = event_time(g.replay, 10) / pool
-        nbytes = M * K / 2 + N * K / 2 + 8 * N + 2 * M * N
-        res["small_m"].append({"M": M, "K": K, "N": N, "out": "f16", "us_per_call": t * 1e6,
-                               "GBps": nbytes / t / 1e9, "frac_hbm_peak": nbytes / t / 1e9 / HBM_PEAK_GBS,
-                               "protocol": f"HIP graph of {pool} back-to-back calls, one distinct 8 MiB weight each"})
-        del a, out, g
-    del ws
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                sweep()
+            t = sorted(event_time(g.replay, 5, warm=1) for _ in range(5))[2] / pool
+            nbytes = M * K / 2 + N * K / 2 + 8 * N + 2 * M * N
+            res["small_m"].append({"M": M, "K": K, "N": N, "out": "f16", "us_per_call": t * 1e6,
+                                   "GBps": nbytes / t / 1e9, "frac_hbm_peak": nbytes / t / 1e9 / HBM_PEAK_GBS,
+                                   "protocol": f"HIP graph of {pool} back-to-back calls on one stream, one distinct "
+                                               f"{N * K // 2 >> 20} MiB weight each"})
+            del a, out, g
+        del ws
 
     # 12-layer BERT-base encoder, batch 32 x seq 128 (M = 4096), int4 vs binary16 layers
     try:

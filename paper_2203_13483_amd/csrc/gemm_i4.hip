@@ -1188,8 +1188,8 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
             (void)t256;
             const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
             if (t256x128 >= 512) cfg = 18;       // two resident workgroups per CU have a tile each
-            else if (t128 >= 256) cfg = 12;
-            else cfg = 14;
+            else if (t128 >= 128) cfg = 12;      // half the CUs busy with 64x64-per-wave tiles beats
+            else cfg = 14;                       // all of them with 32x32-per-wave ones
         }
     }
     if (cfg >= 10 && !dma_ok) return MKQ_ERR_UNSUPPORTED;
