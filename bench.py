@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the large-M / small-M side measurements")
+    ap.add_argument("--only", choices=["large-m", "small-m"], default=None,
+                    help="run only that group of side measurements, eagerly and a few launches each (the form "
+                         "that rocprofv3 --kernel-trace / --pmc runs are taken of); prints their JSON")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one 256 MiB device-to-device copy kernel, so that a rocprofv3 --pmc run "
                          "of this command holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -154,6 +157,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.only:
+        print(json.dumps(profile_launches(mkq, args.only)))
+        return
+
     cfg = wl.CONFIGS[1]
     M = cfg["M"]
     rng = np.random.default_rng(cfg["seed"])
@@ -248,13 +255,49 @@ def main():
     print(json.dumps(out))
 
 
+LARGE_M_SHAPES = [(16384, 1024, 4096), (16384, 4096, 1024), (16384, 768, 3072), (65536, 1024, 4096)]
+
+
+def profile_launches(mkq, which, launches=5):
+    """A few eager launches of each large-M GEMM (bf16 out) or of the small-M weight-streaming
+    linears (cold weights), for profiler runs; returns what was launched."""
+    import torch
+    done = []
+    if which == "large-m":
+        for (M, K, N) in LARGE_M_SHAPES:
+            a = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
+            w = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
+            sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+            out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+            for _ in range(launches):
+                mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_BF16, out=out)
+            torch.cuda.synchronize()
+            done.append({"M": M, "K": K, "N": N, "launches": launches, "ops_per_launch": 2.0 * M * N * K,
+                         "grid_threads": None})
+            del a, w, out
+    else:
+        for (K, N) in ((4096, 4096), (8192, 8192)):
+            ws = [torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda") for _ in range(24)]
+            sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+            for M in (1, 16, 64):
+                a = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
+                out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+                for w in ws:
+                    mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_F16, out=out)
+                torch.cuda.synchronize()
+                done.append({"M": M, "K": K, "N": N, "launches": len(ws),
+                             "bytes_per_launch": M * K / 2 + N * K / 2 + 8 * N + 2 * M * N})
+            del ws
+    return {"only": which, "launched": done}
+
+
 def side_measurements(mkq, event_time):
     """Points beside the headline: large-M (MFMA-bound) GEMMs, small-M weight streaming
     (HBM-bound, cold weights), and the 12-layer encoder in int4 vs the binary16 baseline."""
     import numpy as np
     import torch
     res = {"large_m": [], "small_m": [], "encoder": None}
-    for (M, K, N) in [(16384, 1024, 4096), (16384, 4096, 1024), (16384, 768, 3072), (65536, 1024, 4096)]:
+    for (M, K, N) in LARGE_M_SHAPES:
         a = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
         w = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
         sw = torch.rand(N, device="cuda") * 0.049 + 0.001
