@@ -585,7 +585,10 @@ struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
     static constexpr int LDS_BYTES = S * Base::STAGE_BYTES;
     // resident waves per SIMD the kernel is compiled for: as many workgroups as the LDS
     // holds (at most 2 are useful), one wave of each per SIMD per WAVES / 4
-    static constexpr int WGS_PER_CU = (160 * 1024 / LDS_BYTES) >= 2 ? 2 : 1;
+    // two (small per-wave tiles: up to four, 128 registers each then) resident workgroups
+    static constexpr int WGS_FIT = 160 * 1024 / (LDS_BYTES + WAVES * 512);
+    static constexpr int WGS_WANT = (Base::TM * Base::TN <= 2) ? 4 : 2;
+    static constexpr int WGS_PER_CU = WGS_FIT < 1 ? 1 : (WGS_FIT < WGS_WANT ? WGS_FIT : WGS_WANT);
     static constexpr int WAVES_PER_EU = WGS_PER_CU * WAVES / 4;
     static_assert(COPIES % WAVES == 0, "copies must divide evenly over the waves");
     static_assert(BM_ % ROWS_PER_COPY == 0, "a copy must not straddle the A / W boundary");
@@ -1189,7 +1192,7 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
             const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
             if (t256x128 >= 512) cfg = 18;       // two resident workgroups per CU have a tile each
             else if (t128 >= 128) cfg = 12;      // half the CUs busy with 64x64-per-wave tiles beats
-            else cfg = 14;                       // all of them with 32x32-per-wave ones
+            else cfg = 27;                       // all of them with 32x32-per-wave ones (4 workgroups per CU)
         }
     }
     if (cfg >= 10 && !dma_ok) return MKQ_ERR_UNSUPPORTED;
@@ -1202,6 +1205,8 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     case 18: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
     case 19: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 256, 2, 2, 64, 3>>(p, epi, st);
     case 20: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 32, 6>>(p, epi, st);
+    case 27: return launch_dma_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>>(p, epi, st);
+    case 28: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 64, 2, 2, 64, 3>>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }
