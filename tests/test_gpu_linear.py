@@ -177,6 +177,24 @@ def test_every_tile_configuration(mkq, cfg, M, N, K):
 
 
 @pytest.mark.parametrize("cfg", [c for c in ALL_CFGS if c >= 10])
+@pytest.mark.parametrize("K", [128, 640])
+def test_single_stage_tiles_and_f16_residual(mkq, cfg, K):
+    """K = 128 is one ring stage per tile (the shortest pipeline); with a binary16 residual
+    and binary16 output the compile-time residual epilogue runs."""
+    import torch
+    M, N = 2100, 1160
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg + K)
+    res = np.random.default_rng(K).normal(0, 1, (M, N)).astype(np.float16)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, residual=res.astype(np.float32), out_dtype=oracle.F16)
+    mkq.debug_set_gemm_config(cfg)
+    try:
+        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, residual=to_dev(res))
+    finally:
+        mkq.debug_set_gemm_config(-1)
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+
+
+@pytest.mark.parametrize("cfg", [c for c in ALL_CFGS if c >= 10])
 @pytest.mark.parametrize("out_name", ["bf16", "i4"])
 def test_persistent_pipeline_over_many_tiles(mkq, cfg, out_name):
     """More tiles than resident workgroups, ragged edges, the compile-time epilogues:
