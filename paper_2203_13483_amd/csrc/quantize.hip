@@ -61,6 +61,32 @@ __global__ __launch_bounds__(256) void quantize_kernel(const T *__restrict__ x, 
     }
 }
 
+// The same for contiguous rows (ldx == K) and fewer than 2^31 words: no row/column split
+// (a 64-bit division per word in the general kernel), two words per thread with both loads
+// in flight before the arithmetic starts.
+template <typename T>
+__global__ __launch_bounds__(256) void quantize_contig_kernel(const T *__restrict__ x, int total_words, float s,
+                                                              uint32_t *__restrict__ q)
+{
+    const int stride = (int)(gridDim.x * blockDim.x);
+    const int w0 = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    const int w1 = w0 + stride;
+    if (w0 >= total_words) return;
+    const bool two = w1 < total_words;
+    float v0[8], v1[8];
+    load8<T>(x + (int64_t)w0 * 8, v0);
+    load8<T>(x + (int64_t)(two ? w1 : w0) * 8, v1);
+    int c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = quantize_code(v0[i], s);
+    q[w0] = pack8(c);
+    if (two) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = quantize_code(v1[i], s);
+        q[w1] = pack8(c);
+    }
+}
+
 // max |x| over a block's share, combined with an atomic max on the bit pattern
 // (non-negative floats order like unsigned integers).  *acc_bits must be 0 on entry.
 template <typename T>
@@ -223,6 +249,16 @@ extern "C" int mkq_quantize(const void *x, int x_dtype, int64_t M, int64_t K, in
     if (!x || !q_out) return MKQ_ERR_NULL;
     if (!aligned16(x) || !aligned16(q_out)) return MKQ_ERR_ALIGN;
     const int64_t words = M * (K / 8);
+    if (ldx == K && words < 0x40000000LL) {
+        const int g = (int)ceil_div(ceil_div(words, 2), 256);
+        if (x_dtype == MKQ_F32)
+            quantize_contig_kernel<float><<<g, 256, 0, as_stream(stream)>>>((const float *)x, (int)words, s_x,
+                                                                             (uint32_t *)q_out);
+        else
+            quantize_contig_kernel<__half><<<g, 256, 0, as_stream(stream)>>>((const __half *)x, (int)words, s_x,
+                                                                              (uint32_t *)q_out);
+        return launch_status();
+    }
     const int grid = grid_for(words);
     if (x_dtype == MKQ_F32)
         quantize_kernel<float><<<grid, 256, 0, as_stream(stream)>>>(
