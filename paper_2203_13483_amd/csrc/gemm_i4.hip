@@ -42,17 +42,7 @@ struct GemmI4Params {
     float s_next;
     uint8_t *q_out;     // extra packed codes, or null
     int32_t *acc_out;   // raw accumulators, or null
-#ifdef MKQ_TRACE
-    unsigned long long *dbg;
-#endif
 };
-#ifdef MKQ_TRACE
-static unsigned long long *g_trace_buf = nullptr;
-#define MKQ_TR(tag) do { if (tron && tri < 500) { tr[tri++] = ((unsigned long long)clock64() << 4) | (tag); } } while (0)
-#define MKQ_TRW(tag) do { if (tron && tri < 500) { tr[tri++] = ((unsigned long long)wall_clock64() << 4) | (tag); } } while (0)
-#else
-#define MKQ_TR(tag) do { } while (0)
-#endif
 
 // Widen two packed words (16 codes) to four int8x4 words (values 16*code).
 __device__ __forceinline__ v4i widen(uint32_t w0, uint32_t w1)
@@ -618,13 +608,6 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
     const int fr = lane & 31, fh = lane >> 5;
-#ifdef MKQ_TRACE
-    unsigned long long *tr = (unsigned long long *)(smem + Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS);
-    int tri = 0;
-    const bool tron = (tid == 0);
-    MKQ_TRW(6);
-    MKQ_TR(0);
-#endif
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const int total_tiles = tiles_m * tiles_n;
@@ -811,16 +794,13 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     // Stage boundary: the next stage becomes readable (INFLIGHT-1 younger stages may stay
     // in flight); past the barrier every wave is done with the slot that is refilled next.
     auto stage_boundary = [&]() {
-        MKQ_TR(1);
         if (ASYNC_STORES && stores_pending > 0) {
             wait_vmcnt<ASYNC_STORES ? (INFLIGHT - 1) * LPW + EPI_STORES : 0>();
             --stores_pending;
         } else {
             wait_vmcnt<(INFLIGHT - 1) * LPW>();
         }
-        MKQ_TR(2);
         lds_barrier();
-        MKQ_TR(3);
     };
     auto next_slot = [&](int b) { return (b + 1 == S) ? 0 : b + 1; };
 
@@ -885,7 +865,6 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         if (ck == kt_count) {
             int tile_m, tile_n;
             tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
-            MKQ_TR(4);
             if constexpr (ROWS_EPI) {
                 // the slot of the stage just finished is idle until every wave has passed
                 // the next stage boundary: each wave shuffles through its share of it
@@ -910,18 +889,9 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
                     for (int v = 0; v < 16; ++v) acc[j][t][v] = 0;
             ck = 0;
             ct += gridDim.x;
-            MKQ_TR(5);
         }
     }
     wait_vmcnt<0>();  // the trailing dummy copies must land before the LDS is released
-#ifdef MKQ_TRACE
-    MKQ_TR(8);
-    MKQ_TRW(7);
-    if (tron && p.dbg && blockIdx.x < 1024) {
-        p.dbg[blockIdx.x * 512] = tri;
-        for (int i = 0; i < tri; ++i) p.dbg[blockIdx.x * 512 + 1 + i] = tr[i];
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------------
@@ -1107,12 +1077,7 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
     constexpr bool rows_epi = !Epi::generic && EpiShuffle<Cfg>::usable;
     constexpr size_t lds_kernel = Cfg::LDS_BYTES + (rows_epi ? EpiShuffle<Cfg>::EXTRA_LDS : 0);
-#ifdef MKQ_TRACE
-    const size_t lds = lds_kernel + 4096;
-    const_cast<GemmI4Params &>(p).dbg = g_trace_buf;
-#else
     const size_t lds = lds_kernel;
-#endif
     static int wgs_per_cu = 0;  // per instantiation
     if (wgs_per_cu == 0) {
         if (lds > 65536 &&
@@ -1218,9 +1183,6 @@ using namespace mkq;
 // Tuning hook (not part of the public header): force one tile configuration of the
 // int4 GEMM (-1 = automatic choice).
 extern "C" void mkq_debug_set_gemm_config(int cfg) { mkq::g_forced_cfg = cfg; }
-#ifdef MKQ_TRACE
-extern "C" void mkq_debug_set_trace(unsigned long long *buf) { mkq::g_trace_buf = buf; }
-#endif
 
 extern "C" size_t mkq_linear_int4_workspace_bytes(int64_t M, int64_t N, int64_t K, int a_dtype)
 {
