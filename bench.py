@@ -394,6 +394,24 @@ def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
         t = event_time(g.replay, 20)
         out[name + "_us_per_layer"] = t * 1e6 / layers
     out["int4_vs_fp16_speedup"] = out["fp16_us_per_layer"] / out["int4_us_per_layer"]
+    # context for the binary16 baseline's own quality: the layer's four GEMMs alone, this library's
+    # binary16 kernel vs the vendor library's (torch.nn.functional.linear = hipBLASLt) vs the int4 path
+    try:
+        gem = {"ours_fp16_us": 0.0, "vendor_fp16_us": 0.0, "int4_us": 0.0}
+        for (K, N) in ((H, 3 * H), (H, H), (H, F), (F, H)):
+            a16 = torch.randn(M, K, device="cuda", dtype=torch.float16)
+            w16 = torch.randn(N, K, device="cuda", dtype=torch.float16) * 0.02
+            b32 = torch.zeros(N, device="cuda")
+            o16 = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            gem["ours_fp16_us"] += graph_time(lambda: mkq.mkq_linear_fp16(a16, w16, b32, mkq.MKQ_F16, out=o16)) * 1e6
+            gem["vendor_fp16_us"] += graph_time(lambda: torch.nn.functional.linear(a16, w16, out=None)) * 1e6
+            a4 = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
+            w4 = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
+            sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+            gem["int4_us"] += graph_time(lambda: mkq.mkq_linear_int4(a4, 0.01, w4, sw, b32, N, K, mkq.MKQ_F16, out=o16)) * 1e6
+        out["layer_gemms_only_us"] = gem
+    except Exception as e:
+        out["layer_gemms_only_us"] = {"error": repr(e)}
     gemm_ops = 2.0 * M * (H * 3 * H + H * H + 2 * H * F)
     out["int4_layer_gemm_TOPS"] = gemm_ops / (out["int4_us_per_layer"] * 1e-6) / 1e12
     out["paper_context"] = ("paper: int4 layer 8.6-14.9x faster than float32 and 1.26-1.37x faster than int8 "
