@@ -591,6 +591,9 @@ struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
 };
 
+// log2 of the wave-priority time slice, in shader cycles (0 = off); 2^15 measured best (2-4 %)
+constexpr int PRIO_SLICE_LOG2 = 15;
+
 template <class Cfg, class Epi>
 __global__ __launch_bounds__(Cfg::THREADS) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_EU, Cfg::WAVES_PER_EU)))
 void gemm_i4_dma_kernel(const GemmI4Params p)
@@ -793,7 +796,18 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
 
     // Stage boundary: the next stage becomes readable (INFLIGHT-1 younger stages may stay
     // in flight); past the barrier every wave is done with the slot that is refilled next.
+    // Two workgroups share a CU and the SIMD arbiter always serves the older wave first: the
+    // first-placed workgroup runs at full speed, the second in its gaps (and alone at the end).
+    // Each workgroup therefore takes the higher wave priority in alternate time slices of the
+    // CU's cycle counter, in opposite phase, so both progress at the same average rate.
+    const unsigned prio_phase = (2 * blockIdx.x >= gridDim.x) ? 1u : 0u;
+    unsigned long long tnow = 0;
     auto stage_boundary = [&]() {
+        if constexpr (Cfg::WGS_PER_CU == 2 && PRIO_SLICE_LOG2 > 0) {
+            const unsigned hi = __builtin_amdgcn_readfirstlane(((unsigned)(tnow >> PRIO_SLICE_LOG2) ^ prio_phase) & 1u);
+            if (hi) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         if (ASYNC_STORES && stores_pending > 0) {
             wait_vmcnt<ASYNC_STORES ? (INFLIGHT - 1) * LPW + EPI_STORES : 0>();
             --stores_pending;
@@ -829,6 +843,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     int ct = blockIdx.x, ck = 0;  // compute cursor
     int buf = 0;                  // ring slot of the stage being computed
     for (int s = 0; s < steps; s += 3 - ROUNDS) {
+        if constexpr (Cfg::WGS_PER_CU == 2 && PRIO_SLICE_LOG2 > 0) tnow = __builtin_readcyclecounter();  // used at the boundary
         if constexpr (ROWS_EPI) {
             if (ck == scale_stage) stage_scales(ct);
         }
