@@ -123,6 +123,30 @@ int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, co
                     const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
                     const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same linear with both operands in 8 bits (the int8 column of Table 2 in
+ * section 5.4; the 8-bit layers of the mixed 4/8-bit models of section 4.2).  Eq. 1
+ * with k = 8: codes in [-128, 127], one byte each, row-major, K-contiguous.
+ *   mkq_quantize_int8      x [M, K] (F32 / F16, row stride ldx) -> int8 [M, K], per-tensor
+ *                          step s_x; NaN -> 0.  K % 16 == 0.
+ *   mkq_pack_weights_int8  W [N, K] binary32 -> int8 [N, K] and per-channel steps
+ *                          s_w[n] = max_k |W[n,k]| / 127 (all-zero row -> 1) unless
+ *                          s_w_in gives them.  K % 16 == 0.
+ *   mkq_linear_int8        acc[m,n] = sum_k a[m,k] w[n,k] (int32, exact; |acc| <= K * 2^14),
+ *                          y = fma((float)acc, s_x * s_w[n], bias[n]), then residual and
+ *                          activation as in mkq_linear_int4.  a is int8 codes [M, K]
+ *                          (quantize first; there is no workspace), out [M, N] of
+ *                          F32 / F16 / BF16, or NULL with epi->acc_out.  Code outputs
+ *                          (out_dtype MKQ_I4, epi->q_out) are not offered: UNSUPPORTED.
+ *                          K % 64 == 0, K < 65536.  M == 0 is a no-op.
+ * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, UNSUPPORTED, HIP. */
+int mkq_quantize_int8(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, float s_x,
+                      int8_t *q_out, void *stream);
+int mkq_pack_weights_int8(const float *W, int64_t N, int64_t K, const float *s_w_in,
+                          float *s_w_out, int8_t *Wq_out, void *stream);
+int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w,
+                    const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                    const mkq_epilogue *epi, void *stream);
+
 /* 16-bit float baseline linear (same epilogue, no quantizers):
  *   a [M, K] binary16, W [N, K] binary16, bias [N] binary32 or NULL, binary32
  *   accumulation, out [M, N] of out_dtype (F32 or F16), residual binary16 or NULL.

@@ -22,6 +22,7 @@ EXPORTS = [
     "mkq_status_string", "mkq_version", "mkq_quantize", "mkq_absmax_scale",
     "mkq_packed_weight_bytes", "mkq_pack_weights_int4", "mkq_pack_codes_int4",
     "mkq_unpack_weights_int4", "mkq_linear_int4_workspace_bytes", "mkq_linear_int4",
+    "mkq_quantize_int8", "mkq_pack_weights_int8", "mkq_linear_int8",
     "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
     "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
 ]
@@ -85,6 +86,9 @@ def load() -> C.CDLL:
         "mkq_linear_int4_workspace_bytes": (sz, [i64, i64, i64, ci]),
         "mkq_linear_int4": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
                                  C.POINTER(Epilogue), vp, sz, vp]),
+        "mkq_quantize_int8": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
+        "mkq_pack_weights_int8": (ci, [vp, i64, i64, vp, vp, vp, vp]),
+        "mkq_linear_int8": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp]),
         "mkq_linear_fp16": (ci, [vp, vp, vp, i64, i64, i64, vp, ci, ci, vp, vp]),
         "mkq_bert_layer_workspace": (ci, [C.POINTER(BertLayerParams), C.POINTER(BertLayerWorkspaceLayout)]),
         "mkq_bert_layer_int4": (ci, [C.POINTER(BertLayerParams), vp, ci, vp, vp, vp, vp, sz, vp]),
@@ -239,6 +243,45 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
                                   M, N, K, _ptr(out), int(out_dtype), C.byref(epi), _ptr(workspace),
                                   ws_bytes, _stream(stream)), "mkq_linear_int4")
     return {"out": out, "q": q, "acc": acc}
+
+
+def mkq_quantize_int8(x, s_x: float, q_out=None, stream=None):
+    """x [M,K] float32/float16 -> int8 codes [M,K] (8-bit range of the quantizer)."""
+    torch = _torch()
+    M, K = x.shape
+    if q_out is None:
+        q_out = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    _check(load().mkq_quantize_int8(_ptr(x), _dtype_code(x), M, K, x.stride(0), float(s_x), _ptr(q_out),
+                                    _stream(stream)), "mkq_quantize_int8")
+    return q_out
+
+
+def mkq_pack_weights_int8(W, s_w_in=None, stream=None):
+    """W [N,K] float32 -> (int8 codes [N,K], s_w float32 [N])."""
+    torch = _torch()
+    N, K = W.shape
+    Wq = torch.empty((N, K), dtype=torch.int8, device=W.device)
+    s_w = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(load().mkq_pack_weights_int8(_ptr(W), N, K, _ptr(s_w_in), _ptr(s_w), _ptr(Wq),
+                                        _stream(stream)), "mkq_pack_weights_int8")
+    return Wq, s_w
+
+
+def mkq_linear_int8(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, act: int = MKQ_ACT_NONE,
+                    residual=None, want_acc: bool = False, out=None, stream=None):
+    """The 8-bit linear: ``a`` int8 codes [M,K], ``Wq`` int8 codes [N,K]."""
+    torch = _torch()
+    M, K = a.shape
+    N = Wq.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=_torch_dtype(out_dtype), device=a.device)
+    acc = torch.empty((M, N), dtype=torch.int32, device=a.device) if want_acc else None
+    epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
+                   residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
+                   s_next=0.0, q_out=None, acc_out=acc.data_ptr() if acc is not None else None)
+    _check(load().mkq_linear_int8(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
+                                  int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int8")
+    return {"out": out, "acc": acc}
 
 
 def mkq_linear_fp16(a, W, bias, out_dtype: int = MKQ_F16, act: int = MKQ_ACT_NONE, residual=None,

@@ -42,6 +42,10 @@ struct GemmI4Params {
     float s_next;
     uint8_t *q_out;     // extra packed codes, or null
     int32_t *acc_out;   // raw accumulators, or null
+    // What the int32 accumulator holds: 2^acc_shift * sum(a*w).  The 4-bit path feeds the
+    // matrix core 16*code on both sides (shift 8); the 8-bit path feeds the codes themselves.
+    int acc_shift;
+    float acc_unit;     // 2^-acc_shift, folded into the per-channel scale (exact)
 };
 
 // Widen two packed words (16 codes) to four int8x4 words (values 16*code).
@@ -136,7 +140,7 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                 }
             }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sc[e] = (p.s_x * sc[e]) * 0.00390625f;  // * 2^-8, exact
+            for (int e = 0; e < 8; ++e) sc[e] = (p.s_x * sc[e]) * p.acc_unit;  // power of two: exact
             static_for<TM>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;
                 __builtin_amdgcn_sched_barrier(0);
@@ -149,10 +153,10 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
 
                 if (acc_out) {
                     if (vec_ok) {
-                        *reinterpret_cast<int4 *>(acc_out + o) = make_int4(a[0] >> 8, a[1] >> 8, a[2] >> 8, a[3] >> 8);
-                        *reinterpret_cast<int4 *>(acc_out + o + 4) = make_int4(a[4] >> 8, a[5] >> 8, a[6] >> 8, a[7] >> 8);
+                        *reinterpret_cast<int4 *>(acc_out + o) = make_int4(a[0] >> p.acc_shift, a[1] >> p.acc_shift, a[2] >> p.acc_shift, a[3] >> p.acc_shift);
+                        *reinterpret_cast<int4 *>(acc_out + o + 4) = make_int4(a[4] >> p.acc_shift, a[5] >> p.acc_shift, a[6] >> p.acc_shift, a[7] >> p.acc_shift);
                     } else {
-                        for (int e = 0; e < nvalid; ++e) acc_out[o + e] = a[e] >> 8;
+                        for (int e = 0; e < nvalid; ++e) acc_out[o + e] = a[e] >> p.acc_shift;
                     }
                 }
                 if (!need_y) return;
@@ -273,11 +277,11 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
     const int rrow = lane >> 2;        // reader: rows rrow and rrow + 16
     const int pc = lane & 3;           // reader: channels 8 * pc .. + 7 of the 32-channel tile
 
-    // sc_lds holds s_w then bias of the wave's WTN channels.  Fold s_x * 2^-8 (exact) into
-    // the scales once; no bias -> zeros.
+    // sc_lds holds s_w then bias of the wave's WTN channels.  Fold s_x and the accumulator's
+    // power-of-two unit (exact) into the scales once; no bias -> zeros.
 #pragma unroll
     for (int c = lane; c < WTN; c += 64) {
-        sc_lds[c] = (p.s_x * sc_lds[c]) * 0.00390625f;
+        sc_lds[c] = (p.s_x * sc_lds[c]) * p.acc_unit;
         if (!p.bias) sc_lds[Sh::BIAS_AT + c] = 0.0f;
     }
     // writer: the lane's 8 values of unit G are pieces 4G + 2fh, 4G + 2fh + 1 of row fr
@@ -594,10 +598,14 @@ struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
 // log2 of the wave-priority time slice, in shader cycles (0 = off); 2^15 measured best (2-4 %)
 constexpr int PRIO_SLICE_LOG2 = 15;
 
-template <class Cfg, class Epi>
+// BITS = 4: nibble-packed operands, widened on the way to the matrix core.  BITS = 8: the
+// operands are int8 codes already (the W8A8 comparison path): same ring, same epilogues, a
+// 64-byte stage is then two k steps of 32 codes and nothing is widened.
+template <class Cfg, class Epi, int BITS>
 __global__ __launch_bounds__(Cfg::THREADS) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_EU, Cfg::WAVES_PER_EU)))
 void gemm_i4_dma_kernel(const GemmI4Params p)
 {
+    static_assert(BITS == 4 || (BITS == 8 && Cfg::RB == 64), "8-bit operands use 64-byte stages");
     constexpr int BM = Cfg::BM, BN = Cfg::BN, RB = Cfg::RB, CH = Cfg::CH;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     constexpr int S = Cfg::S, LPW = Cfg::LPW;
@@ -614,7 +622,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const int total_tiles = tiles_m * tiles_n;
-    const int row_bytes = p.K / 2;
+    const int row_bytes = p.K * BITS / 8;
     const int kt_count = row_bytes / RB;
     // Persistent workgroup: tiles blockIdx.x, blockIdx.x + gridDim.x, ... run through ONE
     // software pipeline, so a tile's first stages are in flight during the previous
@@ -767,6 +775,32 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         });
     };
 
+    // 8-bit operands: one k step per 32-byte round, two per stage.  Step H multiplies the round
+    // in raw[H] while round H^1 (of this stage in step 0, of the next stage in step 1, which also
+    // issues the wave's copies) is fetched into raw[H^1].
+    auto k_step8 = [&](auto hc, int rd_off, int cslot) {
+        constexpr int H = decltype(hc)::value;
+        static_for<NMFMA>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            constexpr int j = i / TN, t = i % TN;
+            const v4i fw = {(int)raw[H][t][0], (int)raw[H][t][1], (int)raw[H][t][2], (int)raw[H][t][3]};
+            const v4i fa = {(int)raw[H][TN + j][0], (int)raw[H][TN + j][1], (int)raw[H][TN + j][2],
+                            (int)raw[H][TN + j][3]};
+            acc[j][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw, fa, acc[j][t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            constexpr int f0 = i * NF / NMFMA, f1 = (i + 1) * NF / NMFMA;
+            static_for<f1 - f0>([&](auto fc) {
+                constexpr int f = f0 + decltype(fc)::value;
+                read_frag(rd_off, IntC<f>{}, IntC<H == 0 ? 1 : 0>{}, raw[H ^ 1][f]);
+            });
+            if constexpr (H == 1) {
+                constexpr int q0 = i * LPW / NMFMA, q1 = (i + 1) * LPW / NMFMA;
+                static_for<q1 - q0>([&](auto qc) { copy_one(cslot, IntC<q0 + decltype(qc)::value>{}); });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
     // prologue: put INFLIGHT + 1 stages in flight, wait for stage 0, prime the register pipeline
 #pragma unroll
     for (int i = 0; i < INFLIGHT + 1; ++i) {
@@ -776,10 +810,12 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     wait_vmcnt<INFLIGHT * LPW>();
     lds_barrier();
     static_for<NF>([&](auto fc) { read_frag(0, fc, IntC<0>{}, raw[0][decltype(fc)::value]); });
-    static_for<4 * NF>([&](auto mc) {
-        constexpr int m = decltype(mc)::value;
-        wid[0][m / 4][m % 4] = widen_reg(raw[0][m / 4], IntC<0>{}, IntC<m % 4>{});
-    });
+    if constexpr (BITS == 4) {
+        static_for<4 * NF>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            wid[0][m / 4][m % 4] = widen_reg(raw[0][m / 4], IntC<0>{}, IntC<m % 4>{});
+        });
+    }
 
     // Epilogue stores share the in-order vmcnt counter with the copies.  For the
     // INFLIGHT stage boundaries that follow an epilogue the wanted copies are older than
@@ -847,7 +883,15 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         if constexpr (ROWS_EPI) {
             if (ck == scale_stage) stage_scales(ct);
         }
-        if constexpr (ROUNDS == 2) {
+        if constexpr (BITS == 8) {
+            const int nbuf = next_slot(buf);
+            k_step8(IntC<0>{}, buf * Cfg::STAGE_BYTES, 0);
+            stage_boundary();
+            k_step8(IntC<1>{}, nbuf * Cfg::STAGE_BYTES, buf == 0 ? S - 1 : buf - 1);
+            copy_advance();
+            buf = nbuf;
+            ck += 1;
+        } else if constexpr (ROUNDS == 2) {
             // one 128-code stage: round 1 is fetched from the same stage, then the boundary,
             // then round 0 of the next stage while the slot of the previous one is refilled
             const int nbuf = next_slot(buf);
@@ -1085,7 +1129,7 @@ static int launch_gemm_i4(const GemmI4Params &p, hipStream_t st)
     return full ? launch_one<Cfg, true>(p, tiles, st) : launch_one<Cfg, false>(p, tiles, st);
 }
 
-template <class Cfg, class Epi>
+template <class Cfg, class Epi, int BITS = 4>
 static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
@@ -1096,11 +1140,11 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
     static int wgs_per_cu = 0;  // per instantiation
     if (wgs_per_cu == 0) {
         if (lds > 65536 &&
-            hipFuncSetAttribute((const void *)gemm_i4_dma_kernel<Cfg, Epi>,
+            hipFuncSetAttribute((const void *)gemm_i4_dma_kernel<Cfg, Epi, BITS>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return MKQ_ERR_HIP;
         int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_dma_kernel<Cfg, Epi>, Cfg::THREADS, lds) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_dma_kernel<Cfg, Epi, BITS>, Cfg::THREADS, lds) !=
                 hipSuccess || occ < 1)
             return MKQ_ERR_HIP;
         if (g_num_cus == 0) {
@@ -1114,7 +1158,7 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
     }
     const int64_t resident = (int64_t)g_num_cus * wgs_per_cu;
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
-    gemm_i4_dma_kernel<Cfg, Epi><<<grid, Cfg::THREADS, lds, st>>>(p);
+    gemm_i4_dma_kernel<Cfg, Epi, BITS><<<grid, Cfg::THREADS, lds, st>>>(p);
     return launch_status();
 }
 
@@ -1191,6 +1235,30 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     }
 }
 
+// 8-bit operands (W8A8 comparison path): [M, K] and [N, K] int8 codes, K a multiple of 64.
+template <class Cfg>
+static int launch_i8_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
+{
+    switch (epi) {
+    case EPI_F16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, false, false>, 8>(p, st);
+    case EPI_BF16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_BF16, false, false>, 8>(p, st);
+    case EPI_F32: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F32, false, false>, 8>(p, st);
+    default: return launch_gemm_i4_dma<Cfg, EpiGeneric, 8>(p, st);
+    }
+}
+
+int run_gemm_i8(const GemmI4Params &p, hipStream_t st)
+{
+    if ((p.K % 64) != 0) return MKQ_ERR_UNSUPPORTED;
+    int epi = classify_epilogue(p);
+    if (epi == EPI_F16_RES16 || epi == EPI_I4 || epi == EPI_I4_GELU) epi = EPI_GENERIC;
+    const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
+    const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
+    if (t256x128 >= 512) return launch_i8_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
+    if (t128 >= 128) return launch_i8_by_epilogue<DmaMid>(p, epi, st);
+    return launch_i8_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>>(p, epi, st);
+}
+
 }  // namespace mkq
 
 using namespace mkq;
@@ -1259,5 +1327,48 @@ extern "C" int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint
     p.s_next = epi ? epi->s_next : 1.0f;
     p.q_out = (epi && !(out && out_dtype == MKQ_I4)) ? epi->q_out : nullptr;
     p.acc_out = epi ? epi->acc_out : nullptr;
+    p.acc_shift = 8;
+    p.acc_unit = 0.00390625f;
     return run_gemm_i4(p, as_stream(stream));
+}
+
+extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w,
+                               const float *bias, int64_t M, int64_t N, int64_t K, void *out,
+                               int out_dtype, const mkq_epilogue *epi, void *stream)
+{
+    const bool want_acc = epi && epi->acc_out;
+    if (out_dtype == MKQ_I4 || (epi && epi->q_out)) return MKQ_ERR_UNSUPPORTED;
+    if (out_dtype != MKQ_F32 && out_dtype != MKQ_F16 && out_dtype != MKQ_BF16) return MKQ_ERR_DTYPE;
+    if (epi) {
+        if (epi->act != MKQ_ACT_NONE && epi->act != MKQ_ACT_GELU) return MKQ_ERR_DTYPE;
+        if (epi->residual && epi->residual_dtype != MKQ_F32 && epi->residual_dtype != MKQ_F16)
+            return MKQ_ERR_DTYPE;
+    }
+    if (M < 0 || N <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
+    if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
+    if (M == 0) return MKQ_OK;
+    if (!a || !Wq || !s_w) return MKQ_ERR_NULL;
+    if (!out && !want_acc) return MKQ_ERR_NULL;
+    if (!aligned16(a) || !aligned16(Wq) || (out && !aligned16(out)) || !aligned16(s_w) ||
+        (bias && !aligned16(bias)))
+        return MKQ_ERR_ALIGN;
+    if (epi && ((epi->residual && !aligned16(epi->residual)) || (epi->acc_out && !aligned16(epi->acc_out))))
+        return MKQ_ERR_ALIGN;
+    // 32-bit byte offsets into the operands
+    if (K >= 65536 || M > 0x7FFFFFFF || N > 0x7FFFFFFF || M * K > 0xFFFFFFFFLL || N * K > 0xFFFFFFFFLL)
+        return MKQ_ERR_UNSUPPORTED;
+
+    GemmI4Params p;
+    p.A = (const uint8_t *)a; p.W = (const uint8_t *)Wq; p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.s_x = s_x; p.s_w = s_w; p.bias = bias;
+    p.residual = epi ? epi->residual : nullptr;
+    p.residual_dtype = epi ? epi->residual_dtype : MKQ_F32;
+    p.act = epi ? epi->act : MKQ_ACT_NONE;
+    p.out = out; p.out_dtype = out ? out_dtype : -1;
+    p.s_next = 1.0f;
+    p.q_out = nullptr;
+    p.acc_out = epi ? epi->acc_out : nullptr;
+    p.acc_shift = 0;   // byte operands enter the MFMA as they are
+    p.acc_unit = 1.0f;
+    return run_gemm_i8(p, as_stream(stream));
 }

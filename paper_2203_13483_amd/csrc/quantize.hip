@@ -227,6 +227,76 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const uint32_t *__res
     }
 }
 
+// ---- 8-bit range (the comparison column of Table 2; mixed 4/8-bit models of section 4.2) ----
+// Eq. 1 with k = 8: clamp to [-128, 127], one byte per code, no packing.
+
+__device__ __forceinline__ int quantize_code8(float x, float s)
+{
+    float v = x / s;
+    v = (v != v) ? 0.0f : v;
+    v = fminf(fmaxf(v, -128.0f), 127.0f);
+    return (int)__builtin_rintf(v);
+}
+
+__device__ __forceinline__ uint2 bytes8(const int (&c)[8])
+{
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        lo |= ((uint32_t)c[i] & 0xFFu) << (8 * i);
+        hi |= ((uint32_t)c[4 + i] & 0xFFu) << (8 * i);
+    }
+    return make_uint2(lo, hi);
+}
+
+// x [M,K] (row stride ldx) -> int8 codes [M,K]; each thread turns 8 values into 8 bytes.
+template <typename T>
+__global__ __launch_bounds__(256) void quantize8_kernel(const T *__restrict__ x, int64_t M, int64_t K,
+                                                        int64_t ldx, float s, uint2 *__restrict__ q)
+{
+    const int64_t groups_per_row = K / 8;
+    const int64_t total = M * groups_per_row;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t m = g / groups_per_row;
+        const int64_t kg = g - m * groups_per_row;
+        float v[8];
+        load8<T>(x + m * ldx + kg * 8, v);
+        int c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = quantize_code8(v[i], s);
+        q[g] = bytes8(c);
+    }
+}
+
+// One workgroup per output channel: step = max|row| / 127 (or the given one), then codes.
+__global__ __launch_bounds__(256) void pack_weights8_kernel(const float *__restrict__ W, int64_t K,
+                                                            const float *__restrict__ s_in,
+                                                            float *__restrict__ s_out,
+                                                            uint2 *__restrict__ q)
+{
+    __shared__ float part[4];
+    const int64_t n = blockIdx.x;
+    const float *row = W + n * K;
+    float s;
+    if (s_in) {
+        s = s_in[n];
+    } else {
+        const float mx = row_absmax<float>(row, K, part);
+        s = (mx > 0.0f) ? mx / 127.0f : 1.0f;
+    }
+    if (threadIdx.x == 0) s_out[n] = s;
+    uint2 *qrow = q + n * (K / 8);
+    for (int64_t k = (int64_t)threadIdx.x * 8; k < K; k += (int64_t)blockDim.x * 8) {
+        float v[8];
+        load8<float>(row + k, v);
+        int c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = quantize_code8(v[i], s);
+        qrow[k / 8] = bytes8(c);
+    }
+}
+
 static inline int grid_for(int64_t items, int threads = 256, int max_blocks = 256 * 16)
 {
     int64_t b = ceil_div(items, threads);
@@ -312,6 +382,38 @@ extern "C" int mkq_pack_weights_int4(const float *W, int64_t N, int64_t K, const
         return MKQ_ERR_ALIGN;
     pack_weights_kernel<<<(int)N, 256, 0, as_stream(stream)>>>(W, K, s_w_in, s_w_out,
                                                                (uint32_t *)Wq_out);
+    return launch_status();
+}
+
+extern "C" int mkq_quantize_int8(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                                 float s_x, int8_t *q_out, void *stream)
+{
+    if (x_dtype != MKQ_F32 && x_dtype != MKQ_F16) return MKQ_ERR_DTYPE;
+    if (M < 0 || K < 0 || (K % 16) != 0 || ldx < K || (ldx % 8) != 0) return MKQ_ERR_SHAPE;
+    if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
+    if (M == 0 || K == 0) return MKQ_OK;
+    if (!x || !q_out) return MKQ_ERR_NULL;
+    if (!aligned16(x) || !aligned16(q_out)) return MKQ_ERR_ALIGN;
+    const int grid = grid_for(M * (K / 8));
+    if (x_dtype == MKQ_F32)
+        quantize8_kernel<float><<<grid, 256, 0, as_stream(stream)>>>((const float *)x, M, K, ldx, s_x,
+                                                                     (uint2 *)q_out);
+    else
+        quantize8_kernel<__half><<<grid, 256, 0, as_stream(stream)>>>((const __half *)x, M, K, ldx, s_x,
+                                                                      (uint2 *)q_out);
+    return launch_status();
+}
+
+extern "C" int mkq_pack_weights_int8(const float *W, int64_t N, int64_t K, const float *s_w_in,
+                                     float *s_w_out, int8_t *Wq_out, void *stream)
+{
+    if (!W || !s_w_out || !Wq_out) return MKQ_ERR_NULL;
+    if (N <= 0 || K <= 0 || (K % 16) != 0) return MKQ_ERR_SHAPE;
+    if (N > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    if (!aligned16(W) || !aligned16(Wq_out) || (reinterpret_cast<uintptr_t>(s_w_out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(s_w_in) & 3u))
+        return MKQ_ERR_ALIGN;
+    pack_weights8_kernel<<<(int)N, 256, 0, as_stream(stream)>>>(W, K, s_w_in, s_w_out, (uint2 *)Wq_out);
     return launch_status();
 }
 
