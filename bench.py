@@ -304,10 +304,26 @@ def side_measurements(mkq, event_time):
         out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
         t = graph_time(lambda: mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_BF16, out=out))
         tops = 2.0 * M * N * K / t / 1e12
-        res["large_m"].append({"M": M, "K": K, "N": N, "out": "bf16", "us": t * 1e6, "TOPS": tops,
-                               "frac_int8_peak": tops / INT8_MFMA_PEAK_TOPS,
-                               "protocol": "HIP graph of 20 back-to-back launches, median of 7 samples"})
-        del a, w, out
+        row = {"M": M, "K": K, "N": N, "out": "bf16", "us": t * 1e6, "TOPS": tops,
+               "frac_int8_peak": tops / INT8_MFMA_PEAK_TOPS,
+               "protocol": "HIP graph of 20 back-to-back launches, median of 7 samples"}
+        del a, w
+        # context beside it, same shape and protocol: this library's 8-bit linear (int8 codes in,
+        # bf16 out) and the vendor library's int8 (int32 out) and bf16 GEMMs as torch calls them
+        a8 = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda")
+        w8 = torch.randint(-128, 128, (N, K), dtype=torch.int8, device="cuda")
+        row["int8_us"] = graph_time(lambda: mkq.mkq_linear_int8(a8, 0.01, w8, sw, None, mkq.MKQ_BF16, out=out)) * 1e6
+        try:
+            torch._int_mm(a8, w8.t())
+            row["vendor_int8_us"] = graph_time(lambda: torch._int_mm(a8, w8.t())) * 1e6
+        except Exception:
+            row["vendor_int8_us"] = None
+        a16 = torch.randn((M, K), dtype=torch.bfloat16, device="cuda")
+        w16 = torch.randn((N, K), dtype=torch.bfloat16, device="cuda")
+        torch.mm(a16, w16.t(), out=out)
+        row["vendor_bf16_us"] = graph_time(lambda: torch.mm(a16, w16.t(), out=out)) * 1e6
+        res["large_m"].append(row)
+        del a8, w8, a16, w16, out
 
     # small M: every call reads a different weight matrix from a pool larger than the
     # 256 MB last-level cache, so the weights always come from HBM

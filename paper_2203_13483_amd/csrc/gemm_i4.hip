@@ -1210,13 +1210,22 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
         if (!dma_ok) {
             cfg = 3;
         } else {
-            const int64_t t256 = ceil_div(p.M, 256) * ceil_div(p.N, 256);
+            // Tile choice, from sweeps over M = 256 .. 65536 at the BERT-base / BERT-large shapes.
+            // Large problems: 256x128 tiles, two workgroups per CU.  Few tiles: 64x64 tiles, four
+            // workgroups per CU (the launch is latency-bound, parallelism wins).  In between, 128x128
+            // tiles when they fill their 512 slots in whole rounds, else 128x64 (1024 slots).
             const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
-            (void)t256;
+            const int64_t t128x64 = ceil_div(p.M, 128) * ceil_div(p.N, 64);
             const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
-            if (t256x128 >= 512) cfg = 18;       // two resident workgroups per CU have a tile each
-            else if (t128 >= 128) cfg = 12;      // half the CUs busy with 64x64-per-wave tiles beats
-            else cfg = 27;                       // all of them with 32x32-per-wave ones (4 workgroups per CU)
+            const double ops = 2.0 * p.M * p.N * p.K;
+            if (t256x128 >= 512 || (t256x128 >= 256 && ops >= 3e10)) {
+                cfg = 18;
+            } else if (t128x64 < 256) {
+                cfg = 27;
+            } else {
+                const int64_t rounds = ceil_div(t128, 512);
+                cfg = (10 * t128 >= 9 * 512 * rounds) ? 12 : 28;
+            }
         }
     }
     if (cfg >= 10 && !dma_ok) return MKQ_ERR_UNSUPPORTED;
