@@ -367,23 +367,30 @@ def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
     H, heads, F = 768, 12, 3072
     M = batch * seq
     h = torch.from_numpy(wl.hidden_states(batch, seq, H, 2).astype(np.float16)).cuda()
-    int4_layers, fp16_layers = [], []
+    int4_layers, fp16_layers, int8_layers = [], [], []
     for l in range(layers):
         p = wl.bert_layer_weights(H, heads, F, 100 + l)
         ln = {k: torch.from_numpy(p[k]).cuda() for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
-        packed, w16 = {}, {}
+        packed, w16, packed8 = {}, {}, {}
         for nm in ("qkv", "ao", "up", "down"):
             W = torch.from_numpy(p["W_" + nm]).cuda()
             b = torch.from_numpy(p["b_" + nm]).cuda()
             Wq, s_w = mkq.mkq_pack_weights_int4(W)
             packed[nm] = (Wq, s_w, b)
             w16[nm] = (W.half(), b)
+            packed8[nm] = mkq.mkq_pack_weights_int8(W) + (b,)
         # stand-ins for learned steps: ~unit-variance LayerNorm outputs, small context / GELU outputs
         sx = {"qkv": wl.LEARNED_STEP_UNIT_GAUSSIAN, "ao": 0.05, "up": wl.LEARNED_STEP_UNIT_GAUSSIAN, "down": 0.05}
         int4_layers.append(mkq.BertLayerInt4(batch, seq, H, heads, F, packed, sx, ln, 1e-12,
                                              s_out_next=wl.LEARNED_STEP_UNIT_GAUSSIAN))
         fp16_layers.append(mkq.BertLayerFp16(batch, seq, H, heads, F, w16, ln, 1e-12))
+        # the same layer W8A8 (8-bit layers of a mixed model): the same clipping points, 127 / 7 finer steps
+        sx8 = {k: v * 7.0 / 127.0 for k, v in sx.items()}
+        int8_layers.append(mkq.BertLayerInt8(batch, seq, H, heads, F, packed8, sx8, ln, 1e-12,
+                                             s_out_next=wl.LEARNED_STEP_UNIT_GAUSSIAN * 7.0 / 127.0))
     ws4 = torch.empty(int4_layers[0].workspace_bytes(), dtype=torch.uint8, device="cuda")
+    ws8 = torch.empty(int8_layers[0].workspace_bytes(), dtype=torch.uint8, device="cuda")
+    q8bufs = [torch.empty((M, H), dtype=torch.int8, device="cuda") for _ in range(2)]
     ws16 = torch.empty(fp16_layers[0].workspace_bytes(), dtype=torch.uint8, device="cuda")
     bufs = [torch.empty((M, H), dtype=torch.float16, device="cuda") for _ in range(2)]
     qbufs = [torch.empty((M, H // 2), dtype=torch.uint8, device="cuda") for _ in range(2)]
@@ -394,6 +401,12 @@ def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
             layer(x, ws4, h_out=bufs[i & 1], q_in=q, q_out_next=qbufs[i & 1])
             x, q = bufs[i & 1], qbufs[i & 1]
 
+    def run_int8():
+        x, q = h, None
+        for i, layer in enumerate(int8_layers):
+            layer(x, ws8, h_out=bufs[i & 1], q_in=q, q_out_next=q8bufs[i & 1])
+            x, q = bufs[i & 1], q8bufs[i & 1]
+
     def run_fp16():
         x = h
         for i, layer in enumerate(fp16_layers):
@@ -401,7 +414,7 @@ def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
             x = bufs[i & 1]
 
     out = {"layers": layers, "batch": batch, "seq": seq, "hidden": H, "ffn": F}
-    for name, fn in (("int4", run_int4), ("fp16", run_fp16)):
+    for name, fn in (("int4", run_int4), ("fp16", run_fp16), ("int8", run_int8)):
         fn()
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
@@ -410,6 +423,7 @@ def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
         t = event_time(g.replay, 20)
         out[name + "_us_per_layer"] = t * 1e6 / layers
     out["int4_vs_fp16_speedup"] = out["fp16_us_per_layer"] / out["int4_us_per_layer"]
+    out["int4_vs_int8_speedup"] = out["int8_us_per_layer"] / out["int4_us_per_layer"]
     # context for the binary16 baseline's own quality: the layer's four GEMMs alone, this library's
     # binary16 kernel vs the vendor library's (torch.nn.functional.linear = hipBLASLt) vs the int4 path
     try:

@@ -42,7 +42,7 @@ enum {
     MKQ_ERR_HIP = -8          /* the HIP runtime reported an error at launch */
 };
 
-enum { MKQ_F32 = 0, MKQ_F16 = 1, MKQ_BF16 = 2, MKQ_I4 = 3 };
+enum { MKQ_F32 = 0, MKQ_F16 = 1, MKQ_BF16 = 2, MKQ_I4 = 3, MKQ_I8 = 4 };
 enum { MKQ_ACT_NONE = 0, MKQ_ACT_GELU = 1 };
 
 const char *mkq_status_string(int status);
@@ -135,8 +135,9 @@ int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, co
  *                          y = fma((float)acc, s_x * s_w[n], bias[n]), then residual and
  *                          activation as in mkq_linear_int4.  a is int8 codes [M, K]
  *                          (quantize first; there is no workspace), out [M, N] of
- *                          F32 / F16 / BF16, or NULL with epi->acc_out.  Code outputs
- *                          (out_dtype MKQ_I4, epi->q_out) are not offered: UNSUPPORTED.
+ *                          F32 / F16 / BF16, or int8 codes of y under epi->s_next (MKQ_I8),
+ *                          or NULL with epi->acc_out.  4-bit code outputs (out_dtype
+ *                          MKQ_I4, epi->q_out) are not offered: UNSUPPORTED.
  *                          K % 64 == 0, K < 65536.  M == 0 is a no-op.
  * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, UNSUPPORTED, HIP. */
 int mkq_quantize_int8(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, float s_x,
@@ -222,6 +223,18 @@ int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *p_host, const void *h_
                         void *h_out /* binary16 */, void *workspace, size_t workspace_bytes,
                         void *stream);
 
+/* The same encoder layer with every linear W8A8 (an 8-bit layer of a mixed 4/8-bit model,
+ * section 4.2; the int8 column of Table 2): the params struct is the one above with
+ * Wq_* = int8 codes [N, K] from mkq_pack_weights_int8 and sx_* the steps of the 8-bit
+ * range; every code buffer (q_in, q_out_next, the c* intermediates) holds one byte per
+ * code, so the workspace layout has c0, c1, c2 of M*hidden bytes and c3 of M*ffn bytes.
+ * Same shape limits and errors as mkq_bert_layer_int4. */
+int mkq_bert_layer_int8_workspace(const mkq_bert_layer_params *p_host,
+                                  mkq_bert_layer_workspace_layout *layout_host);
+int mkq_bert_layer_int8(const mkq_bert_layer_params *p_host, const void *h_in, int h_dtype,
+                        const int8_t *q_in, void *h_out, int8_t *q_out_next, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
 /* Building blocks of the layer, exported for stage-wise parity checks.
  * LayerNorm over the last dimension in binary32 (section 5); x binary16 [M, D];
  * y binary16 [M, D] (may be NULL); q_out (NULL or [M, D/2]) receives
@@ -234,6 +247,12 @@ int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const
  * Currently d_k == 64, seq % 32 == 0, seq <= 128 (anything else: UNSUPPORTED). */
 int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
                   void *ctx, float s_next, uint8_t *q_out, void *stream);
+
+/* The two building blocks with 8-bit code output: q_out int8 [M, D] / [batch*seq, hidden]. */
+int mkq_layernorm_int8(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                       float eps, void *y, float s_next, int8_t *q_out, void *stream);
+int mkq_attention_int8(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
+                       void *ctx, float s_next, int8_t *q_out, void *stream);
 
 #ifdef __cplusplus
 }

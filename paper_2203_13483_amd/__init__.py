@@ -15,14 +15,15 @@ LIB_PATH = os.path.join(_PKG, "libmkq.so")
 MKQ_OK = 0
 MKQ_ERR_NULL, MKQ_ERR_SHAPE, MKQ_ERR_ALIGN, MKQ_ERR_SCALE = -1, -2, -3, -4
 MKQ_ERR_DTYPE, MKQ_ERR_WORKSPACE, MKQ_ERR_UNSUPPORTED, MKQ_ERR_HIP = -5, -6, -7, -8
-MKQ_F32, MKQ_F16, MKQ_BF16, MKQ_I4 = 0, 1, 2, 3
+MKQ_F32, MKQ_F16, MKQ_BF16, MKQ_I4, MKQ_I8 = 0, 1, 2, 3, 4
 MKQ_ACT_NONE, MKQ_ACT_GELU = 0, 1
 
 EXPORTS = [
     "mkq_status_string", "mkq_version", "mkq_quantize", "mkq_absmax_scale",
     "mkq_packed_weight_bytes", "mkq_pack_weights_int4", "mkq_pack_codes_int4",
     "mkq_unpack_weights_int4", "mkq_linear_int4_workspace_bytes", "mkq_linear_int4",
-    "mkq_quantize_int8", "mkq_pack_weights_int8", "mkq_linear_int8",
+    "mkq_quantize_int8", "mkq_pack_weights_int8", "mkq_linear_int8", "mkq_bert_layer_int8_workspace",
+    "mkq_bert_layer_int8", "mkq_layernorm_int8", "mkq_attention_int8",
     "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
     "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
 ]
@@ -96,6 +97,10 @@ def load() -> C.CDLL:
         "mkq_bert_layer_fp16": (ci, [C.POINTER(BertLayerParamsFp16), vp, vp, vp, sz, vp]),
         "mkq_layernorm": (ci, [vp, i64, i64, vp, vp, f32, vp, f32, vp, vp]),
         "mkq_attention": (ci, [vp, i64, i64, i64, i64, vp, f32, vp, vp]),
+        "mkq_layernorm_int8": (ci, [vp, i64, i64, vp, vp, f32, vp, f32, vp, vp]),
+        "mkq_attention_int8": (ci, [vp, i64, i64, i64, i64, vp, f32, vp, vp]),
+        "mkq_bert_layer_int8_workspace": (ci, [C.POINTER(BertLayerParams), C.POINTER(BertLayerWorkspaceLayout)]),
+        "mkq_bert_layer_int8": (ci, [C.POINTER(BertLayerParams), vp, ci, vp, vp, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -268,17 +273,18 @@ def mkq_pack_weights_int8(W, s_w_in=None, stream=None):
 
 
 def mkq_linear_int8(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, act: int = MKQ_ACT_NONE,
-                    residual=None, want_acc: bool = False, out=None, stream=None):
+                    residual=None, s_next: float = 0.0, want_acc: bool = False, out=None, stream=None):
     """The 8-bit linear: ``a`` int8 codes [M,K], ``Wq`` int8 codes [N,K]."""
     torch = _torch()
     M, K = a.shape
     N = Wq.shape[0]
     if out is None:
-        out = torch.empty((M, N), dtype=_torch_dtype(out_dtype), device=a.device)
+        out = torch.empty((M, N), dtype=torch.int8 if out_dtype == MKQ_I8 else _torch_dtype(out_dtype),
+                          device=a.device)
     acc = torch.empty((M, N), dtype=torch.int32, device=a.device) if want_acc else None
     epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
                    residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
-                   s_next=0.0, q_out=None, acc_out=acc.data_ptr() if acc is not None else None)
+                   s_next=float(s_next), q_out=None, acc_out=acc.data_ptr() if acc is not None else None)
     _check(load().mkq_linear_int8(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
                                   int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int8")
     return {"out": out, "acc": acc}
@@ -318,8 +324,31 @@ def mkq_attention(qkv, batch: int, seq: int, hidden: int, heads: int, s_next: fl
     return ctx, q
 
 
+def mkq_layernorm_int8(x, gamma, beta, eps: float, s_next: float, want_y: bool = True, stream=None):
+    torch = _torch()
+    M, D = x.shape
+    y = torch.empty((M, D), dtype=torch.float16, device=x.device) if want_y else None
+    q = torch.empty((M, D), dtype=torch.int8, device=x.device)
+    _check(load().mkq_layernorm_int8(_ptr(x), M, D, _ptr(gamma), _ptr(beta), float(eps), _ptr(y),
+                                     float(s_next), _ptr(q), _stream(stream)), "mkq_layernorm_int8")
+    return y, q
+
+
+def mkq_attention_int8(qkv, batch: int, seq: int, hidden: int, heads: int, s_next: float,
+                       want_ctx: bool = True, stream=None):
+    torch = _torch()
+    M = batch * seq
+    ctx = torch.empty((M, hidden), dtype=torch.float16, device=qkv.device) if want_ctx else None
+    q = torch.empty((M, hidden), dtype=torch.int8, device=qkv.device)
+    _check(load().mkq_attention_int8(_ptr(qkv), batch, seq, hidden, heads, _ptr(ctx), float(s_next),
+                                     _ptr(q), _stream(stream)), "mkq_attention_int8")
+    return ctx, q
+
+
 class BertLayerInt4:
     """Holds the device tensors of one W4A4 encoder layer and its parameter struct."""
+    _workspace_fn = "mkq_bert_layer_workspace"
+    _run_fn = "mkq_bert_layer_int4"
 
     def __init__(self, batch, seq, hidden, heads, ffn, packed: dict, sx: dict, ln: dict, ln_eps: float,
                  s_out_next: float = 0.0):
@@ -338,7 +367,7 @@ class BertLayerInt4:
         p.s_out_next = float(s_out_next)
         self.params = p
         self.layout = BertLayerWorkspaceLayout()
-        _check(load().mkq_bert_layer_workspace(C.byref(p), C.byref(self.layout)), "mkq_bert_layer_workspace")
+        _check(getattr(load(), self._workspace_fn)(C.byref(p), C.byref(self.layout)), self._workspace_fn)
         self.M, self.hidden, self.ffn = batch * seq, hidden, ffn
 
     def workspace_bytes(self) -> int:
@@ -348,11 +377,17 @@ class BertLayerInt4:
         torch = _torch()
         if h_out is None:
             h_out = torch.empty((self.M, self.hidden), dtype=torch.float16, device=h_in.device)
-        _check(load().mkq_bert_layer_int4(C.byref(self.params), _ptr(h_in), _dtype_code(h_in), _ptr(q_in),
-                                          _ptr(h_out), _ptr(q_out_next), _ptr(workspace),
-                                          workspace.numel() * workspace.element_size(), _stream(stream)),
-               "mkq_bert_layer_int4")
+        _check(getattr(load(), self._run_fn)(C.byref(self.params), _ptr(h_in), _dtype_code(h_in), _ptr(q_in),
+                                             _ptr(h_out), _ptr(q_out_next), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)),
+               self._run_fn)
         return h_out
+
+
+class BertLayerInt8(BertLayerInt4):
+    """The same layer W8A8: ``packed`` holds int8 weights from mkq_pack_weights_int8, code buffers are int8."""
+    _workspace_fn = "mkq_bert_layer_int8_workspace"
+    _run_fn = "mkq_bert_layer_int8"
 
 
 class BertLayerFp16:

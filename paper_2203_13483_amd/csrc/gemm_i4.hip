@@ -221,6 +221,17 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                         for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(h[e >> 1] >> (16 * (e & 1)));
                     }
                 }
+                if (out_dtype == MKQ_I8) {  // Eq. 1 at 8 bits, one byte per code
+                    int cd[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(y[e], p.s_next);
+                    uint8_t *qdst = (uint8_t *)p.out + o;
+                    if (vec_ok) {
+                        *reinterpret_cast<uint2 *>(qdst) = bytes8(cd);
+                    } else {
+                        for (int e = 0; e < nvalid; ++e) qdst[e] = (uint8_t)cd[e];
+                    }
+                }
                 if (out_dtype == MKQ_I4 || q_extra) {
                     // Eq. 1 on the binary32 value.  N is even and nb % 8 == 0, so o is even.
                     uint32_t packed = 0;
@@ -371,6 +382,11 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
                     for (int e = 0; e < 4; ++e)
                         hw[e] = (Epi::out == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1]) : pack2_bf16(y[2 * e], y[2 * e + 1]);
                     if (ok) *reinterpret_cast<uint4 *>((uint16_t *)p.out + o) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                } else if (Epi::out == MKQ_I8) {
+                    int cd[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(y[e], p.s_next);
+                    if (ok) *reinterpret_cast<uint2 *>((uint8_t *)p.out + o) = bytes8(cd);
                 } else {
                     uint32_t packed = 0;  // Eq. 1 on the binary32 value
 #pragma unroll
@@ -1163,7 +1179,7 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
 }
 
 // Epilogue combinations with a dedicated instantiation of the fast kernels.
-enum { EPI_F16 = 0, EPI_BF16, EPI_F32, EPI_F16_RES16, EPI_I4_GELU, EPI_I4, EPI_GENERIC };
+enum { EPI_F16 = 0, EPI_BF16, EPI_F32, EPI_F16_RES16, EPI_I4_GELU, EPI_I4, EPI_I8_GELU, EPI_GENERIC };
 
 static int classify_epilogue(const GemmI4Params &p)
 {
@@ -1176,6 +1192,7 @@ static int classify_epilogue(const GemmI4Params &p)
     if (p.out_dtype == MKQ_BF16 && !gelu) return EPI_BF16;
     if (p.out_dtype == MKQ_F32 && !gelu) return EPI_F32;
     if (p.out_dtype == MKQ_I4) return gelu ? EPI_I4_GELU : EPI_I4;
+    if (p.out_dtype == MKQ_I8 && gelu && !p.residual) return EPI_I8_GELU;
     return EPI_GENERIC;
 }
 
@@ -1199,6 +1216,23 @@ using DmaBig8 = GemmI4DmaCfg<256, 256, 2, 4, 64, 5>;   // 2 waves per SIMD, 128x
 using DmaMid = GemmI4DmaCfg<128, 128, 2, 2, 64, 4>;    // 64 KiB LDS: two workgroups per CU
 using DmaSmall = GemmI4DmaCfg<64, 64, 2, 2, 64, 8>;
 
+// Tile choice of the ring kernels, from sweeps over M = 256 .. 65536 at the BERT-base /
+// BERT-large shapes.  Large problems: 256x128 tiles, two workgroups per CU (18).  Few tiles:
+// 64x64 tiles, four workgroups per CU (27; the launch is latency-bound, parallelism wins).
+// In between, 128x128 tiles (12) when they fill their 512 slots in whole rounds, else
+// 128x64 (28; 1024 slots).
+static int choose_tiles(const GemmI4Params &p)
+{
+    const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
+    const int64_t t128x64 = ceil_div(p.M, 128) * ceil_div(p.N, 64);
+    const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
+    const double ops = 2.0 * p.M * p.N * p.K;
+    if (t256x128 >= 512 || (t256x128 >= 256 && ops >= 3e10)) return 18;
+    if (t128x64 < 256) return 27;
+    const int64_t rounds = ceil_div(t128, 512);
+    return (10 * t128 >= 9 * 512 * rounds) ? 12 : 28;
+}
+
 int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
 {
     int cfg = g_forced_cfg;
@@ -1210,22 +1244,7 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
         if (!dma_ok) {
             cfg = 3;
         } else {
-            // Tile choice, from sweeps over M = 256 .. 65536 at the BERT-base / BERT-large shapes.
-            // Large problems: 256x128 tiles, two workgroups per CU.  Few tiles: 64x64 tiles, four
-            // workgroups per CU (the launch is latency-bound, parallelism wins).  In between, 128x128
-            // tiles when they fill their 512 slots in whole rounds, else 128x64 (1024 slots).
-            const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
-            const int64_t t128x64 = ceil_div(p.M, 128) * ceil_div(p.N, 64);
-            const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
-            const double ops = 2.0 * p.M * p.N * p.K;
-            if (t256x128 >= 512 || (t256x128 >= 256 && ops >= 3e10)) {
-                cfg = 18;
-            } else if (t128x64 < 256) {
-                cfg = 27;
-            } else {
-                const int64_t rounds = ceil_div(t128, 512);
-                cfg = (10 * t128 >= 9 * 512 * rounds) ? 12 : 28;
-            }
+            cfg = choose_tiles(p);
         }
     }
     if (cfg >= 10 && !dma_ok) return MKQ_ERR_UNSUPPORTED;
@@ -1252,6 +1271,8 @@ static int launch_i8_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
     case EPI_F16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, false, false>, 8>(p, st);
     case EPI_BF16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_BF16, false, false>, 8>(p, st);
     case EPI_F32: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F32, false, false>, 8>(p, st);
+    case EPI_F16_RES16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, true, false>, 8>(p, st);
+    case EPI_I8_GELU: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I8, false, true>, 8>(p, st);
     default: return launch_gemm_i4_dma<Cfg, EpiGeneric, 8>(p, st);
     }
 }
@@ -1260,12 +1281,13 @@ int run_gemm_i8(const GemmI4Params &p, hipStream_t st)
 {
     if ((p.K % 64) != 0) return MKQ_ERR_UNSUPPORTED;
     int epi = classify_epilogue(p);
-    if (epi == EPI_F16_RES16 || epi == EPI_I4 || epi == EPI_I4_GELU) epi = EPI_GENERIC;
-    const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
-    const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
-    if (t256x128 >= 512) return launch_i8_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
-    if (t128 >= 128) return launch_i8_by_epilogue<DmaMid>(p, epi, st);
-    return launch_i8_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>>(p, epi, st);
+    if (epi == EPI_I4 || epi == EPI_I4_GELU) epi = EPI_GENERIC;
+    switch (choose_tiles(p)) {
+    case 18: return launch_i8_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
+    case 12: return launch_i8_by_epilogue<DmaMid>(p, epi, st);
+    case 28: return launch_i8_by_epilogue<GemmI4DmaCfg<128, 64, 2, 2, 64, 3>>(p, epi, st);
+    default: return launch_i8_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>>(p, epi, st);
+    }
 }
 
 }  // namespace mkq
@@ -1347,7 +1369,8 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
 {
     const bool want_acc = epi && epi->acc_out;
     if (out_dtype == MKQ_I4 || (epi && epi->q_out)) return MKQ_ERR_UNSUPPORTED;
-    if (out_dtype != MKQ_F32 && out_dtype != MKQ_F16 && out_dtype != MKQ_BF16) return MKQ_ERR_DTYPE;
+    if (out_dtype != MKQ_F32 && out_dtype != MKQ_F16 && out_dtype != MKQ_BF16 && out_dtype != MKQ_I8)
+        return MKQ_ERR_DTYPE;
     if (epi) {
         if (epi->act != MKQ_ACT_NONE && epi->act != MKQ_ACT_GELU) return MKQ_ERR_DTYPE;
         if (epi->residual && epi->residual_dtype != MKQ_F32 && epi->residual_dtype != MKQ_F16)
@@ -1355,6 +1378,7 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
     }
     if (M < 0 || N <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
+    if (out && out_dtype == MKQ_I8 && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
     if (M == 0) return MKQ_OK;
     if (!a || !Wq || !s_w) return MKQ_ERR_NULL;
     if (!out && !want_acc) return MKQ_ERR_NULL;
@@ -1374,7 +1398,7 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
     p.residual_dtype = epi ? epi->residual_dtype : MKQ_F32;
     p.act = epi ? epi->act : MKQ_ACT_NONE;
     p.out = out; p.out_dtype = out ? out_dtype : -1;
-    p.s_next = 1.0f;
+    p.s_next = (epi && out_dtype == MKQ_I8) ? epi->s_next : 1.0f;
     p.q_out = nullptr;
     p.acc_out = epi ? epi->acc_out : nullptr;
     p.acc_shift = 0;   // byte operands enter the MFMA as they are

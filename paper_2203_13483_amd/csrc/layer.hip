@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
                                                         const float *__restrict__ gamma,
                                                         const float *__restrict__ beta, float eps,
                                                         uint16_t *__restrict__ y, float s_next,
-                                                        uint32_t *__restrict__ q)
+                                                        uint32_t *__restrict__ q, int q_bits)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -67,7 +67,12 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
             if (y)
                 *reinterpret_cast<uint4 *>(y + (int64_t)row * D + c * 8) =
                     make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
-            if (q) {
+            if (q && q_bits == 8) {
+                int cd[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(o[e], s_next);
+                reinterpret_cast<uint2 *>(q)[(int64_t)row * chunks + c] = bytes8(cd);
+            } else if (q) {
                 uint32_t packed = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
@@ -88,7 +93,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
 template <int KT>
 __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restrict__ qkv, int seq, int hidden,
                                                         int heads, uint16_t *__restrict__ ctx, float s_next,
-                                                        uint8_t *__restrict__ qout)
+                                                        uint8_t *__restrict__ qout, int q_bits)
 {
     constexpr int DK = 64, SMAX = 32 * KT;
     __shared__ __attribute__((aligned(16))) uint8_t sQ[SMAX * 128];
@@ -203,7 +208,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
             if (ctx)
                 *reinterpret_cast<uint4 *>(ctx + off) =
                     make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
-            if (qout) {
+            if (qout && q_bits == 8) {
+                int cd[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(o[e], s_next);
+                *reinterpret_cast<uint2 *>(qout + off) = bytes8(cd);
+            } else if (qout) {
                 uint32_t packed = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
@@ -218,8 +228,8 @@ static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 using namespace mkq;
 
-extern "C" int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta,
-                             float eps, void *y, float s_next, uint8_t *q_out, void *stream)
+static int layernorm_run(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta, float eps,
+                         void *y, float s_next, void *q_out, int q_bits, void *stream)
 {
     if (M < 0 || D <= 0 || (D % 8) != 0) return MKQ_ERR_SHAPE;
     if (D > 8192) return MKQ_ERR_UNSUPPORTED;
@@ -235,7 +245,7 @@ extern "C" int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *g
     hipStream_t st = as_stream(stream);
 #define MKQ_LN(C)                                                                                       \
     layernorm_kernel<C><<<grid, 256, 0, st>>>((const uint16_t *)x, (int)M, (int)D, gamma, beta, eps, \
-                                              (uint16_t *)y, s_next, (uint32_t *)q_out)
+                                              (uint16_t *)y, s_next, (uint32_t *)q_out, q_bits)
     if (D <= 1024) MKQ_LN(2);
     else if (D <= 2048) MKQ_LN(4);
     else if (D <= 4096) MKQ_LN(8);
@@ -244,9 +254,22 @@ extern "C" int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *g
     return launch_status();
 }
 
-extern "C" int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
-                             void *ctx, float s_next, uint8_t *q_out, void *stream)
+extern "C" int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                             float eps, void *y, float s_next, uint8_t *q_out, void *stream)
 {
+    return layernorm_run(x, M, D, gamma, beta, eps, y, s_next, q_out, 4, stream);
+}
+
+extern "C" int mkq_layernorm_int8(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                                  float eps, void *y, float s_next, int8_t *q_out, void *stream)
+{
+    return layernorm_run(x, M, D, gamma, beta, eps, y, s_next, q_out, 8, stream);
+}
+
+static int attention_run(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads, void *ctx,
+                         float s_next, void *q_out_v, int q_bits, void *stream)
+{
+    uint8_t *q_out = (uint8_t *)q_out_v;
     if (batch < 0 || seq <= 0 || hidden <= 0 || heads <= 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
     if (q_out && !scale_ok(s_next)) return MKQ_ERR_SCALE;
     if (hidden / heads != 64 || (seq % 32) != 0 || seq > 128 || batch * heads > 0x7FFFFFFF)
@@ -258,12 +281,24 @@ extern "C" int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_
     hipStream_t st = as_stream(stream);
     const uint16_t *in = (const uint16_t *)qkv;
     switch (seq / 32) {
-    case 1: attention_kernel<1><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
-    case 2: attention_kernel<2><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
-    case 3: attention_kernel<3><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
-    default: attention_kernel<4><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out); break;
+    case 1: attention_kernel<1><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
+    case 2: attention_kernel<2><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
+    case 3: attention_kernel<3><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
+    default: attention_kernel<4><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
     }
     return launch_status();
+}
+
+extern "C" int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
+                             void *ctx, float s_next, uint8_t *q_out, void *stream)
+{
+    return attention_run(qkv, batch, seq, hidden, heads, ctx, s_next, q_out, 4, stream);
+}
+
+extern "C" int mkq_attention_int8(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
+                                  void *ctx, float s_next, int8_t *q_out, void *stream)
+{
+    return attention_run(qkv, batch, seq, hidden, heads, ctx, s_next, q_out, 8, stream);
 }
 
 // ---------------------------------------------------------------------------------
@@ -275,32 +310,55 @@ static int check_layer_dims(int64_t batch, int64_t seq, int64_t hidden, int64_t 
     return MKQ_OK;
 }
 
-extern "C" int mkq_bert_layer_workspace(const mkq_bert_layer_params *p, mkq_bert_layer_workspace_layout *L)
+// bits = 4: two codes per byte; bits = 8: one
+static int layer_workspace(const mkq_bert_layer_params *p, mkq_bert_layer_workspace_layout *L, int bits)
 {
     if (!p || !L) return MKQ_ERR_NULL;
     const int rc = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn);
     if (rc != MKQ_OK) return rc;
     const size_t M = (size_t)(p->batch * p->seq), H = (size_t)p->hidden, F = (size_t)p->ffn;
+    const size_t cpb = bits == 4 ? 2 : 1;  // codes per byte
     size_t o = 0;
-    L->c0 = o;  o += align256(M * H / 2);
+    L->c0 = o;  o += align256(M * H / cpb);
     L->qkv = o; o += align256(M * 3 * H * 2);
-    L->c1 = o;  o += align256(M * H / 2);
+    L->c1 = o;  o += align256(M * H / cpb);
     L->u = o;   o += align256(M * H * 2);
     L->h1 = o;  o += align256(M * H * 2);
-    L->c2 = o;  o += align256(M * H / 2);
-    L->c3 = o;  o += align256(M * F / 2);
+    L->c2 = o;  o += align256(M * H / cpb);
+    L->c3 = o;  o += align256(M * F / cpb);
     L->d = o;   o += align256(M * H * 2);
     L->total = o;
     return MKQ_OK;
 }
 
-extern "C" int mkq_bert_layer_int4(const mkq_bert_layer_params *p, const void *h_in, int h_dtype,
-                                   const uint8_t *q_in, void *h_out, uint8_t *q_out_next, void *workspace,
-                                   size_t workspace_bytes, void *stream)
+extern "C" int mkq_bert_layer_workspace(const mkq_bert_layer_params *p, mkq_bert_layer_workspace_layout *L)
+{
+    return layer_workspace(p, L, 4);
+}
+
+extern "C" int mkq_bert_layer_int8_workspace(const mkq_bert_layer_params *p, mkq_bert_layer_workspace_layout *L)
+{
+    return layer_workspace(p, L, 8);
+}
+
+// One linear of the layer at either width: codes in, `out` of out_dtype.
+static int layer_linear(int bits, const uint8_t *codes, float s_x, const uint8_t *Wq, const float *s_w,
+                        const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                        const mkq_epilogue *e, void *stream)
+{
+    if (bits == 8)
+        return mkq_linear_int8((const int8_t *)codes, s_x, (const int8_t *)Wq, s_w, bias, M, N, K, out, out_dtype, e,
+                               stream);
+    return mkq_linear_int4(codes, MKQ_I4, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, e, nullptr, 0, stream);
+}
+
+static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *h_in, int h_dtype,
+                          const uint8_t *q_in, void *h_out, uint8_t *q_out_next, void *workspace,
+                          size_t workspace_bytes, void *stream)
 {
     if (!p) return MKQ_ERR_NULL;
     mkq_bert_layer_workspace_layout L;
-    int rc = mkq_bert_layer_workspace(p, &L);
+    int rc = layer_workspace(p, &L, bits);
     if (rc != MKQ_OK) return rc;
     if (h_dtype != MKQ_F16 && h_dtype != MKQ_F32) return MKQ_ERR_DTYPE;
     if (!scale_ok(p->sx_qkv) || !scale_ok(p->sx_ao) || !scale_ok(p->sx_up) || !scale_ok(p->sx_down))
@@ -315,40 +373,56 @@ extern "C" int mkq_bert_layer_int4(const mkq_bert_layer_params *p, const void *h
     if (!workspace || workspace_bytes < L.total || !aligned16(workspace)) return MKQ_ERR_WORKSPACE;
 
     const int64_t M = p->batch * p->seq, H = p->hidden, F = p->ffn;
+    const int code_dtype = bits == 8 ? MKQ_I8 : MKQ_I4;
     uint8_t *ws = (uint8_t *)workspace;
     const uint8_t *c0 = q_in;
     if (!c0) {
-        rc = mkq_quantize(h_in, h_dtype, M, H, H, p->sx_qkv, ws + L.c0, stream);
+        rc = bits == 8 ? mkq_quantize_int8(h_in, h_dtype, M, H, H, p->sx_qkv, (int8_t *)(ws + L.c0), stream)
+                       : mkq_quantize(h_in, h_dtype, M, H, H, p->sx_qkv, ws + L.c0, stream);
         if (rc != MKQ_OK) return rc;
         c0 = ws + L.c0;
     }
     // q | k | v
-    rc = mkq_linear_int4(c0, MKQ_I4, p->sx_qkv, p->Wq_qkv, p->sw_qkv, p->b_qkv, M, 3 * H, H, ws + L.qkv,
-                         MKQ_F16, nullptr, nullptr, 0, stream);
+    rc = layer_linear(bits, c0, p->sx_qkv, p->Wq_qkv, p->sw_qkv, p->b_qkv, M, 3 * H, H, ws + L.qkv, MKQ_F16,
+                      nullptr, stream);
     if (rc != MKQ_OK) return rc;
     // attention context, re-quantized for the output projection
-    rc = mkq_attention(ws + L.qkv, p->batch, p->seq, H, p->heads, nullptr, p->sx_ao, ws + L.c1, stream);
+    rc = attention_run(ws + L.qkv, p->batch, p->seq, H, p->heads, nullptr, p->sx_ao, ws + L.c1, bits, stream);
     if (rc != MKQ_OK) return rc;
     mkq_epilogue e;
     e.act = MKQ_ACT_NONE; e.residual = h_in; e.residual_dtype = h_dtype; e.s_next = 0.0f;
     e.q_out = nullptr; e.acc_out = nullptr;
-    rc = mkq_linear_int4(ws + L.c1, MKQ_I4, p->sx_ao, p->Wq_ao, p->sw_ao, p->b_ao, M, H, H, ws + L.u, MKQ_F16,
-                         &e, nullptr, 0, stream);
+    rc = layer_linear(bits, ws + L.c1, p->sx_ao, p->Wq_ao, p->sw_ao, p->b_ao, M, H, H, ws + L.u, MKQ_F16, &e, stream);
     if (rc != MKQ_OK) return rc;
-    rc = mkq_layernorm(ws + L.u, M, H, p->ln1_gamma, p->ln1_beta, p->ln_eps, ws + L.h1, p->sx_up, ws + L.c2,
+    rc = layernorm_run(ws + L.u, M, H, p->ln1_gamma, p->ln1_beta, p->ln_eps, ws + L.h1, p->sx_up, ws + L.c2, bits,
                        stream);
     if (rc != MKQ_OK) return rc;
     // FFN up: GELU and re-quantization fused, only codes leave the kernel
     e.act = MKQ_ACT_GELU; e.residual = nullptr; e.s_next = p->sx_down;
-    rc = mkq_linear_int4(ws + L.c2, MKQ_I4, p->sx_up, p->Wq_up, p->sw_up, p->b_up, M, F, H, ws + L.c3, MKQ_I4,
-                         &e, nullptr, 0, stream);
+    rc = layer_linear(bits, ws + L.c2, p->sx_up, p->Wq_up, p->sw_up, p->b_up, M, F, H, ws + L.c3, code_dtype, &e,
+                      stream);
     if (rc != MKQ_OK) return rc;
     e.act = MKQ_ACT_NONE; e.residual = ws + L.h1; e.residual_dtype = MKQ_F16; e.s_next = 0.0f;
-    rc = mkq_linear_int4(ws + L.c3, MKQ_I4, p->sx_down, p->Wq_down, p->sw_down, p->b_down, M, H, F, ws + L.d,
-                         MKQ_F16, &e, nullptr, 0, stream);
+    rc = layer_linear(bits, ws + L.c3, p->sx_down, p->Wq_down, p->sw_down, p->b_down, M, H, F, ws + L.d, MKQ_F16, &e,
+                      stream);
     if (rc != MKQ_OK) return rc;
-    return mkq_layernorm(ws + L.d, M, H, p->ln2_gamma, p->ln2_beta, p->ln_eps, h_out,
-                         want_next ? p->s_out_next : 1.0f, want_next ? q_out_next : nullptr, stream);
+    return layernorm_run(ws + L.d, M, H, p->ln2_gamma, p->ln2_beta, p->ln_eps, h_out,
+                         want_next ? p->s_out_next : 1.0f, want_next ? q_out_next : nullptr, bits, stream);
+}
+
+extern "C" int mkq_bert_layer_int4(const mkq_bert_layer_params *p, const void *h_in, int h_dtype,
+                                   const uint8_t *q_in, void *h_out, uint8_t *q_out_next, void *workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    return bert_layer_run(4, p, h_in, h_dtype, q_in, h_out, q_out_next, workspace, workspace_bytes, stream);
+}
+
+extern "C" int mkq_bert_layer_int8(const mkq_bert_layer_params *p, const void *h_in, int h_dtype,
+                                   const int8_t *q_in, void *h_out, int8_t *q_out_next, void *workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    return bert_layer_run(8, p, h_in, h_dtype, (const uint8_t *)q_in, h_out, (uint8_t *)q_out_next, workspace,
+                          workspace_bytes, stream);
 }
 
 extern "C" size_t mkq_bert_layer_fp16_workspace_bytes(const mkq_bert_layer_params_fp16 *p)

@@ -31,6 +31,26 @@ __device__ __forceinline__ int quantize_code(float x, float s)
     return (int)__builtin_rintf(v);     // v_rndne_f32
 }
 
+// Eq. 1 at 8 bits: clamp to [-128, 127]; 8 codes as 8 bytes, element 0 lowest.
+__device__ __forceinline__ int quantize_code8(float x, float s)
+{
+    float v = x / s;
+    v = (v != v) ? 0.0f : v;
+    v = fminf(fmaxf(v, -128.0f), 127.0f);
+    return (int)__builtin_rintf(v);
+}
+
+__device__ __forceinline__ uint2 bytes8(const int (&c)[8])
+{
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        lo |= ((uint32_t)c[i] & 0xFFu) << (8 * i);
+        hi |= ((uint32_t)c[4 + i] & 0xFFu) << (8 * i);
+    }
+    return make_uint2(lo, hi);
+}
+
 __device__ __forceinline__ float wave_max(float v)
 {
 #pragma unroll

@@ -230,25 +230,6 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const uint32_t *__res
 // ---- 8-bit range (the comparison column of Table 2; mixed 4/8-bit models of section 4.2) ----
 // Eq. 1 with k = 8: clamp to [-128, 127], one byte per code, no packing.
 
-__device__ __forceinline__ int quantize_code8(float x, float s)
-{
-    float v = x / s;
-    v = (v != v) ? 0.0f : v;
-    v = fminf(fmaxf(v, -128.0f), 127.0f);
-    return (int)__builtin_rintf(v);
-}
-
-__device__ __forceinline__ uint2 bytes8(const int (&c)[8])
-{
-    uint32_t lo = 0, hi = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        lo |= ((uint32_t)c[i] & 0xFFu) << (8 * i);
-        hi |= ((uint32_t)c[4 + i] & 0xFFu) << (8 * i);
-    }
-    return make_uint2(lo, hi);
-}
-
 // x [M,K] (row stride ldx) -> int8 codes [M,K]; each thread turns 8 values into 8 bytes.
 template <typename T>
 __global__ __launch_bounds__(256) void quantize8_kernel(const T *__restrict__ x, int64_t M, int64_t K,
