@@ -352,6 +352,32 @@ def side_measurements(mkq, event_time):
             del a, out, g
         del ws
 
+    # The token counts of the paper's Table 2 (padding-free batches of 16 and 64 sentences): the four
+    # GEMMs of one BERT-base layer at exactly M valid tokens, binary16 out, in 4 bits, 8 bits and binary16
+    res["table2_token_counts"] = []
+    H, F = 768, 3072
+    for M in (440, 537, 681, 1691, 2011, 2298):
+        row = {"M": M, "int4_us": 0.0, "int8_us": 0.0, "fp16_us": 0.0}
+        for (K, N) in ((H, 3 * H), (H, H), (H, F), (F, H)):
+            o16 = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+            b32 = torch.zeros(N, device="cuda")
+            a4 = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
+            w4 = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
+            row["int4_us"] += graph_time(lambda: mkq.mkq_linear_int4(a4, 0.01, w4, sw, b32, N, K, mkq.MKQ_F16, out=o16),
+                                         repeats=5) * 1e6
+            a8 = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda")
+            w8 = torch.randint(-128, 128, (N, K), dtype=torch.int8, device="cuda")
+            row["int8_us"] += graph_time(lambda: mkq.mkq_linear_int8(a8, 0.01, w8, sw, b32, mkq.MKQ_F16, out=o16),
+                                         repeats=5) * 1e6
+            a16 = torch.randn(M, K, device="cuda", dtype=torch.float16)
+            w16 = torch.randn(N, K, device="cuda", dtype=torch.float16) * 0.02
+            row["fp16_us"] += graph_time(lambda: mkq.mkq_linear_fp16(a16, w16, b32, mkq.MKQ_F16, out=o16),
+                                         repeats=5) * 1e6
+        row["int8_over_int4"] = row["int8_us"] / row["int4_us"]
+        row["fp16_over_int4"] = row["fp16_us"] / row["int4_us"]
+        res["table2_token_counts"].append(row)
+
     # 12-layer BERT-base encoder, batch 32 x seq 128 (M = 4096), int4 vs binary16 layers
     try:
         res["encoder"] = encoder_latency(mkq, event_time)

@@ -92,6 +92,15 @@ def absmax_scale(x, per_row=False, qmax=QMAX):
     return out if per_row else float(out[0])
 
 
+def percentile_scale(x, top_ppm=100, qmax=QMAX):
+    """(s, T): T = k-th largest |x|, k = max(1, n*top_ppm // 10**6); s = T / qmax."""
+    x = _f32(x).ravel()
+    s, t = C.c_float(), C.c_float()
+    _check(lib().mkq_ref_percentile_scale(_p(x, C.c_float), C.c_int64(x.size), C.c_int64(top_ppm), int(qmax),
+                                          C.byref(s), C.byref(t)), "percentile_scale")
+    return float(s.value), float(t.value)
+
+
 def quantize_weights(W, s_w=None, qmin=QMIN, qmax=QMAX):
     """Per-output-channel weight quantization -> (codes [N,K] int8, s_w [N] f32)."""
     W = _f32(W)

@@ -104,6 +104,38 @@ int mkq_ref_absmax_scale(const float *x, int64_t M, int64_t K, int64_t ldx,
     return MKQ_REF_OK;
 }
 
+/* Percentile calibration of an activation step (section 3.1, third paragraph: sampled
+ * activations' absolute values are ranked and the value at the top 0.01 % becomes the
+ * initial clipping point).  Reading: T = the k-th largest of |x_i| with
+ * k = max(1, floor(n * top_ppm / 10^6)) (top_ppm = 100 for 0.01 %), s = T / qmax, and
+ * s = 1 when T = 0.  NaN counts as 0.  Written as the definition: sort, then index. */
+static int cmp_float_asc(const void *a, const void *b)
+{
+    float x = *(const float *)a, y = *(const float *)b;
+    return (x > y) - (x < y);
+}
+
+int mkq_ref_percentile_scale(const float *x, int64_t n, int64_t top_ppm, int qmax, float *s_out,
+                             float *t_out)
+{
+    if (!x || !s_out) return MKQ_REF_ERR_NULL;
+    if (n <= 0 || top_ppm < 0 || top_ppm > 1000000 || qmax <= 0) return MKQ_REF_ERR_SHAPE;
+    float *a = (float *)malloc(sizeof(float) * (size_t)n);
+    if (!a) return MKQ_REF_ERR_NULL;
+    for (int64_t i = 0; i < n; ++i) {
+        float v = fabsf(x[i]);
+        a[i] = (v != v) ? 0.0f : v;
+    }
+    qsort(a, (size_t)n, sizeof(float), cmp_float_asc);
+    int64_t k = n * top_ppm / 1000000;
+    if (k < 1) k = 1;
+    const float T = a[n - k];
+    free(a);
+    if (t_out) *t_out = T;
+    *s_out = (T > 0.0f) ? T / (float)qmax : 1.0f;
+    return MKQ_REF_OK;
+}
+
 /* Per-row (per output channel) weight quantization.  If s_w_in is NULL the
  * scales come from abs-max calibration, otherwise they are taken as given. */
 int mkq_ref_quantize_weights(const float *W, int64_t N, int64_t K,

@@ -152,3 +152,22 @@ def test_encoder_layer_full_batch_sampled_sequences(mkq):
     assert np.isfinite(out).all()
     # LayerNorm with gamma = 1, beta = 0: every output row has zero mean and unit variance
     assert np.abs(out.mean(axis=1)).max() < 2e-2 and np.abs(out.var(axis=1) - 1).max() < 5e-2
+
+
+@pytest.mark.parametrize("M", [440, 537, 681, 1691, 2011, 2298])
+@pytest.mark.parametrize("K,N", [(768, 2304), (3072, 768)])
+def test_padding_free_token_counts(mkq, M, K, N):
+    """The valid-token counts of the paper's Table 2 (section 5.4): ragged M, binary16 out, 4 and 8 bits."""
+    A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, seed=M)
+    b = np.random.default_rng(M).normal(0, 0.1, N).astype(np.float32)
+    r = mkq.mkq_linear_int4(mkq.mkq_pack_codes_int4(to_dev(A)), s_x, mkq.mkq_pack_codes_int4(to_dev(Wc)).reshape(-1),
+                            to_dev(s_w), to_dev(b), N, K, mkq.MKQ_F16, want_acc=True)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, b, out_dtype=oracle.F16)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    rng = np.random.default_rng(M + 1)
+    A8 = rng.integers(-128, 128, (M, K), dtype=np.int8)
+    W8 = rng.integers(-128, 128, (N, K), dtype=np.int8)
+    r = mkq.mkq_linear_int8(to_dev(A8), 0.01, to_dev(W8), to_dev(s_w), to_dev(b), mkq.MKQ_F16)
+    ref = oracle.linear_int4(A8, 0.01, W8, s_w, b, out_dtype=oracle.F16, qmin=-128, qmax=127)
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
