@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the large-M / small-M side measurements")
-    ap.add_argument("--only", choices=["large-m", "small-m"], default=None,
+    ap.add_argument("--only", choices=["large-m", "small-m", "calibration"], default=None,
                     help="run only that group of side measurements, eagerly and a few launches each (the form "
                          "that rocprofv3 --kernel-trace / --pmc runs are taken of); prints their JSON")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -256,6 +256,7 @@ def main():
 
 
 LARGE_M_SHAPES = [(16384, 1024, 4096), (16384, 4096, 1024), (16384, 768, 3072), (65536, 1024, 4096)]
+CALIBRATION_SHAPE = (16384, 4096)  # one activation tensor of the large-M sweep
 
 
 def profile_launches(mkq, which, launches=5):
@@ -275,6 +276,17 @@ def profile_launches(mkq, which, launches=5):
             done.append({"M": M, "K": K, "N": N, "launches": launches, "ops_per_launch": 2.0 * M * N * K,
                          "grid_threads": None})
             del a, w, out
+    elif which == "calibration":
+        M, K = CALIBRATION_SHAPE
+        x = torch.randn((M, K), dtype=torch.float16, device="cuda")
+        g = torch.empty(2, dtype=torch.float64, device="cuda")
+        s1 = torch.empty(1, dtype=torch.float32, device="cuda")
+        wsp = torch.empty(mkq.mkq_percentile_scale_workspace_bytes(), dtype=torch.uint8, device="cuda")
+        for _ in range(launches):
+            mkq.mkq_scale_gradients(x, 0.34, 4, g_out=g)
+            mkq.mkq_percentile_scale(x, 100, 4, s_out=s1, workspace=wsp)
+        torch.cuda.synchronize()
+        done.append({"M": M, "K": K, "x": "binary16", "launches": launches, "bytes_per_pass": 2 * M * K})
     else:
         for (K, N) in ((4096, 4096), (8192, 8192)):
             ws = [torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda") for _ in range(24)]
@@ -351,6 +363,23 @@ def side_measurements(mkq, event_time):
                                                f"{N * K // 2 >> 20} MiB weight each"})
             del a, out, g
         del ws
+
+    # Scale machinery (streaming reductions, HBM-bound): one read of x per pass
+    res["calibration"] = []
+    M, K = CALIBRATION_SHAPE
+    g = torch.empty(2, dtype=torch.float64, device="cuda")
+    s1 = torch.empty(1, dtype=torch.float32, device="cuda")
+    wsp = torch.empty(mkq.mkq_percentile_scale_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    for dt, nb in ((torch.float16, 2), (torch.float32, 4)):
+        x = torch.randn((M, K), dtype=dt, device="cuda")
+        t = graph_time(lambda: mkq.mkq_scale_gradients(x, 0.34, 4, g_out=g), rep=5, repeats=5)
+        res["calibration"].append({"op": "scale_gradients", "M": M, "K": K, "x_bytes": nb, "us": t * 1e6,
+                                   "GBps": nb * M * K / t / 1e9, "frac_hbm_peak": nb * M * K / t / 1e9 / HBM_PEAK_GBS})
+        t = graph_time(lambda: mkq.mkq_percentile_scale(x, 100, 4, s_out=s1, workspace=wsp), rep=5, repeats=5)
+        res["calibration"].append({"op": "percentile_scale (3 passes)", "M": M, "K": K, "x_bytes": nb, "us": t * 1e6,
+                                   "GBps": 3 * nb * M * K / t / 1e9,
+                                   "frac_hbm_peak": 3 * nb * M * K / t / 1e9 / HBM_PEAK_GBS})
+        del x
 
     # The token counts of the paper's Table 2 (padding-free batches of 16 and 64 sentences): the four
     # GEMMs of one BERT-base layer at exactly M valid tokens, binary16 out, in 4 bits, 8 bits and binary16

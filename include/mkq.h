@@ -65,6 +65,30 @@ int mkq_quantize(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, 
 int mkq_absmax_scale(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, int per_row,
                      float *s_out, void *stream);
 
+/* Scale gradients of one tensor under one step (section 4.1):
+ *     g_out[0] = sum_i ( round(x_i/s) - x_i/s )                 STE-based (4.1.1)
+ *     g_out[1] = 2 sum_i ( Q[x_i] - x_i ) round(x_i/s)          MSE-based (4.1.2)
+ * where round() is the code of Eq. 1 (clamp to the `bits`-bit range included, decided in
+ * binary32 like the quantizer) and Q[x] = s * code.  Terms and sums are binary64; the
+ * order of the partial sums is not fixed, so results agree to rounding only.
+ *   x      [M, K] of x_dtype (MKQ_F32 or MKQ_F16), row stride ldx; K % 8 == 0, M > 0
+ *   bits   4 or 8;  g_out  two doubles on the device (overwritten)
+ * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE (x_dtype, bits), HIP. */
+int mkq_scale_gradients(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, float s,
+                        int bits, double *g_out, void *stream);
+
+/* Percentile calibration of an activation step (section 3.1, third paragraph): the
+ * clipping point T is the k-th largest |x_i|, k = max(1, floor(M*K * top_ppm / 10^6))
+ * (top_ppm = 100 for the top 0.01 %), found exactly by radix selection over the bit
+ * patterns of |x| (three counting passes over x); s_out[0] = T / (2^(bits-1) - 1), or 1
+ * when T = 0.  NaN ranks as 0.  top_ppm = 0 gives abs-max calibration.
+ *   workspace  at least mkq_percentile_scale_workspace_bytes() bytes, 16-byte aligned
+ * M*K < 2^32.  Errors: NULL, SHAPE, ALIGN, DTYPE, WORKSPACE, UNSUPPORTED, HIP. */
+size_t mkq_percentile_scale_workspace_bytes(void);
+int mkq_percentile_scale(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                         int64_t top_ppm, int bits, float *s_out, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
 /* Offline weight preparation (Eq. 1 with one step per row = per output channel;
  * abs-max calibration when s_w_in is NULL).
  *   W        [N, K] binary32, row n = output channel n

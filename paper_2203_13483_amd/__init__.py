@@ -24,6 +24,7 @@ EXPORTS = [
     "mkq_unpack_weights_int4", "mkq_linear_int4_workspace_bytes", "mkq_linear_int4",
     "mkq_quantize_int8", "mkq_pack_weights_int8", "mkq_linear_int8", "mkq_bert_layer_int8_workspace",
     "mkq_bert_layer_int8", "mkq_layernorm_int8", "mkq_attention_int8",
+    "mkq_scale_gradients", "mkq_percentile_scale_workspace_bytes", "mkq_percentile_scale",
     "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
     "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
 ]
@@ -81,6 +82,9 @@ def load() -> C.CDLL:
         "mkq_quantize": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
         "mkq_absmax_scale": (ci, [vp, ci, i64, i64, i64, ci, vp, vp]),
         "mkq_packed_weight_bytes": (sz, [i64, i64]),
+        "mkq_scale_gradients": (ci, [vp, ci, i64, i64, i64, f32, ci, vp, vp]),
+        "mkq_percentile_scale_workspace_bytes": (sz, []),
+        "mkq_percentile_scale": (ci, [vp, ci, i64, i64, i64, i64, ci, vp, vp, sz, vp]),
         "mkq_pack_weights_int4": (ci, [vp, i64, i64, vp, vp, vp, vp]),
         "mkq_pack_codes_int4": (ci, [vp, i64, i64, vp, vp]),
         "mkq_unpack_weights_int4": (ci, [vp, i64, i64, vp, vp]),
@@ -176,6 +180,35 @@ def mkq_absmax_scale(x, per_row: bool = False, s_out=None, stream=None):
         s_out = torch.empty(M if per_row else 1, dtype=torch.float32, device=x.device)
     _check(load().mkq_absmax_scale(_ptr(x), _dtype_code(x), M, K, x.stride(0), int(per_row),
                                    _ptr(s_out), _stream(stream)), "mkq_absmax_scale")
+    return s_out
+
+
+def mkq_scale_gradients(x, s: float, bits: int = 4, g_out=None, stream=None):
+    """(STE-based, MSE-based) scale-gradient sums of x [M,K] under step s -> float64 tensor [2]."""
+    torch = _torch()
+    M, K = x.shape
+    if g_out is None:
+        g_out = torch.empty(2, dtype=torch.float64, device=x.device)
+    _check(load().mkq_scale_gradients(_ptr(x), _dtype_code(x), M, K, x.stride(0), float(s), int(bits), _ptr(g_out),
+                                      _stream(stream)), "mkq_scale_gradients")
+    return g_out
+
+
+def mkq_percentile_scale_workspace_bytes() -> int:
+    return int(load().mkq_percentile_scale_workspace_bytes())
+
+
+def mkq_percentile_scale(x, top_ppm: int = 100, bits: int = 4, s_out=None, workspace=None, stream=None):
+    """Step from the k-th largest |x| (k = max(1, n*top_ppm // 10**6)) -> float32 tensor [1]."""
+    torch = _torch()
+    M, K = x.shape
+    if s_out is None:
+        s_out = torch.empty(1, dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(mkq_percentile_scale_workspace_bytes(), dtype=torch.uint8, device=x.device)
+    _check(load().mkq_percentile_scale(_ptr(x), _dtype_code(x), M, K, x.stride(0), int(top_ppm), int(bits),
+                                       _ptr(s_out), _ptr(workspace), workspace.numel(), _stream(stream)),
+           "mkq_percentile_scale")
     return s_out
 
 

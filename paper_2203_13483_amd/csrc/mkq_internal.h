@@ -87,6 +87,31 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
+// 8 consecutive elements of a binary32 / binary16 row as binary32 (16-byte aligned address).
+template <typename T>
+__device__ __forceinline__ void load8(const T *p, float (&v)[8]);
+
+template <>
+__device__ __forceinline__ void load8<float>(const float *p, float (&v)[8])
+{
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+template <>
+__device__ __forceinline__ void load8<__half>(const __half *p, float (&v)[8])
+{
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+        v[2 * i + 1] = half_bits_to_float((uint16_t)(w[i] >> 16));
+    }
+}
+
 // Two binary32 values -> two 16-bit floats in one word (low half = a), round to
 // nearest even, one v_cvt_pk_* instruction each on gfx950.
 typedef float mkq_f2 __attribute__((ext_vector_type(2)));

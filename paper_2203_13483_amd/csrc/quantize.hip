@@ -16,30 +16,6 @@ __device__ __forceinline__ uint32_t pack8(const int (&c)[8])
     return w;
 }
 
-template <typename T>
-__device__ __forceinline__ void load8(const T *p, float (&v)[8]);
-
-template <>
-__device__ __forceinline__ void load8<float>(const float *p, float (&v)[8])
-{
-    const float4 a = *reinterpret_cast<const float4 *>(p);
-    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-
-template <>
-__device__ __forceinline__ void load8<__half>(const __half *p, float (&v)[8])
-{
-    const uint4 a = *reinterpret_cast<const uint4 *>(p);
-    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        v[2 * i] = half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
-        v[2 * i + 1] = half_bits_to_float((uint16_t)(w[i] >> 16));
-    }
-}
-
 // Eq. 1 with a per-tensor step: x [M,K] (row stride ldx) -> packed codes [M,K/2].
 template <typename T>
 __global__ __launch_bounds__(256) void quantize_kernel(const T *__restrict__ x, int64_t M, int64_t K,

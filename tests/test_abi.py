@@ -113,3 +113,26 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(mkq, "LIB_PATH", "/nonexistent/libmkq.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         mkq.load()
+
+
+def test_calibration_argument_errors(lib):
+    sg = lib.mkq_scale_gradients
+    assert sg(None, mkq.MKQ_F32, 4, 64, 64, 1.0, 4, P, None) == mkq.MKQ_ERR_NULL
+    assert sg(P, mkq.MKQ_F32, 4, 64, 64, 1.0, 4, None, None) == mkq.MKQ_ERR_NULL
+    assert sg(P, mkq.MKQ_BF16, 4, 64, 64, 1.0, 4, P, None) == mkq.MKQ_ERR_DTYPE
+    assert sg(P, mkq.MKQ_F32, 4, 64, 64, 1.0, 5, P, None) == mkq.MKQ_ERR_DTYPE
+    assert sg(P, mkq.MKQ_F32, 0, 64, 64, 1.0, 4, P, None) == mkq.MKQ_ERR_SHAPE
+    assert sg(P, mkq.MKQ_F32, 4, 60, 64, 1.0, 4, P, None) == mkq.MKQ_ERR_SHAPE
+    assert sg(P, mkq.MKQ_F32, 4, 64, 64, 0.0, 4, P, None) == mkq.MKQ_ERR_SCALE
+    assert sg(ODD, mkq.MKQ_F32, 4, 64, 64, 1.0, 4, P, None) == mkq.MKQ_ERR_ALIGN
+    ps = lib.mkq_percentile_scale
+    need = lib.mkq_percentile_scale_workspace_bytes()
+    assert need >= 3 * 2048 * 4
+    assert ps(None, mkq.MKQ_F32, 4, 64, 64, 100, 4, P, P, need, None) == mkq.MKQ_ERR_NULL
+    assert ps(P, mkq.MKQ_F32, 4, 64, 64, 100, 4, None, P, need, None) == mkq.MKQ_ERR_NULL
+    assert ps(P, mkq.MKQ_F32, 4, 64, 64, -1, 4, P, P, need, None) == mkq.MKQ_ERR_SHAPE
+    assert ps(P, mkq.MKQ_F32, 4, 64, 64, 1000001, 4, P, P, need, None) == mkq.MKQ_ERR_SHAPE
+    assert ps(P, mkq.MKQ_F32, 4, 64, 64, 100, 3, P, P, need, None) == mkq.MKQ_ERR_DTYPE
+    assert ps(P, mkq.MKQ_F32, 4, 64, 64, 100, 4, P, None, need, None) == mkq.MKQ_ERR_WORKSPACE
+    assert ps(P, mkq.MKQ_F32, 4, 64, 64, 100, 4, P, P, need - 1, None) == mkq.MKQ_ERR_WORKSPACE
+    assert ps(P, mkq.MKQ_F32, 1 << 20, 1 << 13, 1 << 13, 100, 4, P, P, need, None) == mkq.MKQ_ERR_UNSUPPORTED
