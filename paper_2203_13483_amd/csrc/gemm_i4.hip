@@ -597,7 +597,7 @@ struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
     // holds (at most 2 are useful), one wave of each per SIMD per WAVES / 4
     // two (small per-wave tiles: up to four, 128 registers each then) resident workgroups
     static constexpr int WGS_FIT = 160 * 1024 / (LDS_BYTES + WAVES * 512);
-    static constexpr int WGS_WANT = (Base::TM * Base::TN <= 2) ? 4 : 2;
+    static constexpr int WGS_WANT = (Base::TM * Base::TN <= 2) ? 4 : (Base::TM * Base::TN <= 4 ? 3 : 2);
     static constexpr int WGS_PER_CU = WGS_FIT < 1 ? 1 : (WGS_FIT < WGS_WANT ? WGS_FIT : WGS_WANT);
     static constexpr int WAVES_PER_EU = WGS_PER_CU * WAVES / 4;
     static_assert(COPIES % WAVES == 0, "copies must divide evenly over the waves");
@@ -1217,20 +1217,20 @@ using DmaMid = GemmI4DmaCfg<128, 128, 2, 2, 64, 4>;    // 64 KiB LDS: two workgr
 using DmaSmall = GemmI4DmaCfg<64, 64, 2, 2, 64, 8>;
 
 // Tile choice of the ring kernels, from sweeps over M = 256 .. 65536 at the BERT-base /
-// BERT-large shapes.  Large problems: 256x128 tiles, two workgroups per CU (18).  Few tiles:
-// 64x64 tiles, four workgroups per CU (27; the launch is latency-bound, parallelism wins).
-// In between, 128x128 tiles (12) when they fill their 512 slots in whole rounds, else
-// 128x64 (28; 1024 slots).
+// BERT-large shapes (and 4096^2, 8192^2 weights).  Very large problems: 256x128 tiles, two
+// workgroups per CU (18).  Few tiles: 64x64, four per CU (27; the launch is latency-bound,
+// parallelism wins).  In between 128x128 with a three-stage ring, three per CU (29), or
+// 128x64, four per CU (28), when 128x128 tiles would leave most of the 768 slots empty and
+// the k loop is short.
 static int choose_tiles(const GemmI4Params &p)
 {
     const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
     const int64_t t128x64 = ceil_div(p.M, 128) * ceil_div(p.N, 64);
     const int64_t t256x128 = ceil_div(p.M, 256) * ceil_div(p.N, 128);
     const double ops = 2.0 * p.M * p.N * p.K;
-    if (t256x128 >= 512 || (t256x128 >= 256 && ops >= 3e10)) return 18;
-    if (t128x64 < 256) return 27;
-    const int64_t rounds = ceil_div(t128, 512);
-    return (10 * t128 >= 9 * 512 * rounds) ? 12 : 28;
+    if (t256x128 >= 512 && ops >= 6e10) return 18;
+    if (t128x64 <= 256) return 27;
+    return (t128 >= 400 || p.K >= 2048) ? 29 : 28;
 }
 
 int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
@@ -1259,6 +1259,7 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     case 20: return launch_dma_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 32, 6>>(p, epi, st);
     case 27: return launch_dma_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>>(p, epi, st);
     case 28: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 64, 2, 2, 64, 3>>(p, epi, st);
+    case 29: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 3>>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }
@@ -1284,7 +1285,7 @@ int run_gemm_i8(const GemmI4Params &p, hipStream_t st)
     if (epi == EPI_I4 || epi == EPI_I4_GELU) epi = EPI_GENERIC;
     switch (choose_tiles(p)) {
     case 18: return launch_i8_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
-    case 12: return launch_i8_by_epilogue<DmaMid>(p, epi, st);
+    case 29: return launch_i8_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 3>>(p, epi, st);
     case 28: return launch_i8_by_epilogue<GemmI4DmaCfg<128, 64, 2, 2, 64, 3>>(p, epi, st);
     default: return launch_i8_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>>(p, epi, st);
     }

@@ -82,6 +82,96 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
     }
 }
 
+// The same for D <= 1024: one row per half wave (32 lanes, chunks lane, lane + 32, ...: D = 768
+// and 1024 divide evenly), so a lane has up to four 16-byte loads in flight and the two
+// reductions take five steps; gamma and beta are fetched before the reductions, not after.
+template <int MAXC>
+__global__ __launch_bounds__(256) void layernorm_half_kernel(const uint16_t *__restrict__ x, int M, int D,
+                                                             const float *__restrict__ gamma,
+                                                             const float *__restrict__ beta, float eps,
+                                                             uint16_t *__restrict__ y, float s_next,
+                                                             uint32_t *__restrict__ q, int q_bits)
+{
+    const int lane = threadIdx.x & 31;
+    const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (row >= M) return;
+    const int chunks = D / 8;
+    float v[MAXC][8], gg[MAXC][8], bb[MAXC][8];
+    uint4 raw[MAXC];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = lane + i * 32;
+        raw[i] = (c < chunks) ? *reinterpret_cast<const uint4 *>(x + (int64_t)row * D + c * 8) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = lane + i * 32;
+        const bool in = c < chunks;
+        const float4 g0 = (gamma && in) ? *reinterpret_cast<const float4 *>(gamma + c * 8) : make_float4(1, 1, 1, 1);
+        const float4 g1 = (gamma && in) ? *reinterpret_cast<const float4 *>(gamma + c * 8 + 4) : make_float4(1, 1, 1, 1);
+        const float4 b0 = (beta && in) ? *reinterpret_cast<const float4 *>(beta + c * 8) : make_float4(0, 0, 0, 0);
+        const float4 b1 = (beta && in) ? *reinterpret_cast<const float4 *>(beta + c * 8 + 4) : make_float4(0, 0, 0, 0);
+        gg[i][0] = g0.x; gg[i][1] = g0.y; gg[i][2] = g0.z; gg[i][3] = g0.w;
+        gg[i][4] = g1.x; gg[i][5] = g1.y; gg[i][6] = g1.z; gg[i][7] = g1.w;
+        bb[i][0] = b0.x; bb[i][1] = b0.y; bb[i][2] = b0.z; bb[i][3] = b0.w;
+        bb[i][4] = b1.x; bb[i][5] = b1.y; bb[i][6] = b1.z; bb[i][7] = b1.w;
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[i][2 * e] = half_bits_to_float((uint16_t)(w[e] & 0xFFFFu));
+            v[i][2 * e + 1] = half_bits_to_float((uint16_t)(w[e] >> 16));
+        }
+        // chunks past the row hold zeros and add nothing; the order of the sum is the one of
+        // the whole-wave kernel within a lane
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum += v[i][e];
+    }
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    const float mean = sum / (float)D;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        if (lane + i * 32 < chunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float d = v[i][e] - mean;
+                sq += d * d;
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+    const float rstd = 1.0f / sqrtf(sq / (float)D + eps);
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = lane + i * 32;
+        if (c < chunks) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (v[i][e] - mean) * rstd * gg[i][e] + bb[i][e];
+            if (y)
+                *reinterpret_cast<uint4 *>(y + (int64_t)row * D + c * 8) =
+                    make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
+            if (q && q_bits == 8) {
+                int cd[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(o[e], s_next);
+                reinterpret_cast<uint2 *>(q)[(int64_t)row * chunks + c] = bytes8(cd);
+            } else if (q) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
+                q[(int64_t)row * chunks + c] = packed;
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // Attention core for one (sequence, head) per workgroup: d_k = 64, seq = 32*KT <= 128.
 //   S^T = K Q^T / sqrt(d_k)   (MFMA "A" = keys in permuted row order, "B" = queries)
@@ -246,7 +336,17 @@ static int layernorm_run(const void *x, int64_t M, int64_t D, const float *gamma
 #define MKQ_LN(C)                                                                                       \
     layernorm_kernel<C><<<grid, 256, 0, st>>>((const uint16_t *)x, (int)M, (int)D, gamma, beta, eps, \
                                               (uint16_t *)y, s_next, (uint32_t *)q_out, q_bits)
-    if (D <= 1024) MKQ_LN(2);
+    if (D <= 1024 && M >= 2048) {
+        const unsigned grid8 = (unsigned)ceil_div(M, 8);
+#define MKQ_LNH(C)                                                                                             \
+    layernorm_half_kernel<C><<<grid8, 256, 0, st>>>((const uint16_t *)x, (int)M, (int)D, gamma, beta, eps, \
+                                                    (uint16_t *)y, s_next, (uint32_t *)q_out, q_bits)
+        if (D <= 256) MKQ_LNH(1);
+        else if (D <= 512) MKQ_LNH(2);
+        else if (D <= 768) MKQ_LNH(3);
+        else MKQ_LNH(4);
+#undef MKQ_LNH
+    } else if (D <= 1024) MKQ_LN(2);
     else if (D <= 2048) MKQ_LN(4);
     else if (D <= 4096) MKQ_LN(8);
     else MKQ_LN(16);

@@ -155,7 +155,7 @@ def test_deterministic_and_no_out_of_bounds_writes(mkq):
     assert np.array_equal(first, to_np(r2["out"]))
 
 
-ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 27, 28]
+ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29]
 
 
 @pytest.mark.parametrize("cfg", ALL_CFGS)
