@@ -386,7 +386,7 @@ def side_measurements(mkq, event_time):
     res["table2_token_counts"] = []
     H, F = 768, 3072
     for M in (440, 537, 681, 1691, 2011, 2298):
-        row = {"M": M, "int4_us": 0.0, "int8_us": 0.0, "fp16_us": 0.0}
+        row = {"M": M, "int4_us": 0.0, "int8_us": 0.0, "fp16_us": 0.0, "vendor_fp16_us": 0.0}
         for (K, N) in ((H, 3 * H), (H, H), (H, F), (F, H)):
             o16 = torch.empty((M, N), dtype=torch.float16, device="cuda")
             sw = torch.rand(N, device="cuda") * 0.049 + 0.001
@@ -403,8 +403,12 @@ def side_measurements(mkq, event_time):
             w16 = torch.randn(N, K, device="cuda", dtype=torch.float16) * 0.02
             row["fp16_us"] += graph_time(lambda: mkq.mkq_linear_fp16(a16, w16, b32, mkq.MKQ_F16, out=o16),
                                          repeats=5) * 1e6
+            b16 = b32.half()
+            torch.nn.functional.linear(a16, w16, b16)
+            row["vendor_fp16_us"] += graph_time(lambda: torch.nn.functional.linear(a16, w16, b16), repeats=5) * 1e6
         row["int8_over_int4"] = row["int8_us"] / row["int4_us"]
         row["fp16_over_int4"] = row["fp16_us"] / row["int4_us"]
+        row["vendor_fp16_over_int4"] = row["vendor_fp16_us"] / row["int4_us"]
         res["table2_token_counts"].append(row)
 
     # 12-layer BERT-base encoder, batch 32 x seq 128 (M = 4096), int4 vs binary16 layers

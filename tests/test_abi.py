@@ -136,3 +136,42 @@ def test_calibration_argument_errors(lib):
     assert ps(P, mkq.MKQ_F32, 4, 64, 64, 100, 4, P, None, need, None) == mkq.MKQ_ERR_WORKSPACE
     assert ps(P, mkq.MKQ_F32, 4, 64, 64, 100, 4, P, P, need - 1, None) == mkq.MKQ_ERR_WORKSPACE
     assert ps(P, mkq.MKQ_F32, 1 << 20, 1 << 13, 1 << 13, 100, 4, P, P, need, None) == mkq.MKQ_ERR_UNSUPPORTED
+
+
+def test_int8_argument_errors(lib):
+    q8 = lib.mkq_quantize_int8
+    assert q8(None, mkq.MKQ_F32, 4, 64, 64, 1.0, P, None) == mkq.MKQ_ERR_NULL
+    assert q8(P, mkq.MKQ_BF16, 4, 64, 64, 1.0, P, None) == mkq.MKQ_ERR_DTYPE
+    assert q8(P, mkq.MKQ_F32, 4, 40, 40, 1.0, P, None) == mkq.MKQ_ERR_SHAPE   # K % 16
+    assert q8(P, mkq.MKQ_F32, 4, 64, 64, -1.0, P, None) == mkq.MKQ_ERR_SCALE
+    assert q8(P, mkq.MKQ_F32, 0, 64, 64, 1.0, None, None) == mkq.MKQ_OK       # empty
+    pw = lib.mkq_pack_weights_int8
+    assert pw(None, 8, 64, None, P, P, None) == mkq.MKQ_ERR_NULL
+    assert pw(P, 8, 24, None, P, P, None) == mkq.MKQ_ERR_SHAPE
+    assert pw(P, 8, 64, None, P, ODD, None) == mkq.MKQ_ERR_ALIGN
+    lin = lib.mkq_linear_int8
+
+    def call(a=P, s_x=1.0, Wq=P, s_w=P, bias=None, M=8, N=64, K=64, out=P, out_dtype=mkq.MKQ_F16, epi=None):
+        return lin(a, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, epi, None)
+
+    assert call(a=None) == mkq.MKQ_ERR_NULL
+    assert call(out=None) == mkq.MKQ_ERR_NULL
+    assert call(K=96) == mkq.MKQ_ERR_SHAPE          # K % 64
+    assert call(K=65536) == mkq.MKQ_ERR_UNSUPPORTED
+    assert call(s_x=0.0) == mkq.MKQ_ERR_SCALE
+    assert call(out_dtype=9) == mkq.MKQ_ERR_DTYPE
+    assert call(out_dtype=mkq.MKQ_I4) == mkq.MKQ_ERR_UNSUPPORTED
+    assert call(out=ODD) == mkq.MKQ_ERR_ALIGN
+    assert call(M=0, a=None, out=None) == mkq.MKQ_OK
+    e = mkq.Epilogue(act=0, residual=None, residual_dtype=0, s_next=0.0, q_out=None, acc_out=None)
+    assert call(out_dtype=mkq.MKQ_I8, epi=C.byref(e)) == mkq.MKQ_ERR_SCALE   # code output needs s_next
+    e.q_out = 0x1000
+    assert call(epi=C.byref(e)) == mkq.MKQ_ERR_UNSUPPORTED
+    lay = mkq.BertLayerParams()
+    lay.batch, lay.seq, lay.hidden, lay.heads, lay.ffn = 2, 64, 128, 2, 256
+    L4, L8 = mkq.BertLayerWorkspaceLayout(), mkq.BertLayerWorkspaceLayout()
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L4)) == mkq.MKQ_OK
+    assert lib.mkq_bert_layer_int8_workspace(C.byref(lay), C.byref(L8)) == mkq.MKQ_OK
+    assert L8.qkv - L8.c0 == 2 * (L4.qkv - L4.c0) and L8.total > L4.total
+    lay.seq = 160
+    assert lib.mkq_bert_layer_int8_workspace(C.byref(lay), C.byref(L8)) == mkq.MKQ_ERR_UNSUPPORTED
