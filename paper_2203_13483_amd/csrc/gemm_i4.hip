@@ -617,29 +617,42 @@ constexpr int PRIO_SLICE_LOG2 = 15;
 // BITS = 4: nibble-packed operands, widened on the way to the matrix core.  BITS = 8: the
 // operands are int8 codes already (the W8A8 comparison path): same ring, same epilogues, a
 // 64-byte stage is then two k steps of 32 codes and nothing is widened.
-template <class Cfg, class Epi, int BITS>
-__global__ __launch_bounds__(Cfg::THREADS) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_EU, Cfg::WAVES_PER_EU)))
+// KSPLIT = 2 or 4: the workgroup is that many groups of Cfg::WAVES waves, each running this
+// pipeline with a ring of its own over one share of K (for launches with few tiles and a long
+// k loop, where a lone wave per SIMD is bound by its own instruction stream); the other groups'
+// partial accumulators meet the first group's in LDS at the end of a tile and the first group
+// runs the epilogue.
+template <class Cfg, class Epi, int BITS, int KSPLIT = 1>
+__global__ __launch_bounds__(Cfg::THREADS * KSPLIT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_EU, Cfg::WAVES_PER_EU)))
 void gemm_i4_dma_kernel(const GemmI4Params p)
 {
     static_assert(BITS == 4 || (BITS == 8 && Cfg::RB == 64), "8-bit operands use 64-byte stages");
+    static_assert(KSPLIT == 1 || ((KSPLIT == 2 || KSPLIT == 4) && Cfg::TM * Cfg::TN == 1),
+                  "the K split is built for 32x32 per wave");
     constexpr int BM = Cfg::BM, BN = Cfg::BN, RB = Cfg::RB, CH = Cfg::CH;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     constexpr int S = Cfg::S, LPW = Cfg::LPW;
     constexpr int ROUNDS = Cfg::ROUNDS, INFLIGHT = Cfg::INFLIGHT;
 
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
-
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_all[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave_all / Cfg::WAVES;   // K half of this wave's group (0 when KSPLIT == 1)
+    const int wave = wave_all % Cfg::WAVES;
+    // per group: the ring, then the scale / bias area of the row epilogue; after the groups: the
+    // exchange buffer of the K split (one 32x32 int32 tile per wave)
+    constexpr int GROUP_LDS = Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS;
+    uint8_t *const smem = smem_all + grp * GROUP_LDS;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
     const int fr = lane & 31, fh = lane >> 5;
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const int total_tiles = tiles_m * tiles_n;
     const int row_bytes = p.K * BITS / 8;
-    const int kt_count = row_bytes / RB;
+    const int kt_count = row_bytes / RB / KSPLIT;       // stages per tile of this group
+    const int k_first = grp * kt_count * RB;            // first byte of its K range in a row
     // Persistent workgroup: tiles blockIdx.x, blockIdx.x + gridDim.x, ... run through ONE
     // software pipeline, so a tile's first stages are in flight during the previous
     // tile's epilogue.
@@ -719,7 +732,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     set_tile(lt);
     // Per copy: one SALU op (M0 = LDS destination) and the copy itself.  The k offset
     // of the stage is folded into two base pointers that are advanced once per stage.
-    const uint8_t *a_k = p.A, *w_k = p.W;
+    const uint8_t *a_k = p.A + k_first, *w_k = p.W + k_first;
     const uint32_t lds_wave = lds0 + wave * (LPW * 1024);
     auto copy_one = [&](int slot, auto qc) {
         constexpr int q = decltype(qc)::value;
@@ -734,8 +747,8 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         w_k += RB;
         if (++lk == kt_count) {
             lk = 0;
-            a_k = p.A;
-            w_k = p.W;
+            a_k = p.A + k_first;
+            w_k = p.W + k_first;
             if (lt + (int)gridDim.x < total_tiles) {
                 lt += gridDim.x;
                 set_tile(lt);
@@ -897,7 +910,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     for (int s = 0; s < steps; s += 3 - ROUNDS) {
         if constexpr (Cfg::WGS_PER_CU == 2 && PRIO_SLICE_LOG2 > 0) tnow = __builtin_readcyclecounter();  // used at the boundary
         if constexpr (ROWS_EPI) {
-            if (ck == scale_stage) stage_scales(ct);
+            if (grp == 0 && ck == scale_stage) stage_scales(ct);
         }
         if constexpr (BITS == 8) {
             const int nbuf = next_slot(buf);
@@ -940,22 +953,46 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         if (ck == kt_count) {
             int tile_m, tile_n;
             tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
-            if constexpr (ROWS_EPI) {
-                // the slot of the stage just finished is idle until every wave has passed
-                // the next stage boundary: each wave shuffles through its share of it
-                const int done_slot = (buf == 0) ? S - 1 : buf - 1;
-                // the scale / bias copies have landed: only the stage copies issued after
-                // them (INFLIGHT stages, or one per stage of a shorter tile) may be in flight
-                if (kt_count >= INFLIGHT) wait_vmcnt<INFLIGHT * LPW>();
-                else wait_vmcnt<LPW>();
-                gemm_i4_epilogue_rows<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, lane,
-                                                smem + done_slot * Cfg::STAGE_BYTES +
-                                                    wave * EpiShuffle<Cfg>::REGION, sc_lds);
-            } else {
-                gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
+            if constexpr (KSPLIT > 1) {
+                // the other groups hand their partial sums over (16 registers per lane, 4 KiB per wave)
+                int *const xch = reinterpret_cast<int *>(smem_all + KSPLIT * GROUP_LDS) + wave * 1024 + lane * 4;
+                if (grp > 0) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<int4 *>(xch + (grp - 1) * (Cfg::WAVES * 1024) + q * 256) =
+                            make_int4(acc[0][0][4 * q], acc[0][0][4 * q + 1], acc[0][0][4 * q + 2], acc[0][0][4 * q + 3]);
+                }
+                lds_barrier();
+                if (grp == 0) {
+#pragma unroll
+                    for (int g = 0; g < KSPLIT - 1; ++g)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int4 t = *reinterpret_cast<const int4 *>(xch + g * (Cfg::WAVES * 1024) + q * 256);
+                            acc[0][0][4 * q] += t.x; acc[0][0][4 * q + 1] += t.y;
+                            acc[0][0][4 * q + 2] += t.z; acc[0][0][4 * q + 3] += t.w;
+                        }
+                }
+            }
+            if (grp == 0) {
+                if constexpr (ROWS_EPI) {
+                    // the slot of the stage just finished is idle until every wave has passed
+                    // the next stage boundary: each wave shuffles through its share of it
+                    const int done_slot = (buf == 0) ? S - 1 : buf - 1;
+                    // the scale / bias copies have landed: only the stage copies issued after
+                    // them (INFLIGHT stages, or one per stage of a shorter tile) may be in flight
+                    if (kt_count >= INFLIGHT) wait_vmcnt<INFLIGHT * LPW>();
+                    else wait_vmcnt<LPW>();
+                    gemm_i4_epilogue_rows<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, lane,
+                                                    smem + done_slot * Cfg::STAGE_BYTES +
+                                                        wave * EpiShuffle<Cfg>::REGION, sc_lds);
+                } else {
+                    gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
+                }
             }
             const bool interior = (tile_m + 1) * BM <= p.M && (tile_n + 1) * BN <= p.N;
-            stores_pending = (ASYNC_STORES && interior) ? INFLIGHT : 0;
+            // (a group without stores must not count them in its waits)
+            stores_pending = (ASYNC_STORES && interior && grp == 0) ? INFLIGHT : 0;
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
@@ -1145,22 +1182,25 @@ static int launch_gemm_i4(const GemmI4Params &p, hipStream_t st)
     return full ? launch_one<Cfg, true>(p, tiles, st) : launch_one<Cfg, false>(p, tiles, st);
 }
 
-template <class Cfg, class Epi, int BITS = 4>
+template <class Cfg, class Epi, int BITS = 4, int KSPLIT = 1>
 static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
     constexpr bool rows_epi = !Epi::generic && EpiShuffle<Cfg>::usable;
-    constexpr size_t lds_kernel = Cfg::LDS_BYTES + (rows_epi ? EpiShuffle<Cfg>::EXTRA_LDS : 0);
+    constexpr size_t lds_kernel =
+        KSPLIT == 1 ? Cfg::LDS_BYTES + (rows_epi ? EpiShuffle<Cfg>::EXTRA_LDS : 0)
+                    : KSPLIT * (Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS) + (KSPLIT - 1) * Cfg::WAVES * 4096;
+    static_assert(lds_kernel <= 160 * 1024, "LDS is 160 KiB per CU");
     const size_t lds = lds_kernel;
     static int wgs_per_cu = 0;  // per instantiation
     if (wgs_per_cu == 0) {
         if (lds > 65536 &&
-            hipFuncSetAttribute((const void *)gemm_i4_dma_kernel<Cfg, Epi, BITS>,
+            hipFuncSetAttribute((const void *)gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return MKQ_ERR_HIP;
         int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_dma_kernel<Cfg, Epi, BITS>, Cfg::THREADS, lds) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT>, Cfg::THREADS * KSPLIT, lds) !=
                 hipSuccess || occ < 1)
             return MKQ_ERR_HIP;
         if (g_num_cus == 0) {
@@ -1174,7 +1214,7 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
     }
     const int64_t resident = (int64_t)g_num_cus * wgs_per_cu;
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
-    gemm_i4_dma_kernel<Cfg, Epi, BITS><<<grid, Cfg::THREADS, lds, st>>>(p);
+    gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT><<<grid, Cfg::THREADS * KSPLIT, lds, st>>>(p);
     return launch_status();
 }
 
@@ -1207,6 +1247,21 @@ static int launch_dma_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st
     case EPI_I4_GELU: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, true>>(p, st);
     case EPI_I4: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, false>>(p, st);
     default: return launch_gemm_i4_dma<Cfg, EpiGeneric>(p, st);
+    }
+}
+
+// 64x64 tiles with the k loop split between two wave groups of one workgroup.
+template <class Cfg, int KS>
+static int launch_ksplit_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
+{
+    switch (epi) {
+    case EPI_F16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, false, false>, 4, KS>(p, st);
+    case EPI_BF16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_BF16, false, false>, 4, KS>(p, st);
+    case EPI_F32: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F32, false, false>, 4, KS>(p, st);
+    case EPI_F16_RES16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, true, false>, 4, KS>(p, st);
+    case EPI_I4_GELU: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, true>, 4, KS>(p, st);
+    case EPI_I4: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, false>, 4, KS>(p, st);
+    default: return launch_gemm_i4_dma<Cfg, EpiGeneric, 4, KS>(p, st);
     }
 }
 
@@ -1248,6 +1303,14 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
         }
     }
     if (cfg >= 10 && !dma_ok) return MKQ_ERR_UNSUPPORTED;
+    // few 64x64 tiles (at most two workgroups per CU) and a k loop long enough to halve: two wave
+    // groups per workgroup, with the deeper ring when the k loop is very long (four groups gain
+    // nothing over two: what is left is launch, first-load latency and the epilogue)
+    if (g_forced_cfg < 0 && cfg == 27 && (p.K % 256) == 0 && p.K >= 512) {
+        const int64_t t64 = ceil_div(p.M, 64) * ceil_div(p.N, 64);
+        if (t64 <= 512) cfg = (t64 <= 256 && p.K >= 6144) ? 31 : 33;
+    }
+    if ((cfg == 31 || cfg == 33) && (p.K % 256) != 0) return MKQ_ERR_UNSUPPORTED;
     switch (cfg) {
     case 2: return launch_gemm_i4<GemmI4Cfg<128, 128, 2, 2, 64>>(p, st);
     case 3: return launch_gemm_i4<GemmI4Cfg<64, 64, 2, 2, 64>>(p, st);
@@ -1260,6 +1323,8 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     case 27: return launch_dma_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>>(p, epi, st);
     case 28: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 64, 2, 2, 64, 3>>(p, epi, st);
     case 29: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 3>>(p, epi, st);
+    case 31: return launch_ksplit_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>, 2>(p, epi, st);
+    case 33: return launch_ksplit_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 3>, 2>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }

@@ -155,7 +155,8 @@ def test_deterministic_and_no_out_of_bounds_writes(mkq):
     assert np.array_equal(first, to_np(r2["out"]))
 
 
-ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29]
+ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29, 31, 33]
+K_GROUPS = {31: 2, 33: 2}  # configurations that split the k loop between wave groups
 
 
 @pytest.mark.parametrize("cfg", ALL_CFGS)
@@ -163,6 +164,8 @@ ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29]
 def test_every_tile_configuration(mkq, cfg, M, N, K):
     if cfg >= 10 and K % 128:
         pytest.skip("direct-to-LDS configurations need whole 64-byte k stages")
+    if cfg in K_GROUPS and K % (128 * K_GROUPS[cfg]):
+        pytest.skip("the k split needs a whole number of stages per wave group")
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg + M)
     ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.BF16, s_next=0.7)
     mkq.debug_set_gemm_config(cfg)
@@ -182,6 +185,7 @@ def test_single_stage_tiles_and_f16_residual(mkq, cfg, K):
     """K = 128 is one ring stage per tile (the shortest pipeline); with a binary16 residual
     and binary16 output the compile-time residual epilogue runs."""
     import torch
+    K *= K_GROUPS.get(cfg, 1)  # one and five stages per wave group
     M, N = 2100, 1160
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg + K)
     res = np.random.default_rng(K).normal(0, 1, (M, N)).astype(np.float16)
@@ -199,7 +203,7 @@ def test_single_stage_tiles_and_f16_residual(mkq, cfg, K):
 def test_persistent_pipeline_over_many_tiles(mkq, cfg, out_name):
     """More tiles than resident workgroups, ragged edges, the compile-time epilogues:
     the ring pipeline carries on across tiles and epilogue stores stay in flight."""
-    M, N, K = 8200, 2312, 256
+    M, N, K = 8200, 2312, 128 * max(2, K_GROUPS.get(cfg, 1))
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg)
     if out_name == "bf16":
         ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.BF16)
