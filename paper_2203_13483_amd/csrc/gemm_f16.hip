@@ -36,24 +36,31 @@ struct GemmF16Cfg {
     static_assert(S >= 3 && (S - 2) * LPW <= 63 && LDS_BYTES <= 160 * 1024, "ring limits");
 };
 
-template <class Cfg>
-__global__ __launch_bounds__(Cfg::THREADS) void gemm_f16_kernel(const GemmF16Params p)
+// KSPLIT = 2: two groups of Cfg::WAVES waves, each with a ring of its own over one half of K;
+// the second group's partial sums are added to the first group's through LDS before the
+// epilogue (for launches with few tiles, whose lone wave per SIMD is bound by its own
+// instruction stream).
+template <class Cfg, int KSPLIT>
+__global__ __launch_bounds__(Cfg::THREADS * KSPLIT) void gemm_f16_kernel(const GemmF16Params p)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, RB = Cfg::RB, CH = Cfg::CH;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, S = Cfg::S, LPW = Cfg::LPW, KSTEPS = Cfg::KSTEPS;
+    static_assert(KSPLIT == 1 || (KSPLIT == 2 && TM * TN == 1), "the K split is built for 32x32 per wave");
 
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
-
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_all[];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave_all / Cfg::WAVES, wave = wave_all % Cfg::WAVES;
+    uint8_t *const smem = smem_all + grp * Cfg::LDS_BYTES;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
     const int fr = lane & 31, fh = lane >> 5;
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const int total_tiles = tiles_m * tiles_n;
     const int row_bytes = p.K * 2;
-    const int kt_count = row_bytes / RB;
+    const int kt_count = row_bytes / RB / KSPLIT;
+    const int k_first = grp * kt_count * RB;
     const int my_tiles = (total_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
     const int steps = my_tiles * kt_count;
 
@@ -81,8 +88,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_f16_kernel(const GemmF16Par
     set_tile(lt);
     auto copy_next = [&](int slot) {  // always issues LPW copies (dummy re-fetch past the end)
         const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * (LPW * 1024);
-        const uint8_t *a_k = p.A + lk * RB;
-        const uint8_t *w_k = p.W + lk * RB;
+        const uint8_t *a_k = p.A + k_first + lk * RB;
+        const uint8_t *w_k = p.W + k_first + lk * RB;
 #pragma unroll
         for (int q = 0; q < LPW; ++q) {
             const bool is_a = (wave * LPW + q) * Cfg::ROWS_PER_COPY < BM;
@@ -229,7 +236,25 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_f16_kernel(const GemmF16Par
         mfma_step(IntC<1>{});
         buf = nbuf;
         if (++ck == kt_count) {
-            epilogue(ct);
+            if constexpr (KSPLIT == 2) {
+                float *const xch = reinterpret_cast<float *>(smem_all + KSPLIT * Cfg::LDS_BYTES) + wave * 1024 + lane * 4;
+                if (grp == 1) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<float4 *>(xch + q * 256) = make_float4(acc[0][0][4 * q], acc[0][0][4 * q + 1],
+                                                                                 acc[0][0][4 * q + 2], acc[0][0][4 * q + 3]);
+                }
+                lds_barrier();
+                if (grp == 0) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 t = *reinterpret_cast<const float4 *>(xch + q * 256);
+                        acc[0][0][4 * q] += t.x; acc[0][0][4 * q + 1] += t.y;
+                        acc[0][0][4 * q + 2] += t.z; acc[0][0][4 * q + 3] += t.w;
+                    }
+                }
+            }
+            if (grp == 0) epilogue(ct);
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
@@ -243,34 +268,39 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_f16_kernel(const GemmF16Par
     wait_vmcnt<0>();
 }
 
-template <class Cfg>
+template <class Cfg, int KSPLIT = 1>
 static int launch_gemm_f16(const GemmF16Params &p, hipStream_t st)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
-    const size_t lds = Cfg::LDS_BYTES;
+    constexpr size_t lds = KSPLIT * Cfg::LDS_BYTES + (KSPLIT - 1) * Cfg::WAVES * 4096;
+    static_assert(lds <= 160 * 1024, "LDS is 160 KiB per CU");
     static int resident = 0;
     if (resident == 0) {
-        if (lds > 65536 && hipFuncSetAttribute((const void *)gemm_f16_kernel<Cfg>,
+        if (lds > 65536 && hipFuncSetAttribute((const void *)gemm_f16_kernel<Cfg, KSPLIT>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return MKQ_ERR_HIP;
         int occ = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_f16_kernel<Cfg>, Cfg::THREADS, lds) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_f16_kernel<Cfg, KSPLIT>, Cfg::THREADS * KSPLIT, lds) != hipSuccess ||
             occ < 1 || hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
             return MKQ_ERR_HIP;
         resident = occ * cus;
     }
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
-    gemm_f16_kernel<Cfg><<<grid, Cfg::THREADS, lds, st>>>(p);
+    gemm_f16_kernel<Cfg, KSPLIT><<<grid, Cfg::THREADS * KSPLIT, lds, st>>>(p);
     return launch_status();
 }
 
 int run_gemm_f16(const GemmF16Params &p, hipStream_t st)
 {
     const int64_t t128 = ceil_div(p.M, 128) * ceil_div(p.N, 128);
+    const int64_t t64 = ceil_div(p.M, 64) * ceil_div(p.N, 64);
     if (t128 >= 192) return launch_gemm_f16<GemmF16Cfg<128, 128, 2, 2, 4>>(p, st);
-    return launch_gemm_f16<GemmF16Cfg<64, 64, 2, 2, 6>>(p, st);
+    // few tiles: 64x64; while there is at most one workgroup per CU the k loop is split between two
+    // wave groups (four-stage rings), beyond that a three-stage ring lets three workgroups share a CU
+    if (t64 <= 256 && (p.K % 128) == 0 && p.K >= 256) return launch_gemm_f16<GemmF16Cfg<64, 64, 2, 2, 4>, 2>(p, st);
+    return launch_gemm_f16<GemmF16Cfg<64, 64, 2, 2, 3>>(p, st);
 }
 
 }  // namespace mkq
