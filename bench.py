@@ -225,7 +225,7 @@ def main():
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(line.split(":")[1])
     roofline = {
-        "bound": "mfma", "kernel": "gemm_i4_dma_kernel (64x64 / 128x128 tiles chosen per shape, binary16-out epilogue)",
+        "bound": "mfma", "kernel": "gemm_i4_dma_kernel (64x64 tiles with a two-group k split / 128x64 tiles, chosen per shape; binary16-out epilogue)",
         "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS,
         "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
         "algorithmic_bytes_per_launch": sum(c.gemm_bytes for c in cases) / len(cases),
