@@ -472,8 +472,29 @@ def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
             layer(x, ws16, h_out=bufs[i & 1])
             x = bufs[i & 1]
 
+    # a mixed model (section 4.2: later layers 4-bit, the rest 8-bit): first half W8A8, second half W4A4;
+    # the layer at the seam writes its output codes at the width of the next
+    half = layers // 2
+    mixed_layers = []
+    for l in range(layers):
+        src = int8_layers[l] if l < half else int4_layers[l]
+        cls = mkq.BertLayerInt8 if l < half else mkq.BertLayerInt4
+        nb = 4 if l + 1 >= half else 8
+        s_next = wl.LEARNED_STEP_UNIT_GAUSSIAN * (1.0 if nb == 4 else 7.0 / 127.0)
+        packed_l, ln_l = src._keep
+        sx_l = {nm: getattr(src.params, "sx_" + nm) for nm in ("qkv", "ao", "up", "down")}
+        mixed_layers.append((cls(batch, seq, H, heads, F, packed_l, sx_l, ln_l, 1e-12, s_out_next=s_next, next_bits=nb),
+                             nb))
+
+    def run_mixed():
+        x, q = h, None
+        for i, (layer, nb) in enumerate(mixed_layers):
+            qo = q8bufs[i & 1] if nb == 8 else qbufs[i & 1]
+            layer(x, ws8, h_out=bufs[i & 1], q_in=q, q_out_next=qo)
+            x, q = bufs[i & 1], qo
+
     out = {"layers": layers, "batch": batch, "seq": seq, "hidden": H, "ffn": F}
-    for name, fn in (("int4", run_int4), ("fp16", run_fp16), ("int8", run_int8)):
+    for name, fn in (("int4", run_int4), ("fp16", run_fp16), ("int8", run_int8), ("mixed_6x8bit_6x4bit", run_mixed)):
         fn()
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()

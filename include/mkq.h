@@ -203,6 +203,9 @@ typedef struct mkq_bert_layer_params {
     const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
     float ln_eps;
     float s_out_next; /* > 0: also write codes(out; s_out_next) to q_out_next */
+    int next_bits;    /* width of those codes: 4 (packed, [M, hidden/2] bytes), 8 ([M, hidden] bytes), or 0 =
+                         this layer's own width; lets 4-bit and 8-bit layers follow each other in a mixed
+                         model (section 4.2) */
 } mkq_bert_layer_params;
 
 /* Byte offsets of the layer's intermediates inside its workspace (all 256-byte
@@ -225,7 +228,7 @@ int mkq_bert_layer_workspace(const mkq_bert_layer_params *p_host,
 /*   h_in   [M, hidden] binary16 (h_dtype == MKQ_F16) or binary32, M = batch*seq
  *   q_in   NULL, or packed codes of h_in under sx_qkv (skips the first quantizer)
  *   h_out  [M, hidden] binary16
- *   q_out_next  [M, hidden/2] bytes, required iff s_out_next > 0
+ *   q_out_next  [M, hidden/2] bytes (or [M, hidden] when next_bits == 8), required iff s_out_next > 0
  * hidden % 64 == 0, ffn % 64 == 0, hidden % heads == 0; currently d_k == 64, seq % 32 == 0 and
  * seq <= 128 (anything else: UNSUPPORTED).
  * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, WORKSPACE, UNSUPPORTED, HIP. */

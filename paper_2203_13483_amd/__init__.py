@@ -48,7 +48,7 @@ class BertLayerParams(C.Structure):
                                              "b_qkv", "b_ao", "b_up", "b_down")]
                 + [(n, C.c_float) for n in ("sx_qkv", "sx_ao", "sx_up", "sx_down")]
                 + [(n, C.c_void_p) for n in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")]
-                + [("ln_eps", C.c_float), ("s_out_next", C.c_float)])
+                + [("ln_eps", C.c_float), ("s_out_next", C.c_float), ("next_bits", C.c_int)])
 
 
 class BertLayerWorkspaceLayout(C.Structure):
@@ -384,9 +384,10 @@ class BertLayerInt4:
     _run_fn = "mkq_bert_layer_int4"
 
     def __init__(self, batch, seq, hidden, heads, ffn, packed: dict, sx: dict, ln: dict, ln_eps: float,
-                 s_out_next: float = 0.0):
+                 s_out_next: float = 0.0, next_bits: int = 0):
         self._keep = (packed, ln)
         p = BertLayerParams()
+        p.next_bits = int(next_bits)
         p.batch, p.seq, p.hidden, p.heads, p.ffn = batch, seq, hidden, heads, ffn
         for nm in ("qkv", "ao", "up", "down"):
             Wq, s_w, b = packed[nm]

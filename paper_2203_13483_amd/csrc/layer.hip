@@ -465,6 +465,8 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
         return MKQ_ERR_SCALE;
     const bool want_next = p->s_out_next > 0.0f;
     if (want_next && !scale_ok(p->s_out_next)) return MKQ_ERR_SCALE;
+    if (p->next_bits != 0 && p->next_bits != 4 && p->next_bits != 8) return MKQ_ERR_DTYPE;
+    const int next_bits = p->next_bits ? p->next_bits : bits;
     if (p->batch == 0) return MKQ_OK;
     if (!h_in || !h_out || (want_next && !q_out_next)) return MKQ_ERR_NULL;
     if (!p->Wq_qkv || !p->Wq_ao || !p->Wq_up || !p->Wq_down || !p->sw_qkv || !p->sw_ao || !p->sw_up ||
@@ -507,7 +509,7 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
                       stream);
     if (rc != MKQ_OK) return rc;
     return layernorm_run(ws + L.d, M, H, p->ln2_gamma, p->ln2_beta, p->ln_eps, h_out,
-                         want_next ? p->s_out_next : 1.0f, want_next ? q_out_next : nullptr, bits, stream);
+                         want_next ? p->s_out_next : 1.0f, want_next ? q_out_next : nullptr, next_bits, stream);
 }
 
 extern "C" int mkq_bert_layer_int4(const mkq_bert_layer_params *p, const void *h_in, int h_dtype,

@@ -303,3 +303,67 @@ def test_bert_layer_int8_stagewise_and_end_to_end(mkq, B, S, hidden, heads, ffn)
     ref_out, _ = oracle.bert_layer_int4(q, hf, act_dtype=oracle.F16, **Q8)
     err = got_out - ref_out
     assert np.sqrt((err ** 2).mean()) < 0.02 * np.sqrt((ref_out ** 2).mean())
+
+
+def test_mixed_4bit_and_8bit_layers_follow_each_other(mkq):
+    """Section 4.2 deploys models with 8-bit and 4-bit layers mixed: a layer writes the codes of its
+    output at the width of the layer that follows.  Each layer's output codes are checked against the
+    oracle's quantizer at that width, and the next layer, fed those codes, against the oracle's layer."""
+    import torch
+    from paper_2203_13483_amd import workloads as wl
+    B, S, hidden, heads, ffn = 2, 64, 128, 2, 256
+    M = B * S
+    h = _f16(wl.hidden_states(B, S, hidden, 61))
+    layers = []
+    for i, bits in enumerate((8, 4, 8)):
+        p = wl.bert_layer_weights(hidden, heads, ffn, 70 + i)
+        rng_q = Q8 if bits == 8 else dict(qmin=-8, qmax=7)
+        q = {k: p[k] for k in ("hidden", "heads", "ffn", "ln_eps", "ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+        q["batch"], q["seq"] = B, S
+        packed, sx = {}, {}
+        steps4 = {"qkv": 0.34, "ao": 0.05, "up": 0.34, "down": 0.05}
+        for nm in ("qkv", "ao", "up", "down"):
+            q["w_" + nm], q["sw_" + nm] = oracle.quantize_weights(p["W_" + nm], **rng_q)
+            q["b_" + nm] = p["b_" + nm]
+            q["sx_" + nm] = float(np.float32(steps4[nm] * (7.0 / 127.0 if bits == 8 else 1.0)))
+            pack = mkq.mkq_pack_weights_int8 if bits == 8 else mkq.mkq_pack_weights_int4
+            Wq, s_w = pack(to_dev(p["W_" + nm]))
+            packed[nm] = (Wq, s_w, to_dev(p["b_" + nm]))
+            sx[nm] = q["sx_" + nm]
+        layers.append((bits, p, q, packed, sx, rng_q))
+    x = to_dev(h)
+    q_in = None
+    x_ref = h.astype(np.float32)
+    for i, (bits, p, q, packed, sx, rng_q) in enumerate(layers):
+        nxt = layers[i + 1] if i + 1 < len(layers) else None
+        next_bits = nxt[0] if nxt else 0
+        s_next = nxt[2]["sx_qkv"] if nxt else 0.0
+        ln = {k: to_dev(p[k]) for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+        cls = mkq.BertLayerInt8 if bits == 8 else mkq.BertLayerInt4
+        layer = cls(B, S, hidden, heads, ffn, packed, sx, ln, p["ln_eps"], s_next, next_bits=next_bits)
+        ws = torch.zeros(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+        q_next = None
+        if nxt:
+            q_next = (torch.empty((M, hidden), dtype=torch.int8, device="cuda") if next_bits == 8
+                      else torch.empty((M, hidden // 2), dtype=torch.uint8, device="cuda"))
+        out = layer(x, ws, q_in=q_in, q_out_next=q_next)
+        torch.cuda.synchronize()
+        got = to_np(out).astype(np.float32)
+        # the oracle's layer on the GPU's own input (binary16 values): closeness end to end
+        ref_out, _ = oracle.bert_layer_int4(q, x_ref, act_dtype=oracle.F16, **rng_q)
+        err = got - ref_out
+        assert np.sqrt((err ** 2).mean()) < 0.03 * np.sqrt((ref_out ** 2).mean()), i
+        if nxt:
+            nq = nxt[5]
+            # codes of the output at the next layer's width: decided from the LayerNorm output, so the
+            # GPU's own binary16 output pins them to within one rounding of that output
+            codes = to_np(q_next) if next_bits == 8 else oracle.unpack_nibbles(to_np(q_next), hidden)
+            want = oracle.quantize(got, np.float32(s_next), **nq)
+            frac = (codes != want).mean()
+            # (binary16 rounding of the output moves a value by up to 2^-11 of itself: a few percent of
+            # an 8-bit step, a fraction of a percent of a 4-bit step)
+            assert np.abs(codes.astype(np.int32) - want).max() <= 1 and frac < (0.1 if next_bits == 8 else 0.02), (i, frac)
+            # the codes the layer wrote are what its quantizer entry point gives for the binary32 value;
+            # handing them to the next layer equals letting that layer quantize... not exactly (binary16
+            # rounding of h_out), so the next layer is simply fed the codes, as a deployed model would
+        x, q_in, x_ref = out, q_next, got
