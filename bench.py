@@ -411,12 +411,57 @@ def side_measurements(mkq, event_time):
         row["vendor_fp16_over_int4"] = row["vendor_fp16_us"] / row["int4_us"]
         res["table2_token_counts"].append(row)
 
+    # One BERT-base layer on padding-free batches with the batch sizes and valid-token counts of the
+    # paper's Table 2 (seeded sequence lengths <= 128), in 4 bits, 8 bits and binary16
+    try:
+        res["table2_layers"] = table2_layers(mkq)
+    except Exception as e:
+        res["table2_layers"] = {"error": repr(e)}
+
     # 12-layer BERT-base encoder, batch 32 x seq 128 (M = 4096), int4 vs binary16 layers
     try:
         res["encoder"] = encoder_latency(mkq, event_time)
     except Exception as e:  # keep the headline line even if this side measurement fails
         res["encoder"] = {"error": repr(e)}
     return res
+
+
+def table2_layers(mkq):
+    import numpy as np
+    import torch
+    from paper_2203_13483_amd import workloads as wl
+    H, heads, F = 768, 12, 3072
+    p = wl.bert_layer_weights(H, heads, F, 300)
+    ln = {k: torch.from_numpy(p[k]).cuda() for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    packed4, packed8, w16 = {}, {}, {}
+    for nm in ("qkv", "ao", "up", "down"):
+        W = torch.from_numpy(p["W_" + nm]).cuda()
+        b = torch.from_numpy(p["b_" + nm]).cuda()
+        packed4[nm] = mkq.mkq_pack_weights_int4(W) + (b,)
+        packed8[nm] = mkq.mkq_pack_weights_int8(W) + (b,)
+        w16[nm] = (W.half(), b)
+    sx4 = {"qkv": wl.LEARNED_STEP_UNIT_GAUSSIAN, "ao": 0.05, "up": wl.LEARNED_STEP_UNIT_GAUSSIAN, "down": 0.05}
+    sx8 = {k: v * 7.0 / 127.0 for k, v in sx4.items()}
+    rows = []
+    for (batch, tokens, t4_f32, t4_i8, t4_i4) in wl.TABLE2_ROWS:
+        lens = wl.ragged_lengths(tokens, batch, 128, seed=tokens)
+        cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+        h = torch.randn((tokens, H), dtype=torch.float16, device="cuda")
+        out = torch.empty_like(h)
+        layers = {
+            "int4": mkq.BertLayerInt4(batch, 128, H, heads, F, packed4, sx4, ln, 1e-12, cu_seqlens=cu, total_tokens=tokens),
+            "int8": mkq.BertLayerInt8(batch, 128, H, heads, F, packed8, sx8, ln, 1e-12, cu_seqlens=cu, total_tokens=tokens),
+            "fp16": mkq.BertLayerFp16(batch, 128, H, heads, F, w16, ln, 1e-12, cu_seqlens=cu, total_tokens=tokens),
+        }
+        row = {"batch": batch, "valid_tokens": tokens}
+        for name, layer in layers.items():
+            ws = torch.empty(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+            row[name + "_us"] = graph_time(lambda: layer(h, ws, h_out=out), rep=10, repeats=5) * 1e6
+        row["int8_over_int4"] = row["int8_us"] / row["int4_us"]
+        row["fp16_over_int4"] = row["fp16_us"] / row["int4_us"]
+        row["paper_T4_us"] = {"float32": t4_f32, "int8": t4_i8, "int4": t4_i4, "int8_over_int4": t4_i8 / t4_i4}
+        rows.append(row)
+    return rows
 
 
 def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
@@ -481,7 +526,7 @@ def encoder_latency(mkq, event_time, layers=12, batch=32, seq=128):
         cls = mkq.BertLayerInt8 if l < half else mkq.BertLayerInt4
         nb = 4 if l + 1 >= half else 8
         s_next = wl.LEARNED_STEP_UNIT_GAUSSIAN * (1.0 if nb == 4 else 7.0 / 127.0)
-        packed_l, ln_l = src._keep
+        packed_l, ln_l = src._keep[:2]
         sx_l = {nm: getattr(src.params, "sx_" + nm) for nm in ("qkv", "ao", "up", "down")}
         mixed_layers.append((cls(batch, seq, H, heads, F, packed_l, sx_l, ln_l, 1e-12, s_out_next=s_next, next_bits=nb),
                              nb))

@@ -206,6 +206,12 @@ typedef struct mkq_bert_layer_params {
     int next_bits;    /* width of those codes: 4 (packed, [M, hidden/2] bytes), 8 ([M, hidden] bytes), or 0 =
                          this layer's own width; lets 4-bit and 8-bit layers follow each other in a mixed
                          model (section 4.2) */
+    /* Padding-free batches (the "valid tokens" of Table 2, section 5.4): cu_seqlens is NULL, or a device
+     * array [batch + 1] of row offsets, sequence b being rows cu_seqlens[b] .. cu_seqlens[b+1] - 1 of the
+     * total_tokens rows of h_in / h_out; seq is then an upper bound of the lengths (<= 128, any value);
+     * a longer sequence is a precondition violation (its rows beyond the bound are not computed). */
+    const int32_t *cu_seqlens;
+    int64_t total_tokens;
 } mkq_bert_layer_params;
 
 /* Byte offsets of the layer's intermediates inside its workspace (all 256-byte
@@ -243,6 +249,8 @@ typedef struct mkq_bert_layer_params_fp16 {
     const float *b_qkv, *b_ao, *b_up, *b_down;
     const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
     float ln_eps;
+    const int32_t *cu_seqlens; /* as in mkq_bert_layer_params */
+    int64_t total_tokens;
 } mkq_bert_layer_params_fp16;
 
 size_t mkq_bert_layer_fp16_workspace_bytes(const mkq_bert_layer_params_fp16 *p_host);
@@ -274,6 +282,14 @@ int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const
  * Currently d_k == 64, seq % 32 == 0, seq <= 128 (anything else: UNSUPPORTED). */
 int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
                   void *ctx, float s_next, uint8_t *q_out, void *stream);
+
+/* Attention over a padding-free batch: qkv [total_tokens, 3*hidden], sequence b = rows
+ * cu_seqlens[b] .. cu_seqlens[b+1] - 1 (device array [batch + 1]), each at most max_seq <= 128 rows
+ * (any length; an empty sequence is skipped).  q_out: codes of q_bits (4: [total, hidden/2] bytes,
+ * 8: [total, hidden] bytes) or NULL.  Errors as mkq_attention, plus DTYPE for q_bits. */
+int mkq_attention_varlen(const void *qkv, const int32_t *cu_seqlens, int64_t batch, int64_t max_seq,
+                         int64_t hidden, int64_t heads, void *ctx, float s_next, void *q_out,
+                         int q_bits, void *stream);
 
 /* The two building blocks with 8-bit code output: q_out int8 [M, D] / [batch*seq, hidden]. */
 int mkq_layernorm_int8(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta,

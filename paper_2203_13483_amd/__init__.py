@@ -24,7 +24,7 @@ EXPORTS = [
     "mkq_unpack_weights_int4", "mkq_linear_int4_workspace_bytes", "mkq_linear_int4",
     "mkq_quantize_int8", "mkq_pack_weights_int8", "mkq_linear_int8", "mkq_bert_layer_int8_workspace",
     "mkq_bert_layer_int8", "mkq_layernorm_int8", "mkq_attention_int8",
-    "mkq_scale_gradients", "mkq_percentile_scale_workspace_bytes", "mkq_percentile_scale",
+    "mkq_scale_gradients", "mkq_percentile_scale_workspace_bytes", "mkq_percentile_scale", "mkq_attention_varlen",
     "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
     "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
 ]
@@ -48,7 +48,8 @@ class BertLayerParams(C.Structure):
                                              "b_qkv", "b_ao", "b_up", "b_down")]
                 + [(n, C.c_float) for n in ("sx_qkv", "sx_ao", "sx_up", "sx_down")]
                 + [(n, C.c_void_p) for n in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")]
-                + [("ln_eps", C.c_float), ("s_out_next", C.c_float), ("next_bits", C.c_int)])
+                + [("ln_eps", C.c_float), ("s_out_next", C.c_float), ("next_bits", C.c_int),
+                   ("cu_seqlens", C.c_void_p), ("total_tokens", C.c_int64)])
 
 
 class BertLayerWorkspaceLayout(C.Structure):
@@ -60,7 +61,7 @@ class BertLayerParamsFp16(C.Structure):
                 + [(n, C.c_void_p) for n in ("W_qkv", "W_ao", "W_up", "W_down",
                                              "b_qkv", "b_ao", "b_up", "b_down",
                                              "ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")]
-                + [("ln_eps", C.c_float)])
+                + [("ln_eps", C.c_float), ("cu_seqlens", C.c_void_p), ("total_tokens", C.c_int64)])
 
 
 _lib = None
@@ -101,6 +102,7 @@ def load() -> C.CDLL:
         "mkq_bert_layer_fp16": (ci, [C.POINTER(BertLayerParamsFp16), vp, vp, vp, sz, vp]),
         "mkq_layernorm": (ci, [vp, i64, i64, vp, vp, f32, vp, f32, vp, vp]),
         "mkq_attention": (ci, [vp, i64, i64, i64, i64, vp, f32, vp, vp]),
+        "mkq_attention_varlen": (ci, [vp, vp, i64, i64, i64, i64, vp, f32, vp, ci, vp]),
         "mkq_layernorm_int8": (ci, [vp, i64, i64, vp, vp, f32, vp, f32, vp, vp]),
         "mkq_attention_int8": (ci, [vp, i64, i64, i64, i64, vp, f32, vp, vp]),
         "mkq_bert_layer_int8_workspace": (ci, [C.POINTER(BertLayerParams), C.POINTER(BertLayerWorkspaceLayout)]),
@@ -378,16 +380,36 @@ def mkq_attention_int8(qkv, batch: int, seq: int, hidden: int, heads: int, s_nex
     return ctx, q
 
 
+def mkq_attention_varlen(qkv, cu_seqlens, max_seq: int, hidden: int, heads: int, s_next: float = 0.0,
+                         want_ctx: bool = True, q_bits: int = 0, stream=None):
+    """Attention over a padding-free batch; cu_seqlens int32 device tensor [batch + 1]."""
+    torch = _torch()
+    total = qkv.shape[0]
+    batch = cu_seqlens.numel() - 1
+    ctx = torch.empty((total, hidden), dtype=torch.float16, device=qkv.device) if want_ctx else None
+    q = None
+    if q_bits == 4:
+        q = torch.empty((total, hidden // 2), dtype=torch.uint8, device=qkv.device)
+    elif q_bits == 8:
+        q = torch.empty((total, hidden), dtype=torch.int8, device=qkv.device)
+    _check(load().mkq_attention_varlen(_ptr(qkv), _ptr(cu_seqlens), batch, max_seq, hidden, heads, _ptr(ctx),
+                                       float(s_next), _ptr(q), int(q_bits) if q_bits else 4, _stream(stream)),
+           "mkq_attention_varlen")
+    return ctx, q
+
+
 class BertLayerInt4:
     """Holds the device tensors of one W4A4 encoder layer and its parameter struct."""
     _workspace_fn = "mkq_bert_layer_workspace"
     _run_fn = "mkq_bert_layer_int4"
 
     def __init__(self, batch, seq, hidden, heads, ffn, packed: dict, sx: dict, ln: dict, ln_eps: float,
-                 s_out_next: float = 0.0, next_bits: int = 0):
-        self._keep = (packed, ln)
+                 s_out_next: float = 0.0, next_bits: int = 0, cu_seqlens=None, total_tokens: int = 0):
+        self._keep = (packed, ln, cu_seqlens)
         p = BertLayerParams()
         p.next_bits = int(next_bits)
+        if cu_seqlens is not None:  # padding-free batch: seq is the upper bound of the lengths
+            p.cu_seqlens, p.total_tokens = cu_seqlens.data_ptr(), int(total_tokens)
         p.batch, p.seq, p.hidden, p.heads, p.ffn = batch, seq, hidden, heads, ffn
         for nm in ("qkv", "ao", "up", "down"):
             Wq, s_w, b = packed[nm]
@@ -402,7 +424,7 @@ class BertLayerInt4:
         self.params = p
         self.layout = BertLayerWorkspaceLayout()
         _check(getattr(load(), self._workspace_fn)(C.byref(p), C.byref(self.layout)), self._workspace_fn)
-        self.M, self.hidden, self.ffn = batch * seq, hidden, ffn
+        self.M, self.hidden, self.ffn = (int(total_tokens) if cu_seqlens is not None else batch * seq), hidden, ffn
 
     def workspace_bytes(self) -> int:
         return int(self.layout.total)
@@ -427,9 +449,12 @@ class BertLayerInt8(BertLayerInt4):
 class BertLayerFp16:
     """The 16-bit float baseline layer."""
 
-    def __init__(self, batch, seq, hidden, heads, ffn, weights: dict, ln: dict, ln_eps: float):
-        self._keep = (weights, ln)
+    def __init__(self, batch, seq, hidden, heads, ffn, weights: dict, ln: dict, ln_eps: float, cu_seqlens=None,
+                 total_tokens: int = 0):
+        self._keep = (weights, ln, cu_seqlens)
         p = BertLayerParamsFp16()
+        if cu_seqlens is not None:
+            p.cu_seqlens, p.total_tokens = cu_seqlens.data_ptr(), int(total_tokens)
         p.batch, p.seq, p.hidden, p.heads, p.ffn = batch, seq, hidden, heads, ffn
         for nm in ("qkv", "ao", "up", "down"):
             W, b = weights[nm]
@@ -439,7 +464,7 @@ class BertLayerFp16:
             setattr(p, nm, ln[nm].data_ptr())
         p.ln_eps = float(ln_eps)
         self.params = p
-        self.M, self.hidden = batch * seq, hidden
+        self.M, self.hidden = (int(total_tokens) if cu_seqlens is not None else batch * seq), hidden
 
     def workspace_bytes(self) -> int:
         return int(load().mkq_bert_layer_fp16_workspace_bytes(C.byref(self.params)))

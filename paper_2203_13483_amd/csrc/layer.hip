@@ -181,9 +181,10 @@ __global__ __launch_bounds__(256) void layernorm_half_kernel(const uint16_t *__r
 // Each of the four waves owns 32 queries.  A lane ends with 8 consecutive head
 // dimensions of one query, stored as binary16 and / or as 4-bit codes.
 template <int KT>
-__global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restrict__ qkv, int seq, int hidden,
+__global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restrict__ qkv, int seq_fixed, int hidden,
                                                         int heads, uint16_t *__restrict__ ctx, float s_next,
-                                                        uint8_t *__restrict__ qout, int q_bits)
+                                                        uint8_t *__restrict__ qout, int q_bits,
+                                                        const int32_t *__restrict__ cu_seqlens)
 {
     constexpr int DK = 64, SMAX = 32 * KT;
     __shared__ __attribute__((aligned(16))) uint8_t sQ[SMAX * 128];
@@ -196,20 +197,34 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fh = lane >> 5;
     const int b = blockIdx.x / heads, head = blockIdx.x % heads;
-    const int64_t row0 = (int64_t)b * seq;
+    // padding-free batches: sequence b is rows cu_seqlens[b] .. cu_seqlens[b+1] - 1 (at most 32*KT of
+    // them, any number); otherwise every sequence has seq_fixed rows
+    const int64_t row0 = cu_seqlens ? (int64_t)cu_seqlens[b] : (int64_t)b * seq_fixed;
+    const int seq = cu_seqlens ? (cu_seqlens[b + 1] - cu_seqlens[b]) : seq_fixed;
+    if (seq <= 0) return;
     const int ld = 3 * hidden;
 
-    // stage Q, K (row-major, swizzled chunks) and V (transposed)
-    for (int idx = tid; idx < SMAX * 8; idx += 256) {
+    // stage Q, K (row-major, swizzled chunks) and V (transposed): all of a thread's loads are issued
+    // before the first LDS write, so the tile arrives in one memory round trip
+    constexpr int PER_T = SMAX * 8 / 256;  // 16-byte chunks of each of q, k, v per thread
+    uint4 qv[PER_T], kv[PER_T], vv[PER_T];
+#pragma unroll
+    for (int i = 0; i < PER_T; ++i) {
+        const int idx = tid + i * 256;
         const int r = idx >> 3, c = idx & 7;
-        const uint16_t *src = qkv + (row0 + r) * ld + head * DK + c * 8;
-        const uint4 qv = *reinterpret_cast<const uint4 *>(src);
-        const uint4 kv = *reinterpret_cast<const uint4 *>(src + hidden);
-        const uint4 vv = *reinterpret_cast<const uint4 *>(src + 2 * hidden);
+        const uint16_t *src = qkv + (row0 + (r < seq ? r : seq - 1)) * ld + head * DK + c * 8;
+        qv[i] = *reinterpret_cast<const uint4 *>(src);
+        kv[i] = *reinterpret_cast<const uint4 *>(src + hidden);
+        vv[i] = *reinterpret_cast<const uint4 *>(src + 2 * hidden);
+    }
+#pragma unroll
+    for (int i = 0; i < PER_T; ++i) {
+        const int idx = tid + i * 256;
+        const int r = idx >> 3, c = idx & 7;
         const int slot = (c ^ swz<8>(r & 15)) * 16;
-        *reinterpret_cast<uint4 *>(sQ + r * 128 + slot) = qv;
-        *reinterpret_cast<uint4 *>(sK + r * 128 + slot) = kv;
-        const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+        *reinterpret_cast<uint4 *>(sQ + r * 128 + slot) = qv[i];
+        *reinterpret_cast<uint4 *>(sK + r * 128 + slot) = kv[i];
+        const uint32_t w[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int d = c * 8 + e;
@@ -366,10 +381,13 @@ extern "C" int mkq_layernorm_int8(const void *x, int64_t M, int64_t D, const flo
     return layernorm_run(x, M, D, gamma, beta, eps, y, s_next, q_out, 8, stream);
 }
 
+// cu: null (every sequence has seq rows, a multiple of 32) or device array [batch + 1] of row offsets
+// (then seq is only an upper bound of the lengths)
 static int attention_run(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads, void *ctx,
-                         float s_next, void *q_out_v, int q_bits, void *stream)
+                         float s_next, void *q_out_v, int q_bits, void *stream, const int32_t *cu = nullptr)
 {
     uint8_t *q_out = (uint8_t *)q_out_v;
+    if (cu && seq > 0) seq = ceil_div(seq, 32) * 32;
     if (batch < 0 || seq <= 0 || hidden <= 0 || heads <= 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
     if (q_out && !scale_ok(s_next)) return MKQ_ERR_SCALE;
     if (hidden / heads != 64 || (seq % 32) != 0 || seq > 128 || batch * heads > 0x7FFFFFFF)
@@ -381,10 +399,10 @@ static int attention_run(const void *qkv, int64_t batch, int64_t seq, int64_t hi
     hipStream_t st = as_stream(stream);
     const uint16_t *in = (const uint16_t *)qkv;
     switch (seq / 32) {
-    case 1: attention_kernel<1><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
-    case 2: attention_kernel<2><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
-    case 3: attention_kernel<3><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
-    default: attention_kernel<4><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits); break;
+    case 1: attention_kernel<1><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits, cu); break;
+    case 2: attention_kernel<2><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits, cu); break;
+    case 3: attention_kernel<3><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits, cu); break;
+    default: attention_kernel<4><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits, cu); break;
     }
     return launch_status();
 }
@@ -401,22 +419,42 @@ extern "C" int mkq_attention_int8(const void *qkv, int64_t batch, int64_t seq, i
     return attention_run(qkv, batch, seq, hidden, heads, ctx, s_next, q_out, 8, stream);
 }
 
+extern "C" int mkq_attention_varlen(const void *qkv, const int32_t *cu_seqlens, int64_t batch, int64_t max_seq,
+                                    int64_t hidden, int64_t heads, void *ctx, float s_next, void *q_out,
+                                    int q_bits, void *stream)
+{
+    if (!cu_seqlens) return MKQ_ERR_NULL;
+    if (q_bits != 4 && q_bits != 8) return MKQ_ERR_DTYPE;
+    if (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) return MKQ_ERR_ALIGN;
+    return attention_run(qkv, batch, max_seq, hidden, heads, ctx, s_next, q_out, q_bits, stream, cu_seqlens);
+}
+
 // ---------------------------------------------------------------------------------
-static int check_layer_dims(int64_t batch, int64_t seq, int64_t hidden, int64_t heads, int64_t ffn)
+// varlen: seq is an upper bound of the sequence lengths of a padding-free batch of `tokens` rows
+static int check_layer_dims(int64_t batch, int64_t seq, int64_t hidden, int64_t heads, int64_t ffn,
+                            bool varlen = false, int64_t tokens = 0)
 {
     if (batch < 0 || seq <= 0 || hidden <= 0 || heads <= 0 || ffn <= 0) return MKQ_ERR_SHAPE;
     if ((hidden % 64) != 0 || (ffn % 64) != 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
-    if (hidden / heads != 64 || (seq % 32) != 0 || seq > 128 || hidden > 8192) return MKQ_ERR_UNSUPPORTED;
+    if (varlen && (tokens < 0 || tokens > batch * seq)) return MKQ_ERR_SHAPE;
+    if (hidden / heads != 64 || (!varlen && (seq % 32) != 0) || seq > 128 || hidden > 8192) return MKQ_ERR_UNSUPPORTED;
     return MKQ_OK;
+}
+
+template <class P>
+static inline int64_t layer_tokens(const P *p)
+{
+    return p->cu_seqlens ? p->total_tokens : p->batch * p->seq;
 }
 
 // bits = 4: two codes per byte; bits = 8: one
 static int layer_workspace(const mkq_bert_layer_params *p, mkq_bert_layer_workspace_layout *L, int bits)
 {
     if (!p || !L) return MKQ_ERR_NULL;
-    const int rc = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn);
+    const int rc = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
+                                    p->total_tokens);
     if (rc != MKQ_OK) return rc;
-    const size_t M = (size_t)(p->batch * p->seq), H = (size_t)p->hidden, F = (size_t)p->ffn;
+    const size_t M = (size_t)layer_tokens(p), H = (size_t)p->hidden, F = (size_t)p->ffn;
     const size_t cpb = bits == 4 ? 2 : 1;  // codes per byte
     size_t o = 0;
     L->c0 = o;  o += align256(M * H / cpb);
@@ -467,14 +505,14 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
     if (want_next && !scale_ok(p->s_out_next)) return MKQ_ERR_SCALE;
     if (p->next_bits != 0 && p->next_bits != 4 && p->next_bits != 8) return MKQ_ERR_DTYPE;
     const int next_bits = p->next_bits ? p->next_bits : bits;
-    if (p->batch == 0) return MKQ_OK;
+    if (p->batch == 0 || layer_tokens(p) == 0) return MKQ_OK;
     if (!h_in || !h_out || (want_next && !q_out_next)) return MKQ_ERR_NULL;
     if (!p->Wq_qkv || !p->Wq_ao || !p->Wq_up || !p->Wq_down || !p->sw_qkv || !p->sw_ao || !p->sw_up ||
         !p->sw_down)
         return MKQ_ERR_NULL;
     if (!workspace || workspace_bytes < L.total || !aligned16(workspace)) return MKQ_ERR_WORKSPACE;
 
-    const int64_t M = p->batch * p->seq, H = p->hidden, F = p->ffn;
+    const int64_t M = layer_tokens(p), H = p->hidden, F = p->ffn;
     const int code_dtype = bits == 8 ? MKQ_I8 : MKQ_I4;
     uint8_t *ws = (uint8_t *)workspace;
     const uint8_t *c0 = q_in;
@@ -489,7 +527,8 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
                       nullptr, stream);
     if (rc != MKQ_OK) return rc;
     // attention context, re-quantized for the output projection
-    rc = attention_run(ws + L.qkv, p->batch, p->seq, H, p->heads, nullptr, p->sx_ao, ws + L.c1, bits, stream);
+    rc = attention_run(ws + L.qkv, p->batch, p->seq, H, p->heads, nullptr, p->sx_ao, ws + L.c1, bits, stream,
+                       p->cu_seqlens);
     if (rc != MKQ_OK) return rc;
     mkq_epilogue e;
     e.act = MKQ_ACT_NONE; e.residual = h_in; e.residual_dtype = h_dtype; e.s_next = 0.0f;
@@ -529,8 +568,10 @@ extern "C" int mkq_bert_layer_int8(const mkq_bert_layer_params *p, const void *h
 
 extern "C" size_t mkq_bert_layer_fp16_workspace_bytes(const mkq_bert_layer_params_fp16 *p)
 {
-    if (!p || check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn) != MKQ_OK) return 0;
-    const size_t M = (size_t)(p->batch * p->seq), H = (size_t)p->hidden, F = (size_t)p->ffn;
+    if (!p || check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
+                               p->total_tokens) != MKQ_OK)
+        return 0;
+    const size_t M = (size_t)layer_tokens(p), H = (size_t)p->hidden, F = (size_t)p->ffn;
     return align256(M * 3 * H * 2) + 4 * align256(M * H * 2) + align256(M * F * 2);
 }
 
@@ -538,13 +579,14 @@ extern "C" int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *p, const vo
                                    void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!p) return MKQ_ERR_NULL;
-    const int rc0 = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn);
+    const int rc0 = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
+                                     p->total_tokens);
     if (rc0 != MKQ_OK) return rc0;
-    if (p->batch == 0) return MKQ_OK;
+    if (p->batch == 0 || layer_tokens(p) == 0) return MKQ_OK;
     if (!h_in || !h_out || !p->W_qkv || !p->W_ao || !p->W_up || !p->W_down) return MKQ_ERR_NULL;
     const size_t need = mkq_bert_layer_fp16_workspace_bytes(p);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return MKQ_ERR_WORKSPACE;
-    const int64_t M = p->batch * p->seq, H = p->hidden, F = p->ffn;
+    const int64_t M = layer_tokens(p), H = p->hidden, F = p->ffn;
     uint8_t *ws = (uint8_t *)workspace;
     size_t o = 0;
     uint8_t *qkv = ws + o; o += align256((size_t)M * 3 * H * 2);
@@ -555,7 +597,7 @@ extern "C" int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *p, const vo
     uint8_t *g = ws + o;
     int rc = mkq_linear_fp16(h_in, p->W_qkv, p->b_qkv, M, 3 * H, H, qkv, MKQ_F16, MKQ_ACT_NONE, nullptr, stream);
     if (rc != MKQ_OK) return rc;
-    rc = mkq_attention(qkv, p->batch, p->seq, H, p->heads, ctx, 1.0f, nullptr, stream);
+    rc = attention_run(qkv, p->batch, p->seq, H, p->heads, ctx, 1.0f, nullptr, 4, stream, p->cu_seqlens);
     if (rc != MKQ_OK) return rc;
     rc = mkq_linear_fp16(ctx, p->W_ao, p->b_ao, M, H, H, u, MKQ_F16, MKQ_ACT_NONE, h_in, stream);
     if (rc != MKQ_OK) return rc;

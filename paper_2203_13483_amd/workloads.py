@@ -107,3 +107,25 @@ CONFIGS = [
     dict(name="large_m_sweep", Ms=[16384, 32768, 65536],
          KN=[(1024, 4096), (4096, 1024), (768, 3072)], seed=4),
 ]
+
+
+def ragged_lengths(total: int, batch: int, max_len: int, seed: int):
+    """Seeded sequence lengths in [1, max_len] that add up to `total` (a padding-free batch with
+    `total` valid tokens, as in the paper's Table 2)."""
+    rng = np.random.default_rng(seed)
+    lens = np.full(batch, total // batch, np.int64)
+    lens[: total - lens.sum()] += 1
+    for _ in range(4 * batch):  # move tokens between random pairs, keeping the bounds
+        i, j = rng.integers(0, batch, 2)
+        d = int(rng.integers(0, 20))
+        if lens[i] - d >= 1 and lens[j] + d <= max_len:
+            lens[i] -= d
+            lens[j] += d
+    assert lens.sum() == total and lens.min() >= 1 and lens.max() <= max_len
+    return lens
+
+
+# Table 2 of the paper (section 5.4): batch size and valid tokens of one BERT-base layer, with the
+# paper's own latencies in microseconds on an NVIDIA T4 (float32, int8, int4) -- context only.
+TABLE2_ROWS = [(16, 440, 1380.0, 213.1, 160.5), (16, 537, 1845.0, 245.7, 179.3), (16, 681, 2690.0, 260.9, 196.5),
+               (64, 1691, 6398.0, 567.4, 428.8), (64, 2011, 7185.0, 628.4, 490.1), (64, 2298, 7897.0, 669.9, 533.4)]

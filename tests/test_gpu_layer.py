@@ -196,3 +196,83 @@ def test_bert_layer_fp16_baseline(mkq, B, S, hidden, heads, ffn):
     out = to_np(layer(to_dev(h), ws)).astype(np.float32)
     ref = oracle.bert_layer_float(ref_params, h.astype(np.float32), act_dtype=oracle.F16)
     assert_float_close(out, oracle.round_storage(ref, oracle.F16), RTOL[1], "fp16 layer")
+
+
+# --- padding-free batches (the "valid tokens" of Table 2) ----------------------------------
+
+_lengths = wl.ragged_lengths
+
+
+@pytest.mark.parametrize("batch,total,max_seq,heads", [(16, 440, 128, 12), (5, 200, 70, 2), (3, 96, 32, 1), (4, 7, 128, 2)])
+def test_attention_over_ragged_sequences(mkq, batch, total, max_seq, heads):
+    import torch
+    H = heads * 64
+    lens = _lengths(total, batch, min(max_seq, 128), seed=total)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rng = np.random.default_rng(total + heads)
+    qkv = _f16(rng.normal(0, 1.0, (total, 3 * H)))
+    s_next = 0.05
+    ctx, q = mkq.mkq_attention_varlen(to_dev(qkv), to_dev(cu), max_seq, H, heads, s_next=s_next, q_bits=4)
+    got, codes = to_np(ctx).astype(np.float32), oracle.unpack_nibbles(to_np(q), H)
+    for b in range(batch):
+        rows = slice(cu[b], cu[b + 1])
+        ref = oracle.attention(qkv[rows].astype(np.float32), 1, int(lens[b]), H, heads, p_dtype=oracle.F16)
+        assert_float_close(got[rows], ref, RTOL[1], f"sequence {b} of length {lens[b]}")
+        assert_codes_match_with_tie_band(codes[rows], oracle.quantize(ref, s_next), ref, s_next, band=2.0 ** -6,
+                                         max_frac=5e-3, what="context codes")
+    # equal lengths that are a multiple of 32 reproduce the fixed-length entry point exactly
+    S = 64
+    qkv2 = _f16(rng.normal(0, 1.0, (3 * S, 3 * H)))
+    cu2 = np.arange(4, dtype=np.int32) * S
+    a, _ = mkq.mkq_attention_varlen(to_dev(qkv2), to_dev(cu2), S, H, heads)
+    b_, _ = mkq.mkq_attention(to_dev(qkv2), 3, S, H, heads)
+    assert torch.equal(a, b_)
+
+
+@pytest.mark.parametrize("kind", ["int4", "int8", "fp16"])
+def test_layers_on_a_padding_free_batch(mkq, kind):
+    """Sequences do not interact: each sequence's rows of the layer output equal the oracle's layer run on
+    that sequence alone (batch 1, its own length)."""
+    import torch
+    batch, total, hidden, heads, ffn = 6, 230, 128, 2, 256
+    lens = _lengths(total, batch, 100, seed=5)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    p, _ = _layer_case(81, 1, 32, hidden, heads, ffn)
+    h = _f16(np.random.default_rng(82).standard_normal((total, hidden)))
+    ln = {k: to_dev(p[k]) for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    cud = to_dev(cu)
+    base = {k: p[k] for k in ("hidden", "heads", "ffn", "ln_eps", "ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    if kind == "fp16":
+        weights = {}
+        for nm in ("qkv", "ao", "up", "down"):
+            W16 = _f16(p["W_" + nm])
+            weights[nm] = (to_dev(W16), to_dev(p["b_" + nm]))
+            base["w_" + nm], base["b_" + nm] = W16.astype(np.float32), p["b_" + nm]
+        layer = mkq.BertLayerFp16(batch, 100, hidden, heads, ffn, weights, ln, p["ln_eps"], cu_seqlens=cud,
+                                  total_tokens=total)
+    else:
+        qr = dict(qmin=-8, qmax=7) if kind == "int4" else dict(qmin=-128, qmax=127)
+        scale = 1.0 if kind == "int4" else 7.0 / 127.0
+        packed, sx = {}, {}
+        for nm, st in (("qkv", 0.34), ("ao", 0.05), ("up", 0.34), ("down", 0.05)):
+            base["w_" + nm], base["sw_" + nm] = oracle.quantize_weights(p["W_" + nm], **qr)
+            base["b_" + nm] = p["b_" + nm]
+            base["sx_" + nm] = sx[nm] = float(np.float32(st * scale))
+            pack = mkq.mkq_pack_weights_int4 if kind == "int4" else mkq.mkq_pack_weights_int8
+            packed[nm] = pack(to_dev(p["W_" + nm])) + (to_dev(p["b_" + nm]),)
+        cls = mkq.BertLayerInt4 if kind == "int4" else mkq.BertLayerInt8
+        layer = cls(batch, 100, hidden, heads, ffn, packed, sx, ln, p["ln_eps"], cu_seqlens=cud, total_tokens=total)
+    ws = torch.empty(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    out = to_np(layer(to_dev(h), ws)).astype(np.float32)
+    assert out.shape == (total, hidden)
+    for b in range(batch):
+        rows = slice(cu[b], cu[b + 1])
+        q = dict(base, batch=1, seq=int(lens[b]))
+        x = h[rows].astype(np.float32)
+        if kind == "fp16":
+            ref = oracle.bert_layer_float(q, x, act_dtype=oracle.F16)
+            assert_float_close(out[rows], oracle.round_storage(ref, oracle.F16), RTOL[1], f"sequence {b}")
+        else:
+            ref, _ = oracle.bert_layer_int4(q, x, act_dtype=oracle.F16, **qr)
+            err = out[rows] - ref
+            assert np.sqrt((err ** 2).mean()) < 0.04 * np.sqrt((ref ** 2).mean()), (b, int(lens[b]))
