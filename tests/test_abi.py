@@ -175,3 +175,24 @@ def test_int8_argument_errors(lib):
     assert L8.qkv - L8.c0 == 2 * (L4.qkv - L4.c0) and L8.total > L4.total
     lay.seq = 160
     assert lib.mkq_bert_layer_int8_workspace(C.byref(lay), C.byref(L8)) == mkq.MKQ_ERR_UNSUPPORTED
+
+
+def test_padding_free_argument_errors(lib):
+    av = lib.mkq_attention_varlen
+    assert av(P, None, 2, 64, 128, 2, P, 1.0, None, 4, None) == mkq.MKQ_ERR_NULL      # cu_seqlens
+    assert av(P, P, 2, 64, 128, 2, P, 1.0, None, 5, None) == mkq.MKQ_ERR_DTYPE        # q_bits
+    assert av(P, P, 2, 200, 128, 2, P, 1.0, None, 4, None) == mkq.MKQ_ERR_UNSUPPORTED  # max_seq > 128
+    assert av(P, P, 2, 70, 128, 3, P, 1.0, None, 4, None) == mkq.MKQ_ERR_SHAPE        # hidden % heads
+    assert av(P, P, 0, 70, 128, 2, None, 1.0, None, 4, None) == mkq.MKQ_OK            # empty batch
+    lay = mkq.BertLayerParams()
+    lay.batch, lay.seq, lay.hidden, lay.heads, lay.ffn = 4, 100, 128, 2, 256          # seq = bound, any value <= 128
+    L = mkq.BertLayerWorkspaceLayout()
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L)) == mkq.MKQ_ERR_UNSUPPORTED  # fixed length: % 32
+    lay.cu_seqlens, lay.total_tokens = 0x1000, 230
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L)) == mkq.MKQ_OK
+    assert L.qkv - L.c0 == 256 * ((230 * 128 // 2 + 255) // 256)
+    lay.total_tokens = 401                                                            # more than batch * seq
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L)) == mkq.MKQ_ERR_SHAPE
+    lay.total_tokens, lay.next_bits = 230, 5
+    assert lib.mkq_bert_layer_int4(C.byref(lay), P, mkq.MKQ_F16, None, P, None, P, 1 << 30, None) in (
+        mkq.MKQ_ERR_SCALE, mkq.MKQ_ERR_DTYPE)
