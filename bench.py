@@ -330,6 +330,14 @@ def side_measurements(mkq, event_time):
             row["vendor_int8_us"] = graph_time(lambda: torch._int_mm(a8, w8.t())) * 1e6
         except Exception:
             row["vendor_int8_us"] = None
+        # the experimental 6-bit float route of the same 4-bit linear (E3M2 containers, exact integers)
+        c8 = torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda")
+        a6 = mkq.mkq_pack_codes_e3m2(c8)
+        del c8
+        w6 = mkq.mkq_pack_codes_e3m2(torch.randint(-8, 8, (N, K), dtype=torch.int8, device="cuda"))
+        row["e3m2_route_us"] = graph_time(lambda: mkq.mkq_linear_int4_e3m2(a6, 0.01, w6, sw, None, mkq.MKQ_BF16,
+                                                                           out=out)) * 1e6
+        del a6, w6
         a16 = torch.randn((M, K), dtype=torch.bfloat16, device="cuda")
         w16 = torch.randn((N, K), dtype=torch.bfloat16, device="cuda")
         torch.mm(a16, w16.t(), out=out)

@@ -172,6 +172,26 @@ int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s
                     const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
                     const mkq_epilogue *epi, void *stream);
 
+/* Experimental: the 4-bit linear through the 6-bit float path of the matrix core.  Every code in [-8, 8]
+ * is an E3M2 value (sign, 3 exponent bits with bias 3, 2 mantissa bits), products and sums of codes are
+ * exact in binary32 while |sum| < 2^24, so the result is the same exact integer contraction as
+ * mkq_linear_int4 -- with no widening and half the matrix instructions per k.  Operands are "containers":
+ * 6 bits per code, rows of 3K/4 bytes made of groups of 64 codes = 48 bytes; the 32 codes of half h of a
+ * group are a 192-bit little-endian stream (code i in bits [6i, 6i + 6)) stored as bytes [16h, 16h + 16)
+ * and then [32 + 8h, 40 + 8h) of the group.  K % 64 == 0, K < 262144.  The quantizer and the weight preparation are those of
+ * mkq_quantize / mkq_pack_weights_int4 (Eq. 1, per-tensor / per-channel steps), written as containers;
+ * mkq_pack_codes_e3m2 takes int8 codes in [-8, 8].  mkq_linear_int4_e3m2: arguments and epilogue as
+ * mkq_linear_int4 with both operands given as containers (no workspace).
+ * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, UNSUPPORTED, HIP. */
+int mkq_quantize_e3m2(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, float s_x,
+                      uint8_t *q_out, void *stream);
+int mkq_pack_codes_e3m2(const int8_t *codes, int64_t rows, int64_t K, uint8_t *q_out, void *stream);
+int mkq_pack_weights_e3m2(const float *W, int64_t N, int64_t K, const float *s_w_in, float *s_w_out,
+                          uint8_t *Wq_out, void *stream);
+int mkq_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,
+                         const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                         const mkq_epilogue *epi, void *stream);
+
 /* 16-bit float baseline linear (same epilogue, no quantizers):
  *   a [M, K] binary16, W [N, K] binary16, bias [N] binary32 or NULL, binary32
  *   accumulation, out [M, N] of out_dtype (F32 or F16), residual binary16 or NULL.

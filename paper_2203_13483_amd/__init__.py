@@ -25,6 +25,7 @@ EXPORTS = [
     "mkq_quantize_int8", "mkq_pack_weights_int8", "mkq_linear_int8", "mkq_bert_layer_int8_workspace",
     "mkq_bert_layer_int8", "mkq_layernorm_int8", "mkq_attention_int8",
     "mkq_scale_gradients", "mkq_percentile_scale_workspace_bytes", "mkq_percentile_scale", "mkq_attention_varlen",
+    "mkq_quantize_e3m2", "mkq_pack_codes_e3m2", "mkq_pack_weights_e3m2", "mkq_linear_int4_e3m2",
     "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
     "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
 ]
@@ -96,6 +97,10 @@ def load() -> C.CDLL:
         "mkq_pack_weights_int8": (ci, [vp, i64, i64, vp, vp, vp, vp]),
         "mkq_linear_int8": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp]),
         "mkq_linear_fp16": (ci, [vp, vp, vp, i64, i64, i64, vp, ci, ci, vp, vp]),
+        "mkq_quantize_e3m2": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
+        "mkq_pack_codes_e3m2": (ci, [vp, i64, i64, vp, vp]),
+        "mkq_pack_weights_e3m2": (ci, [vp, i64, i64, vp, vp, vp, vp]),
+        "mkq_linear_int4_e3m2": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp]),
         "mkq_bert_layer_workspace": (ci, [C.POINTER(BertLayerParams), C.POINTER(BertLayerWorkspaceLayout)]),
         "mkq_bert_layer_int4": (ci, [C.POINTER(BertLayerParams), vp, ci, vp, vp, vp, vp, sz, vp]),
         "mkq_bert_layer_fp16_workspace_bytes": (sz, [C.POINTER(BertLayerParamsFp16)]),
@@ -323,6 +328,56 @@ def mkq_linear_int8(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, a
     _check(load().mkq_linear_int8(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
                                   int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int8")
     return {"out": out, "acc": acc}
+
+
+def mkq_quantize_e3m2(x, s_x: float, stream=None):
+    """x [M,K] float -> E3M2 containers uint8 [M, 3K/4] (experimental 6-bit float path)."""
+    torch = _torch()
+    M, K = x.shape
+    q = torch.empty((M, K * 3 // 4), dtype=torch.uint8, device=x.device)
+    _check(load().mkq_quantize_e3m2(_ptr(x), _dtype_code(x), M, K, x.stride(0), float(s_x), _ptr(q),
+                                    _stream(stream)), "mkq_quantize_e3m2")
+    return q
+
+
+def mkq_pack_codes_e3m2(codes, stream=None):
+    torch = _torch()
+    rows, K = codes.shape
+    q = torch.empty((rows, K * 3 // 4), dtype=torch.uint8, device=codes.device)
+    _check(load().mkq_pack_codes_e3m2(_ptr(codes), rows, K, _ptr(q), _stream(stream)), "mkq_pack_codes_e3m2")
+    return q
+
+
+def mkq_pack_weights_e3m2(W, s_w_in=None, stream=None):
+    torch = _torch()
+    N, K = W.shape
+    Wq = torch.empty((N, K * 3 // 4), dtype=torch.uint8, device=W.device)
+    s_w = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(load().mkq_pack_weights_e3m2(_ptr(W), N, K, _ptr(s_w_in), _ptr(s_w), _ptr(Wq), _stream(stream)),
+           "mkq_pack_weights_e3m2")
+    return Wq, s_w
+
+
+def mkq_linear_int4_e3m2(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, act: int = MKQ_ACT_NONE,
+                         residual=None, s_next: float = 0.0, want_q: bool = False, want_acc: bool = False,
+                         out=None, stream=None):
+    """The 4-bit linear on E3M2 containers: a uint8 [M, 3K/4], Wq uint8 [N, 3K/4]."""
+    torch = _torch()
+    M, K = a.shape[0], a.shape[1] * 4 // 3
+    N = Wq.shape[0]
+    dev = a.device
+    if out is None:
+        out = (torch.empty((M, N // 2), dtype=torch.uint8, device=dev) if out_dtype == MKQ_I4
+               else torch.empty((M, N), dtype=_torch_dtype(out_dtype), device=dev))
+    q = torch.empty((M, N // 2), dtype=torch.uint8, device=dev) if want_q else None
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
+                   residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
+                   s_next=float(s_next), q_out=q.data_ptr() if q is not None else None,
+                   acc_out=acc.data_ptr() if acc is not None else None)
+    _check(load().mkq_linear_int4_e3m2(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
+                                       int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int4_e3m2")
+    return {"out": out, "q": q, "acc": acc}
 
 
 def mkq_linear_fp16(a, W, bias, out_dtype: int = MKQ_F16, act: int = MKQ_ACT_NONE, residual=None,

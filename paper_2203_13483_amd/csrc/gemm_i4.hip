@@ -1356,6 +1356,173 @@ int run_gemm_i8(const GemmI4Params &p, hipStream_t st)
     }
 }
 
+
+// ---------------------------------------------------------------------------------
+// Experimental: the same int4 x int4 -> exact integer contraction through the 6-bit float path of the
+// matrix core.  Every code in [-8, 8] is an E3M2 value, products and sums of such values are exact in
+// binary32 while |sum| < 2^24 (K < 2^18), and v_mfma_scale_f32_32x32x64_f8f6f4 with unit scales returns
+// them exactly (checked by brute force in the tests).  Operands are stored as E3M2 codes, 6 bits each,
+// code k of a row in bits [6k, 6k + 6) of the row's little-endian bit stream (96 bytes per 128 codes):
+// no widening, and one MFMA covers 64 codes of k.
+// Tile 256 x 128, four waves of 128 x 64, ring of 4 stages of 64 codes (48-byte rows, 18 KiB per stage).
+// A stage is 1152 16-byte chunks = 18 wave copies: waves 0, 1 issue five of them, waves 2, 3 four.
+struct E3Cfg {
+    static constexpr int BM = 256, BN = 128, WGM = 2, WGN = 2, THREADS = 256, WAVES = 4;
+    static constexpr int WTM = 128, WTN = 64, TM = 4, TN = 2;
+    static constexpr int ROWB = 48, S = 4, STAGE_BYTES = (BM + BN) * ROWB, LDS_BYTES = S * STAGE_BYTES;
+    static constexpr int A_COPIES = BM * 3 / 64, COPIES = (BM + BN) * 3 / 64;  // 12 of 18
+};
+
+template <class Epi>
+__global__ __launch_bounds__(E3Cfg::THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_e3m2_kernel(const GemmI4Params p)
+{
+    using Cfg = E3Cfg;
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::S, ROWB = Cfg::ROWB;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
+    const int fr = lane & 31, fh = lane >> 5;
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    int tm, tn;
+    tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int row_bytes = p.K / 4 * 3;
+    const int kt_count = p.K / 64;
+
+    // copy q of this wave is stage copy c = wave + 4q: chunks 64c .. 64c + 63, chunk g = row g / 3, slot g % 3
+    const int ncp = wave < 2 ? 5 : 4;
+    uint32_t goff[5];
+#pragma unroll
+    for (int q = 0; q < 5; ++q) {
+        const int g = (wave + 4 * q) * 64 + lane;
+        const int row = g / 3, slot = g - row * 3;
+        int src;
+        if (row < BM) {
+            src = tm * BM + row;
+            src = src < p.M ? src : p.M - 1;  // rows past the edge re-read the last row; never stored
+        } else {
+            src = tn * BN + (row - BM);
+            src = src < p.N ? src : p.N - 1;
+        }
+        goff[q] = (uint32_t)src * (uint32_t)row_bytes + slot * 16;
+    }
+    int lk = 0;  // next stage to fetch (clamped: past the end the last stage is fetched again, never read)
+    auto issue = [&](int slot) {
+        const int kb = (lk < kt_count ? lk : kt_count - 1) * ROWB;
+        const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * 1024;
+        static_for<5>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            if (q < 4 || wave < 2) {
+                const bool is_a = (wave + 4 * q) < Cfg::A_COPIES;  // wave-uniform
+                dma_copy16<q * 4096>((is_a ? p.A : p.W) + kb, goff[q], dst);
+            }
+        });
+        ++lk;
+    };
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][t][v] = 0.0f;
+
+    // fragment byte offsets inside a stage: 16 bytes at row * 48 + 16 * fh, then 8 at row * 48 + 32 + 8 * fh
+    int rdW[TN], rdA[TM];
+#pragma unroll
+    for (int t = 0; t < TN; ++t) rdW[t] = (BM + wn * Cfg::WTN + t * 32 + w_row_perm(fr)) * ROWB + 16 * fh;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) rdA[j] = (wm * Cfg::WTM + j * 32 + fr) * ROWB + 16 * fh;
+
+    v8i fw[2][TN], fa[2][TM];  // fragments of two consecutive stages
+    auto read_stage = [&](int slot, auto bc) {
+        constexpr int b = decltype(bc)::value;
+        const uint8_t *st = smem + slot * Cfg::STAGE_BYTES;
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdW[t]);
+            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdW[t] + 32 - 8 * fh);
+            fw[b][t] = v8i{(int)x.x, (int)x.y, (int)x.z, (int)x.w, (int)y.x, (int)y.y, 0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdA[j]);
+            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdA[j] + 32 - 8 * fh);
+            fa[b][j] = v8i{(int)x.x, (int)x.y, (int)x.z, (int)x.w, (int)y.x, (int)y.y, 0, 0};
+        }
+    };
+    auto multiply = [&](auto bc) {
+        constexpr int b = decltype(bc)::value;
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+                acc[j][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw[b][t], fa[b][j], acc[j][t], 3, 3, 0,
+                                                                            0x7f7f7f7f, 0, 0x7f7f7f7f);
+    };
+    // One stage: by its barrier stage s + 1 has landed everywhere and every wave holds stage s in
+    // registers, so the slot of stage s - 1 is refilled with stage s + 3 while the fragments of stage
+    // s + 1 are fetched and stage s is multiplied.
+    auto stage = [&](int s, auto cur, auto nxt) {
+        if (wave < 2) wait_vmcnt<5>();  // only the copies of stage s + 2 may be outstanding
+        else wait_vmcnt<4>();
+        lds_barrier();
+        issue((s + S - 1) & (S - 1));
+        read_stage((s + 1) & (S - 1), nxt);
+        multiply(cur);
+    };
+
+#pragma unroll
+    for (int i = 0; i < S - 1; ++i) issue(i);
+    if (wave < 2) wait_vmcnt<10>();
+    else wait_vmcnt<8>();
+    lds_barrier();
+    read_stage(0, IntC<0>{});
+    for (int s = 0; s < kt_count; s += 2) {
+        stage(s, IntC<0>{}, IntC<1>{});
+        if (s + 1 < kt_count) stage(s + 1, IntC<1>{}, IntC<0>{});
+    }
+    wait_vmcnt<0>();  // the trailing copies must land before the LDS is released
+
+    v16i acci[TM][TN];
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acci[j][t][v] = (int)acc[j][t][v];  // exact: integers below 2^24
+    gemm_i4_epilogue<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, fr, fh);
+}
+
+template <class Epi>
+static int launch_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
+{
+    const int64_t tiles = ceil_div(p.M, E3Cfg::BM) * ceil_div(p.N, E3Cfg::BN);
+    if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    static bool ready = false;
+    if (!ready) {
+        if (hipFuncSetAttribute((const void *)gemm_e3m2_kernel<Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                E3Cfg::LDS_BYTES) != hipSuccess)
+            return MKQ_ERR_HIP;
+        ready = true;
+    }
+    gemm_e3m2_kernel<Epi><<<(unsigned)tiles, E3Cfg::THREADS, E3Cfg::LDS_BYTES, st>>>(p);
+    return launch_status();
+}
+
+int run_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
+{
+    switch (classify_epilogue(p)) {
+    case EPI_F16: return launch_gemm_e3m2<EpiFixed<MKQ_F16, false, false>>(p, st);
+    case EPI_BF16: return launch_gemm_e3m2<EpiFixed<MKQ_BF16, false, false>>(p, st);
+    case EPI_F32: return launch_gemm_e3m2<EpiFixed<MKQ_F32, false, false>>(p, st);
+    default: return launch_gemm_e3m2<EpiGeneric>(p, st);
+    }
+}
+
 }  // namespace mkq
 
 using namespace mkq;
@@ -1470,4 +1637,49 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
     p.acc_shift = 0;   // byte operands enter the MFMA as they are
     p.acc_unit = 1.0f;
     return run_gemm_i8(p, as_stream(stream));
+}
+
+extern "C" int mkq_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,
+                                    const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                                    const mkq_epilogue *epi, void *stream)
+{
+    const bool want_q = epi && epi->q_out;
+    const bool want_acc = epi && epi->acc_out;
+    if (out_dtype != MKQ_F32 && out_dtype != MKQ_F16 && out_dtype != MKQ_BF16 && out_dtype != MKQ_I4)
+        return MKQ_ERR_DTYPE;
+    if (epi) {
+        if (epi->act != MKQ_ACT_NONE && epi->act != MKQ_ACT_GELU) return MKQ_ERR_DTYPE;
+        if (epi->residual && epi->residual_dtype != MKQ_F32 && epi->residual_dtype != MKQ_F16)
+            return MKQ_ERR_DTYPE;
+    }
+    const bool writes_codes = (out && out_dtype == MKQ_I4) || want_q;
+    if (M < 0 || N <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
+    if (writes_codes && (N % 2) != 0) return MKQ_ERR_SHAPE;
+    if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
+    if (writes_codes && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
+    if (M == 0) return MKQ_OK;
+    if (!a || !Wq || !s_w) return MKQ_ERR_NULL;
+    if (!out && !want_q && !want_acc) return MKQ_ERR_NULL;
+    if (!aligned16(a) || !aligned16(Wq) || (out && !aligned16(out)) || !aligned16(s_w) || (bias && !aligned16(bias)))
+        return MKQ_ERR_ALIGN;
+    if (epi && ((epi->residual && !aligned16(epi->residual)) || (epi->q_out && !aligned16(epi->q_out)) ||
+                (epi->acc_out && !aligned16(epi->acc_out))))
+        return MKQ_ERR_ALIGN;
+    // exact sums need |acc| <= 64 K < 2^24; 32-bit byte offsets
+    if (K >= 262144 || M > 0x7FFFFFFF || N > 0x7FFFFFFF || M * (K / 4 * 3) > 0xFFFFFFFFLL ||
+        N * (K / 4 * 3) > 0xFFFFFFFFLL)
+        return MKQ_ERR_UNSUPPORTED;
+    GemmI4Params p;
+    p.A = a; p.W = Wq; p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.s_x = s_x; p.s_w = s_w; p.bias = bias;
+    p.residual = epi ? epi->residual : nullptr;
+    p.residual_dtype = epi ? epi->residual_dtype : MKQ_F32;
+    p.act = epi ? epi->act : MKQ_ACT_NONE;
+    p.out = out; p.out_dtype = out ? out_dtype : -1;
+    p.s_next = epi ? epi->s_next : 1.0f;
+    p.q_out = (epi && !(out && out_dtype == MKQ_I4)) ? epi->q_out : nullptr;
+    p.acc_out = epi ? epi->acc_out : nullptr;
+    p.acc_shift = 0;
+    p.acc_unit = 1.0f;
+    return run_gemm_e3m2(p, as_stream(stream));
 }

@@ -254,6 +254,119 @@ __global__ __launch_bounds__(256) void pack_weights8_kernel(const float *__restr
     }
 }
 
+// ---- E3M2 containers (experimental 6-bit float path of the GEMM) ------------------------------
+// A code c in [-8, 8] as a 6-bit float: sign, 3 exponent bits (bias 3), 2 mantissa bits.  The nine
+// magnitudes, 6 bits each, sit in one 64-bit constant.
+__device__ __forceinline__ uint32_t e3m2_of_code(int c)
+{
+    constexpr unsigned long long MAG = 0x00ull | (0x0Cull << 6) | (0x10ull << 12) | (0x12ull << 18) | (0x14ull << 24) |
+                                       (0x15ull << 30) | (0x16ull << 36) | (0x17ull << 42) | (0x18ull << 48);
+    const int m = c < 0 ? -c : c;
+    return (uint32_t)((MAG >> (6 * m)) & 0x3Full) | (c < 0 ? 0x20u : 0u);
+}
+
+// 16 codes -> 96 bits, code i in bits [6i, 6i + 6)
+__device__ __forceinline__ void pack16_e3m2(const int (&c)[16], uint32_t (&w)[3])
+{
+    uint32_t e[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) e[i] = e3m2_of_code(c[i]);
+    w[0] = e[0] | (e[1] << 6) | (e[2] << 12) | (e[3] << 18) | (e[4] << 24) | (e[5] << 30);
+    w[1] = (e[5] >> 2) | (e[6] << 4) | (e[7] << 10) | (e[8] << 16) | (e[9] << 22) | (e[10] << 28);
+    w[2] = (e[10] >> 4) | (e[11] << 2) | (e[12] << 8) | (e[13] << 14) | (e[14] << 20) | (e[15] << 26);
+}
+
+// Container layout: a row is groups of 64 codes = 48 bytes.  The 32 codes of half h of a group form a
+// 192-bit little-endian stream (code i in bits [6i, 6i + 6)) -- one matrix-core operand of a lane --
+// stored as bytes [16h, 16h + 16) then [32 + 8h, 32 + 8h + 8) of the group, so that a lane fetches its
+// operand with one aligned 16-byte and one 8-byte read.  This writes half `half` (0 / 1) of group `g`.
+__device__ __forceinline__ void store_half_e3m2(uint8_t *group, int half, const int (&c)[32])
+{
+    int lo[16], hi[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        lo[i] = c[i];
+        hi[i] = c[16 + i];
+    }
+    uint32_t a[3], b[3];
+    pack16_e3m2(lo, a);
+    pack16_e3m2(hi, b);
+    *reinterpret_cast<uint4 *>(group + 16 * half) = make_uint4(a[0], a[1], a[2], b[0]);
+    *reinterpret_cast<uint2 *>(group + 32 + 8 * half) = make_uint2(b[1], b[2]);
+}
+
+// Eq. 1 then the container: x [M, K] -> [M, 3K/4] bytes; one thread per 32 values (half a group)
+template <typename T>
+__global__ __launch_bounds__(256) void quantize_e3m2_kernel(const T *__restrict__ x, int64_t M, int64_t K, int64_t ldx,
+                                                            float s, uint8_t *__restrict__ q)
+{
+    const int64_t halves_per_row = K / 32;
+    const int64_t total = M * halves_per_row;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t m = g / halves_per_row;
+        const int64_t kh = g - m * halves_per_row;
+        int c[32];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float v[8];
+            load8<T>(x + m * ldx + kh * 32 + j * 8, v);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) c[8 * j + i] = quantize_code(v[i], s);
+        }
+        store_half_e3m2(q + m * (K / 4 * 3) + (kh >> 1) * 48, (int)(kh & 1), c);
+    }
+}
+
+// int8 codes [rows, K] (values in [-8, 8]) -> containers
+__global__ __launch_bounds__(256) void pack_codes_e3m2_kernel(const int8_t *__restrict__ codes, int64_t total_halves,
+                                                              uint8_t *__restrict__ q)
+{
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total_halves;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        int c[32];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(codes + g * 32 + j * 16);
+            const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[16 * j + i] = (int)(int8_t)(rw[i >> 2] >> (8 * (i & 3)));
+        }
+        // rows are whole groups, so half g of the flat array is half g % 2 of group g / 2
+        store_half_e3m2(q + (g >> 1) * 48, (int)(g & 1), c);
+    }
+}
+
+// Offline weight preparation into containers, one workgroup per output channel
+__global__ __launch_bounds__(256) void pack_weights_e3m2_kernel(const float *__restrict__ W, int64_t K,
+                                                                const float *__restrict__ s_in,
+                                                                float *__restrict__ s_out, uint8_t *__restrict__ q)
+{
+    __shared__ float part[4];
+    const int64_t n = blockIdx.x;
+    const float *row = W + n * K;
+    float s;
+    if (s_in) {
+        s = s_in[n];
+    } else {
+        const float mx = row_absmax<float>(row, K, part);
+        s = (mx > 0.0f) ? mx / (float)QMAX : 1.0f;
+    }
+    if (threadIdx.x == 0) s_out[n] = s;
+    uint8_t *qrow = q + n * (K / 4 * 3);
+    for (int64_t kh = threadIdx.x; kh < K / 32; kh += blockDim.x) {
+        int c[32];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float v[8];
+            load8<float>(row + kh * 32 + j * 8, v);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) c[8 * j + i] = quantize_code(v[i], s);
+        }
+        store_half_e3m2(qrow + (kh >> 1) * 48, (int)(kh & 1), c);
+    }
+}
+
 static inline int grid_for(int64_t items, int threads = 256, int max_blocks = 256 * 16)
 {
     int64_t b = ceil_div(items, threads);
@@ -371,6 +484,46 @@ extern "C" int mkq_pack_weights_int8(const float *W, int64_t N, int64_t K, const
         (reinterpret_cast<uintptr_t>(s_w_in) & 3u))
         return MKQ_ERR_ALIGN;
     pack_weights8_kernel<<<(int)N, 256, 0, as_stream(stream)>>>(W, K, s_w_in, s_w_out, (uint2 *)Wq_out);
+    return launch_status();
+}
+
+extern "C" int mkq_quantize_e3m2(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, float s_x,
+                                 uint8_t *q_out, void *stream)
+{
+    if (x_dtype != MKQ_F32 && x_dtype != MKQ_F16) return MKQ_ERR_DTYPE;
+    if (M < 0 || K < 0 || (K % 64) != 0 || ldx < K || (ldx % 8) != 0) return MKQ_ERR_SHAPE;
+    if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
+    if (M == 0 || K == 0) return MKQ_OK;
+    if (!x || !q_out) return MKQ_ERR_NULL;
+    if (!aligned16(x) || !aligned16(q_out)) return MKQ_ERR_ALIGN;
+    const int grid = grid_for(M * (K / 32));
+    if (x_dtype == MKQ_F32)
+        quantize_e3m2_kernel<float><<<grid, 256, 0, as_stream(stream)>>>((const float *)x, M, K, ldx, s_x, q_out);
+    else
+        quantize_e3m2_kernel<__half><<<grid, 256, 0, as_stream(stream)>>>((const __half *)x, M, K, ldx, s_x, q_out);
+    return launch_status();
+}
+
+extern "C" int mkq_pack_codes_e3m2(const int8_t *codes, int64_t rows, int64_t K, uint8_t *q_out, void *stream)
+{
+    if (!codes || !q_out) return MKQ_ERR_NULL;
+    if (rows <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
+    if (!aligned16(codes) || !aligned16(q_out)) return MKQ_ERR_ALIGN;
+    const int64_t halves = rows * (K / 32);
+    pack_codes_e3m2_kernel<<<grid_for(halves), 256, 0, as_stream(stream)>>>(codes, halves, q_out);
+    return launch_status();
+}
+
+extern "C" int mkq_pack_weights_e3m2(const float *W, int64_t N, int64_t K, const float *s_w_in, float *s_w_out,
+                                     uint8_t *Wq_out, void *stream)
+{
+    if (!W || !s_w_out || !Wq_out) return MKQ_ERR_NULL;
+    if (N <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
+    if (N > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    if (!aligned16(W) || !aligned16(Wq_out) || (reinterpret_cast<uintptr_t>(s_w_out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(s_w_in) & 3u))
+        return MKQ_ERR_ALIGN;
+    pack_weights_e3m2_kernel<<<(int)N, 256, 0, as_stream(stream)>>>(W, K, s_w_in, s_w_out, Wq_out);
     return launch_status();
 }
 
