@@ -178,7 +178,8 @@ int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s
  * mkq_linear_int4 -- with no widening and half the matrix instructions per k.  Operands are "containers":
  * 6 bits per code, rows of 3K/4 bytes made of groups of 64 codes = 48 bytes; the 32 codes of half h of a
  * group are a 192-bit little-endian stream (code i in bits [6i, 6i + 6)) stored as bytes [16h, 16h + 16)
- * and then [32 + 8h, 40 + 8h) of the group.  K % 64 == 0, K < 262144.  The quantizer and the weight preparation are those of
+ * and then [32 + 8h, 40 + 8h) of the group.  K % 64 == 0 for the containers, K % 128 == 0 and
+ * K < 262144 for the linear.  The quantizer and the weight preparation are those of
  * mkq_quantize / mkq_pack_weights_int4 (Eq. 1, per-tensor / per-channel steps), written as containers;
  * mkq_pack_codes_e3m2 takes int8 codes in [-8, 8].  mkq_linear_int4_e3m2: arguments and epilogue as
  * mkq_linear_int4 with both operands given as containers (no workspace).

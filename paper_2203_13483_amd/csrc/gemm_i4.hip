@@ -1364,21 +1364,31 @@ int run_gemm_i8(const GemmI4Params &p, hipStream_t st)
 // them exactly (checked by brute force in the tests).  Operands are stored as E3M2 codes, 6 bits each,
 // code k of a row in bits [6k, 6k + 6) of the row's little-endian bit stream (96 bytes per 128 codes):
 // no widening, and one MFMA covers 64 codes of k.
-// Tile 256 x 128, four waves of 128 x 64, ring of 4 stages of 64 codes (48-byte rows, 18 KiB per stage).
-// A stage is 1152 16-byte chunks = 18 wave copies: waves 0, 1 issue five of them, waves 2, 3 four.
-struct E3Cfg {
-    static constexpr int BM = 256, BN = 128, WGM = 2, WGN = 2, THREADS = 256, WAVES = 4;
+// Tile 256 x 256, eight waves of 128 x 64, ring of 3 stages of 128 codes (96-byte rows = two container
+// groups = two MFMA k steps, 48 KiB per stage, 48 wave copies of which every wave issues six); one
+// workgroup per CU.  The tile is this large and the stage rows this long because the route is bound by
+// the number of 64-byte requests the global->LDS copies make, not by the matrix pipe: a 48-byte row
+// segment straddles request boundaries (1.75 requests on average), a 96-byte one takes exactly two.
+template <int BN_, int WGN_, int S_>
+struct E3CfgT {
+    static constexpr int BM = 256, BN = BN_, WGM = 2, WGN = WGN_, WAVES = WGM * WGN, THREADS = WAVES * 64;
     static constexpr int WTM = 128, WTN = 64, TM = 4, TN = 2;
-    static constexpr int ROWB = 48, S = 4, STAGE_BYTES = (BM + BN) * ROWB, LDS_BYTES = S * STAGE_BYTES;
-    static constexpr int A_COPIES = BM * 3 / 64, COPIES = (BM + BN) * 3 / 64;  // 12 of 18
+    static_assert(BN == WGN * WTN, "waves of 128 x 64");
+    // S slots keep S - 1 stages in flight: when a stage's second k step has been fetched by every wave its
+    // slot is free for the stage S further on
+    static constexpr int ROWB = 96, KSTEPS = 2, S = S_, STAGE_BYTES = (BM + BN) * ROWB, LDS_BYTES = S * STAGE_BYTES;
+    static constexpr int CPR = ROWB / 16;                                   // 16-byte chunks per row
+    static constexpr int A_COPIES = BM * CPR / 64, COPIES = (BM + BN) * CPR / 64, LPW = COPIES / WAVES;
+    static_assert(COPIES % WAVES == 0 && (BM * CPR) % 64 == 0, "copies split evenly, none straddles A / W");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
 };
 
-template <class Epi>
-__global__ __launch_bounds__(E3Cfg::THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <class Cfg, class Epi>
+__global__ __launch_bounds__(Cfg::THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void gemm_e3m2_kernel(const GemmI4Params p)
 {
-    using Cfg = E3Cfg;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::S, ROWB = Cfg::ROWB;
+    constexpr int LPW = Cfg::LPW, CPR = Cfg::CPR, WAVES = Cfg::WAVES;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1389,15 +1399,17 @@ void gemm_e3m2_kernel(const GemmI4Params p)
     int tm, tn;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int row_bytes = p.K / 4 * 3;
-    const int kt_count = p.K / 64;
+    const int kt_count = p.K / 128;
 
-    // copy q of this wave is stage copy c = wave + 4q: chunks 64c .. 64c + 63, chunk g = row g / 3, slot g % 3
-    const int ncp = wave < 2 ? 5 : 4;
-    uint32_t goff[5];
+    // copy q of this wave is stage copy c = wave + WAVES * q: chunks 64c .. 64c + 63, chunk g = row g / CPR, slot g % CPR
+    uint32_t goff[LPW];
 #pragma unroll
-    for (int q = 0; q < 5; ++q) {
-        const int g = (wave + 4 * q) * 64 + lane;
-        const int row = g / 3, slot = g - row * 3;
+    for (int q = 0; q < LPW; ++q) {
+        const int g = (wave + WAVES * q) * 64 + lane;
+        const int row = g / CPR, slot = g - row * CPR;
+        // rows 8 .. 15 of every 16 hold their six chunks rotated by one: 16 consecutive rows then spread a
+        // 16-byte column over all 64 banks (a row is 24 banks long)
+        const int chunk = (slot + CPR - ((row >> 3) & 1)) % CPR;
         int src;
         if (row < BM) {
             src = tm * BM + row;
@@ -1406,18 +1418,16 @@ void gemm_e3m2_kernel(const GemmI4Params p)
             src = tn * BN + (row - BM);
             src = src < p.N ? src : p.N - 1;
         }
-        goff[q] = (uint32_t)src * (uint32_t)row_bytes + slot * 16;
+        goff[q] = (uint32_t)src * (uint32_t)row_bytes + chunk * 16;
     }
     int lk = 0;  // next stage to fetch (clamped: past the end the last stage is fetched again, never read)
     auto issue = [&](int slot) {
         const int kb = (lk < kt_count ? lk : kt_count - 1) * ROWB;
         const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * 1024;
-        static_for<5>([&](auto qc) {
+        static_for<LPW>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
-            if (q < 4 || wave < 2) {
-                const bool is_a = (wave + 4 * q) < Cfg::A_COPIES;  // wave-uniform
-                dma_copy16<q * 4096>((is_a ? p.A : p.W) + kb, goff[q], dst);
-            }
+            const bool is_a = (wave + WAVES * q) < Cfg::A_COPIES;  // wave-uniform
+            dma_copy16<q * WAVES * 1024>((is_a ? p.A : p.W) + kb, goff[q], dst);
         });
         ++lk;
     };
@@ -1430,27 +1440,34 @@ void gemm_e3m2_kernel(const GemmI4Params p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][t][v] = 0.0f;
 
-    // fragment byte offsets inside a stage: 16 bytes at row * 48 + 16 * fh, then 8 at row * 48 + 32 + 8 * fh
-    int rdW[TN], rdA[TM];
+    // fragment byte offsets inside a stage.  Logical chunk c of a row sits at chunk (c + rot) % 6, rot = bit 3
+    // of the row.  K step r takes 16 bytes of chunk 3r + fh and 8 bytes (half fh) of chunk 3r + 2.
+    int rdW[TN][3], rdA[TM][3];  // [0]: 16-byte read of k step 0 (k step 1: + 48), [1], [2]: the 8-byte reads
+    auto offsets = [&](int row, int (&o)[3]) {
+        const int rot = (row >> 3) & 1;
+        o[0] = row * ROWB + (fh + rot) * 16;
+        o[1] = row * ROWB + (2 + rot) * 16 + 8 * fh;
+        o[2] = row * ROWB + (rot ? 0 : 80) + 8 * fh;
+    };
 #pragma unroll
-    for (int t = 0; t < TN; ++t) rdW[t] = (BM + wn * Cfg::WTN + t * 32 + w_row_perm(fr)) * ROWB + 16 * fh;
+    for (int t = 0; t < TN; ++t) offsets(BM + wn * Cfg::WTN + t * 32 + w_row_perm(fr), rdW[t]);
 #pragma unroll
-    for (int j = 0; j < TM; ++j) rdA[j] = (wm * Cfg::WTM + j * 32 + fr) * ROWB + 16 * fh;
+    for (int j = 0; j < TM; ++j) offsets(wm * Cfg::WTM + j * 32 + fr, rdA[j]);
 
-    v8i fw[2][TN], fa[2][TM];  // fragments of two consecutive stages
-    auto read_stage = [&](int slot, auto bc) {
-        constexpr int b = decltype(bc)::value;
+    v8i fw[2][TN], fa[2][TM];  // fragments of two consecutive k steps
+    auto read_step = [&](int slot, auto rc, auto bc) {
+        constexpr int r = decltype(rc)::value, b = decltype(bc)::value;
         const uint8_t *st = smem + slot * Cfg::STAGE_BYTES;
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdW[t]);
-            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdW[t] + 32 - 8 * fh);
+            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdW[t][0] + r * 48);
+            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdW[t][1 + r]);
             fw[b][t] = v8i{(int)x.x, (int)x.y, (int)x.z, (int)x.w, (int)y.x, (int)y.y, 0, 0};
         }
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdA[j]);
-            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdA[j] + 32 - 8 * fh);
+            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdA[j][0] + r * 48);
+            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdA[j][1 + r]);
             fa[b][j] = v8i{(int)x.x, (int)x.y, (int)x.z, (int)x.w, (int)y.x, (int)y.y, 0, 0};
         }
     };
@@ -1463,27 +1480,27 @@ void gemm_e3m2_kernel(const GemmI4Params p)
                 acc[j][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw[b][t], fa[b][j], acc[j][t], 3, 3, 0,
                                                                             0x7f7f7f7f, 0, 0x7f7f7f7f);
     };
-    // One stage: by its barrier stage s + 1 has landed everywhere and every wave holds stage s in
-    // registers, so the slot of stage s - 1 is refilled with stage s + 3 while the fragments of stage
-    // s + 1 are fetched and stage s is multiplied.
-    auto stage = [&](int s, auto cur, auto nxt) {
-        if (wave < 2) wait_vmcnt<5>();  // only the copies of stage s + 2 may be outstanding
-        else wait_vmcnt<4>();
-        lds_barrier();
-        issue((s + S - 1) & (S - 1));
-        read_stage((s + 1) & (S - 1), nxt);
-        multiply(cur);
-    };
 
+    // prologue: stages 0 and 1 in flight, stage 0 landed, its first k step in registers
 #pragma unroll
-    for (int i = 0; i < S - 1; ++i) issue(i);
-    if (wave < 2) wait_vmcnt<10>();
-    else wait_vmcnt<8>();
+    for (int i = 0; i < S; ++i) issue(i);
+    wait_vmcnt<(S - 1) * LPW>();
     lds_barrier();
-    read_stage(0, IntC<0>{});
-    for (int s = 0; s < kt_count; s += 2) {
-        stage(s, IntC<0>{}, IntC<1>{});
-        if (s + 1 < kt_count) stage(s + 1, IntC<1>{}, IntC<0>{});
+    read_step(0, IntC<0>{}, IntC<0>{});
+    int slot = 0;
+    for (int s = 0; s < kt_count; ++s) {
+        const int nslot = (slot + 1 == S) ? 0 : slot + 1;
+        // k step 0 of stage s while its k step 1 is fetched
+        read_step(slot, IntC<1>{}, IntC<1>{});
+        multiply(IntC<0>{});
+        // stage s + 1 has landed (the S - 2 stages after it may still be in flight); past the barrier every
+        // wave holds all of stage s in registers, so its slot takes stage s + S
+        wait_vmcnt<(S - 2) * LPW>();
+        lds_barrier();
+        issue(slot);
+        read_step(nslot, IntC<0>{}, IntC<0>{});
+        multiply(IntC<1>{});
+        slot = nslot;
     }
     wait_vmcnt<0>();  // the trailing copies must land before the LDS is released
 
@@ -1494,33 +1511,59 @@ void gemm_e3m2_kernel(const GemmI4Params p)
         for (int t = 0; t < TN; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acci[j][t][v] = (int)acc[j][t][v];  // exact: integers below 2^24
-    gemm_i4_epilogue<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, fr, fh);
+    if constexpr (Epi::generic) {
+        gemm_i4_epilogue<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, fr, fh);
+    } else {
+        // the row epilogue through LDS: the ring is idle now; once every wave has left the k loop each wave
+        // takes 4 KiB of it for the transposition and 512 bytes for its channels' scales and biases
+        lds_barrier();
+        uint8_t *const scr = smem + wave * 4096;
+        float *const sc_lds = reinterpret_cast<float *>(smem + WAVES * 4096 + wave * 512);
+        {
+            int n = tn * BN + wn * Cfg::WTN + lane;  // WTN = 64: one channel per lane
+            n = n < p.N ? n : p.N - 1;
+            sc_lds[lane] = p.s_w[n];
+            sc_lds[EpiShuffle<Cfg>::BIAS_AT + lane] = p.bias ? p.bias[n] : 0.0f;
+        }
+        gemm_i4_epilogue_rows<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, lane, scr, sc_lds);
+    }
 }
 
-template <class Epi>
+template <class Cfg, class Epi>
 static int launch_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
 {
-    const int64_t tiles = ceil_div(p.M, E3Cfg::BM) * ceil_div(p.N, E3Cfg::BN);
+    const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
     static bool ready = false;
     if (!ready) {
-        if (hipFuncSetAttribute((const void *)gemm_e3m2_kernel<Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                E3Cfg::LDS_BYTES) != hipSuccess)
+        if (hipFuncSetAttribute((const void *)gemm_e3m2_kernel<Cfg, Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                Cfg::LDS_BYTES) != hipSuccess)
             return MKQ_ERR_HIP;
         ready = true;
     }
-    gemm_e3m2_kernel<Epi><<<(unsigned)tiles, E3Cfg::THREADS, E3Cfg::LDS_BYTES, st>>>(p);
+    gemm_e3m2_kernel<Cfg, Epi><<<(unsigned)tiles, Cfg::THREADS, Cfg::LDS_BYTES, st>>>(p);
     return launch_status();
+}
+
+template <class Cfg>
+static int launch_e3m2_by_epilogue(const GemmI4Params &p, hipStream_t st)
+{
+    switch (classify_epilogue(p)) {
+    case EPI_F16: return launch_gemm_e3m2<Cfg, EpiFixed<MKQ_F16, false, false>>(p, st);
+    case EPI_BF16: return launch_gemm_e3m2<Cfg, EpiFixed<MKQ_BF16, false, false>>(p, st);
+    case EPI_F32: return launch_gemm_e3m2<Cfg, EpiFixed<MKQ_F32, false, false>>(p, st);
+    default: return launch_gemm_e3m2<Cfg, EpiGeneric>(p, st);
+    }
 }
 
 int run_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
 {
-    switch (classify_epilogue(p)) {
-    case EPI_F16: return launch_gemm_e3m2<EpiFixed<MKQ_F16, false, false>>(p, st);
-    case EPI_BF16: return launch_gemm_e3m2<EpiFixed<MKQ_BF16, false, false>>(p, st);
-    case EPI_F32: return launch_gemm_e3m2<EpiFixed<MKQ_F32, false, false>>(p, st);
-    default: return launch_gemm_e3m2<EpiGeneric>(p, st);
-    }
+    // 256 x 256 tiles (one 8-wave workgroup per CU) make the fewest global->LDS requests per MFMA; 256 x 128
+    // (two 4-wave workgroups per CU) overlap one tile's epilogue with the other's k loop
+    if (g_forced_cfg == 41) return launch_e3m2_by_epilogue<E3CfgT<256, 4, 3>>(p, st);
+    if (g_forced_cfg == 42) return launch_e3m2_by_epilogue<E3CfgT<128, 2, 2>>(p, st);
+    if (p.K >= 2048) return launch_e3m2_by_epilogue<E3CfgT<256, 4, 3>>(p, st);
+    return launch_e3m2_by_epilogue<E3CfgT<128, 2, 2>>(p, st);
 }
 
 }  // namespace mkq
@@ -1653,7 +1696,7 @@ extern "C" int mkq_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *
             return MKQ_ERR_DTYPE;
     }
     const bool writes_codes = (out && out_dtype == MKQ_I4) || want_q;
-    if (M < 0 || N <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
+    if (M < 0 || N <= 0 || K <= 0 || (K % 128) != 0) return MKQ_ERR_SHAPE;
     if (writes_codes && (N % 2) != 0) return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
     if (writes_codes && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;

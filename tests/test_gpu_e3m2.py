@@ -59,7 +59,7 @@ def test_containers_bit_exact(mkq):
     assert np.array_equal(to_np(s_w), sw) and np.array_equal(to_np(Wq), _containers(wc))
 
 
-@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (300, 200, 128), (1, 8, 64), (1024, 768, 768), (517, 1000, 1024),
+@pytest.mark.parametrize("M,N,K", [(256, 128, 128), (300, 200, 128), (1, 8, 128), (1024, 768, 768), (517, 1000, 1024),
                                    (2048, 256, 4096)])
 def test_accumulators_and_outputs_match_the_oracle(mkq, M, N, K):
     A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, seed=M + K)
@@ -75,7 +75,7 @@ def test_accumulators_and_outputs_match_the_oracle(mkq, M, N, K):
         assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
 
 
-@pytest.mark.parametrize("K", [64, 4096, 65536])
+@pytest.mark.parametrize("K", [128, 4096, 65536])
 def test_accumulator_extremes(mkq, K):
     M, N = 40, 72
     lo = np.full((M, K), -8, np.int8)
