@@ -1361,14 +1361,17 @@ int run_gemm_i8(const GemmI4Params &p, hipStream_t st)
 // Experimental: the same int4 x int4 -> exact integer contraction through the 6-bit float path of the
 // matrix core.  Every code in [-8, 8] is an E3M2 value, products and sums of such values are exact in
 // binary32 while |sum| < 2^24 (K < 2^18), and v_mfma_scale_f32_32x32x64_f8f6f4 with unit scales returns
-// them exactly (checked by brute force in the tests).  Operands are stored as E3M2 codes, 6 bits each,
-// code k of a row in bits [6k, 6k + 6) of the row's little-endian bit stream (96 bytes per 128 codes):
-// no widening, and one MFMA covers 64 codes of k.
+// them exactly (checked by brute force in the tests).  Operands are stored as E3M2 codes, 6 bits each, in
+// groups of 64 codes = 48 bytes: the 32 codes of half h of a group are one 192-bit MFMA operand of a lane,
+// stored at bytes [16h, 16h + 16) and [32 + 8h, 40 + 8h) of the group, so that every lane fetches its
+// operand with one aligned 16-byte and one aligned 8-byte LDS read.  No widening, and one MFMA covers 64
+// codes of k.
 // Tile 256 x 256, eight waves of 128 x 64, ring of 3 stages of 128 codes (96-byte rows = two container
 // groups = two MFMA k steps, 48 KiB per stage, 48 wave copies of which every wave issues six); one
-// workgroup per CU.  The tile is this large and the stage rows this long because the route is bound by
-// the number of 64-byte requests the global->LDS copies make, not by the matrix pipe: a 48-byte row
-// segment straddles request boundaries (1.75 requests on average), a 96-byte one takes exactly two.
+// persistent workgroup per CU.  The tile is this large and the stage rows this long because the route is
+// bound by the number of 64-byte requests the global->LDS copies make, not by the matrix pipe: a 48-byte
+// row segment straddles request boundaries (1.75 requests on average), a 96-byte one takes 1.5.
+// (256 x 128 on four waves with a two-stage ring, two workgroups per CU, is the second shape.)
 template <int BN_, int WGN_, int S_>
 struct E3CfgT {
     static constexpr int BM = 256, BN = BN_, WGM = 2, WGN = WGN_, WAVES = WGM * WGN, THREADS = WAVES * 64;
@@ -1389,6 +1392,8 @@ void gemm_e3m2_kernel(const GemmI4Params p)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::S, ROWB = Cfg::ROWB;
     constexpr int LPW = Cfg::LPW, CPR = Cfg::CPR, WAVES = Cfg::WAVES;
+    using Sh = EpiShuffle<Cfg>;
+    static_assert(Cfg::WTN == 64 && Sh::NSL == 1, "one channel per lane in the scale copies");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1396,137 +1401,197 @@ void gemm_e3m2_kernel(const GemmI4Params p)
     const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
     const int fr = lane & 31, fh = lane >> 5;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    int tm, tn;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int total_tiles = tiles_m * tiles_n;
     const int row_bytes = p.K / 4 * 3;
     const int kt_count = p.K / 128;
 
-    // copy q of this wave is stage copy c = wave + WAVES * q: chunks 64c .. 64c + 63, chunk g = row g / CPR, slot g % CPR
+    // The workgroup is persistent: it walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... and its copies
+    // run ahead of the arithmetic as one stream of stages across tile boundaries, so the first stages of
+    // a tile are fetched while the previous tile is still being multiplied and stored.
+    // Copy q of this wave is stage copy c = wave + WAVES * q: chunks 64c .. 64c + 63, chunk g = row g / CPR,
+    // slot g % CPR.
     uint32_t goff[LPW];
+    auto set_fetch_tile = [&](int t) {
+        int tm, tn;
+        tile_coords(t, tiles_m, tiles_n, tm, tn);
+        // (recomputed from the lane index at every tile change: kept across the k loop, the per-copy rows and
+        // chunks would cost more registers than the wave has to spare)
+        int l = lane;
+        asm volatile("" : "+v"(l));
 #pragma unroll
-    for (int q = 0; q < LPW; ++q) {
-        const int g = (wave + WAVES * q) * 64 + lane;
-        const int row = g / CPR, slot = g - row * CPR;
-        // rows 8 .. 15 of every 16 hold their six chunks rotated by one: 16 consecutive rows then spread a
-        // 16-byte column over all 64 banks (a row is 24 banks long)
-        const int chunk = (slot + CPR - ((row >> 3) & 1)) % CPR;
-        int src;
-        if (row < BM) {
-            src = tm * BM + row;
-            src = src < p.M ? src : p.M - 1;  // rows past the edge re-read the last row; never stored
-        } else {
-            src = tn * BN + (row - BM);
-            src = src < p.N ? src : p.N - 1;
+        for (int q = 0; q < LPW; ++q) {
+            const int g = (wave + WAVES * q) * 64 + l;
+            const int row = g / CPR, slot = g - row * CPR;
+            // rows 8 .. 15 of every 16 hold their six chunks rotated by one: 16 consecutive rows then spread a
+            // 16-byte column over all 64 banks (a row is 24 banks long)
+            const int chunk = (slot + CPR - ((row >> 3) & 1)) % CPR;
+            int src;
+            if (row < BM) {
+                src = tm * BM + row;
+                src = src < p.M ? src : p.M - 1;  // rows past the edge re-read the last row; never stored
+            } else {
+                src = tn * BN + (row - BM);
+                src = src < p.N ? src : p.N - 1;
+            }
+            goff[q] = (uint32_t)src * (uint32_t)row_bytes + chunk * 16;
         }
-        goff[q] = (uint32_t)src * (uint32_t)row_bytes + chunk * 16;
-    }
-    int lk = 0;  // next stage to fetch (clamped: past the end the last stage is fetched again, never read)
+    };
+    int ft = blockIdx.x, fk = 0;  // copy cursor: tile and stage; past the last tile it fetches that tile again
+    set_fetch_tile(ft);
     auto issue = [&](int slot) {
-        const int kb = (lk < kt_count ? lk : kt_count - 1) * ROWB;
+        const int kb = fk * ROWB;
         const uint32_t dst = lds0 + slot * Cfg::STAGE_BYTES + wave * 1024;
         static_for<LPW>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
             const bool is_a = (wave + WAVES * q) < Cfg::A_COPIES;  // wave-uniform
             dma_copy16<q * WAVES * 1024>((is_a ? p.A : p.W) + kb, goff[q], dst);
         });
-        ++lk;
+        if (++fk == kt_count) {
+            fk = 0;
+            if (ft + (int)gridDim.x < total_tiles) {
+                ft += gridDim.x;
+                set_fetch_tile(ft);
+            }
+        }
     };
-
-    v16f acc[TM][TN];
-#pragma unroll
-    for (int j = 0; j < TM; ++j)
-#pragma unroll
-        for (int t = 0; t < TN; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][t][v] = 0.0f;
+    // s_w and bias of the wave's 64 channels of tile t, copied to the wave's 512 bytes beyond the ring; always
+    // SC copies, so the number of copies in flight never depends on the arguments
+    constexpr int SC = 2;
+    float *const sc_lds = reinterpret_cast<float *>(smem + Cfg::LDS_BYTES + wave * Sh::SCALE_BYTES);
+    auto issue_scales = [&](int t) {
+        int tm, tn;
+        tile_coords(t, tiles_m, tiles_n, tm, tn);
+        int n = tn * BN + wn * Cfg::WTN + lane;
+        n = n < p.N ? n : p.N - 1;
+        const uint32_t dst = lds0 + Cfg::LDS_BYTES + wave * Sh::SCALE_BYTES;
+        dma_copy4<0>(reinterpret_cast<const uint8_t *>(p.s_w), (uint32_t)n * 4u, dst);
+        dma_copy4<Sh::BIAS_AT * 4>(reinterpret_cast<const uint8_t *>(p.bias ? p.bias : p.s_w), (uint32_t)n * 4u, dst);
+    };
 
     // fragment byte offsets inside a stage.  Logical chunk c of a row sits at chunk (c + rot) % 6, rot = bit 3
     // of the row.  K step r takes 16 bytes of chunk 3r + fh and 8 bytes (half fh) of chunk 3r + 2.
-    int rdW[TN][3], rdA[TM][3];  // [0]: 16-byte read of k step 0 (k step 1: + 48), [1], [2]: the 8-byte reads
+    // The rotation is the same for all row blocks of an operand (blocks are 32 rows apart), so one set of
+    // offsets per operand serves every block with a constant added.
+    int rdW[3], rdA[3];  // [0]: 16-byte read of k step 0 (k step 1: + 48), [1], [2]: the 8-byte reads
     auto offsets = [&](int row, int (&o)[3]) {
         const int rot = (row >> 3) & 1;
         o[0] = row * ROWB + (fh + rot) * 16;
         o[1] = row * ROWB + (2 + rot) * 16 + 8 * fh;
         o[2] = row * ROWB + (rot ? 0 : 80) + 8 * fh;
     };
-#pragma unroll
-    for (int t = 0; t < TN; ++t) offsets(BM + wn * Cfg::WTN + t * 32 + w_row_perm(fr), rdW[t]);
-#pragma unroll
-    for (int j = 0; j < TM; ++j) offsets(wm * Cfg::WTM + j * 32 + fr, rdA[j]);
+    offsets(BM + wn * Cfg::WTN + w_row_perm(fr), rdW);
+    offsets(wm * Cfg::WTM + fr, rdA);
 
+    v16f acc[TM][TN];
     v8i fw[2][TN], fa[2][TM];  // fragments of two consecutive k steps
-    auto read_step = [&](int slot, auto rc, auto bc) {
-        constexpr int r = decltype(rc)::value, b = decltype(bc)::value;
-        const uint8_t *st = smem + slot * Cfg::STAGE_BYTES;
-#pragma unroll
-        for (int t = 0; t < TN; ++t) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdW[t][0] + r * 48);
-            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdW[t][1 + r]);
-            fw[b][t] = v8i{(int)x.x, (int)x.y, (int)x.z, (int)x.w, (int)y.x, (int)y.y, 0, 0};
-        }
-#pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdA[j][0] + r * 48);
-            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdA[j][1 + r]);
+    // fragment of one operand row block: u = 0 .. TN-1: W blocks, TN .. TN+TM-1: A blocks
+    auto read_one = [&](int sl, auto rc, auto bc, auto uc) {
+        constexpr int r = decltype(rc)::value, b = decltype(bc)::value, u = decltype(uc)::value;
+        const uint8_t *st = smem + sl * Cfg::STAGE_BYTES;
+        if constexpr (u < TN) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdW[0] + (u * 32 * ROWB + r * 48));
+            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdW[1 + r] + u * 32 * ROWB);
+            fw[b][u] = v8i{(int)x.x, (int)x.y, (int)x.z, (int)x.w, (int)y.x, (int)y.y, 0, 0};
+        } else {
+            constexpr int j = u - TN;
+            const uint4 x = *reinterpret_cast<const uint4 *>(st + rdA[0] + (j * 32 * ROWB + r * 48));
+            const uint2 y = *reinterpret_cast<const uint2 *>(st + rdA[1 + r] + j * 32 * ROWB);
             fa[b][j] = v8i{(int)x.x, (int)x.y, (int)x.z, (int)x.w, (int)y.x, (int)y.y, 0, 0};
         }
     };
-    auto multiply = [&](auto bc) {
-        constexpr int b = decltype(bc)::value;
+    auto mfma_one = [&](auto bc, auto ic) {
+        constexpr int b = decltype(bc)::value, i = decltype(ic)::value, j = i / TN, t = i % TN;
+        acc[j][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw[b][t], fa[b][j], acc[j][t], 3, 3, 0, 0x7f7f7f7f,
+                                                                    0, 0x7f7f7f7f);
+    };
+
+    // Epilogue stores share the in-order vmcnt counter with the copies.  At the S - 2 stage boundaries that
+    // follow an epilogue the wanted copies are older than its stores, so the stores may stay outstanding if
+    // the wait allows for their exact number (known for interior tiles of the fixed epilogues).
+    constexpr int SPU = Epi::generic ? 0 : (Epi::out == MKQ_F32 ? 2 : 1);
+    constexpr int EPI_STORES = TN * 2 * TM * SPU;
+    constexpr int N0 = (S - 2) * LPW, N1 = N0 + EPI_STORES + SC;
+    constexpr bool ASYNC_STORES = !Epi::generic && S >= 3 && N1 <= 63;
+    int stores_pending = 0;
+
+    // prologue: S stages and the first tile's scales in flight, stage 0 landed, its first k step in registers
+#pragma unroll
+    for (int i = 0; i < S; ++i) issue(i);
+    issue_scales(blockIdx.x);
+    wait_vmcnt<(S - 1) * LPW + SC>();
+    lds_barrier();
+    static_for<TM + TN>([&](auto uc) { read_one(0, IntC<0>{}, IntC<0>{}, uc); });
+    int slot = 0;
+    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
 #pragma unroll
         for (int j = 0; j < TM; ++j)
 #pragma unroll
             for (int t = 0; t < TN; ++t)
-                acc[j][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw[b][t], fa[b][j], acc[j][t], 3, 3, 0,
-                                                                            0x7f7f7f7f, 0, 0x7f7f7f7f);
-    };
-
-    // prologue: stages 0 and 1 in flight, stage 0 landed, its first k step in registers
 #pragma unroll
-    for (int i = 0; i < S; ++i) issue(i);
-    wait_vmcnt<(S - 1) * LPW>();
-    lds_barrier();
-    read_step(0, IntC<0>{}, IntC<0>{});
-    int slot = 0;
-    for (int s = 0; s < kt_count; ++s) {
-        const int nslot = (slot + 1 == S) ? 0 : slot + 1;
-        // k step 0 of stage s while its k step 1 is fetched
-        read_step(slot, IntC<1>{}, IntC<1>{});
-        multiply(IntC<0>{});
-        // stage s + 1 has landed (the S - 2 stages after it may still be in flight); past the barrier every
-        // wave holds all of stage s in registers, so its slot takes stage s + S
-        wait_vmcnt<(S - 2) * LPW>();
-        lds_barrier();
-        issue(slot);
-        read_step(nslot, IntC<0>{}, IntC<0>{});
-        multiply(IntC<1>{});
-        slot = nslot;
+                for (int v = 0; v < 16; ++v) acc[j][t][v] = 0.0f;
+        for (int s = 0; s < kt_count; ++s) {
+            const int nslot = (slot + 1 == S) ? 0 : slot + 1;
+            // k step 0 of the stage; one fragment block of its k step 1 is fetched behind each of the first
+            // six MFMAs
+            static_for<TM * TN>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                mfma_one(IntC<0>{}, ic);
+                if constexpr (i < TM + TN) read_one(slot, IntC<1>{}, IntC<1>{}, ic);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            // two MFMAs of k step 1 keep the matrix pipe busy across the boundary
+            mfma_one(IntC<1>{}, IntC<0>{});
+            mfma_one(IntC<1>{}, IntC<1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            // boundary: the next stage has landed (the S - 2 stages after it may still be in flight); past
+            // the barrier every wave holds all of this stage in registers, so its slot takes the stage S
+            // further on -- except behind a tile's last stage, where the slot first serves the epilogue
+            if (ASYNC_STORES && stores_pending > 0) {
+                wait_vmcnt<ASYNC_STORES ? N1 : 0>();
+                --stores_pending;
+            } else {
+                wait_vmcnt<N0>();
+            }
+            lds_barrier();
+            if (s + 1 < kt_count) issue(slot);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<TM * TN - 2>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                read_one(nslot, IntC<0>{}, IntC<0>{}, ic);
+                mfma_one(IntC<1>{}, IntC<i + 2>{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            slot = nslot;
+        }
+
+        const int done_slot = (slot == 0) ? S - 1 : slot - 1;  // idle: read by every wave, not yet refilled
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, tm, tn);
+        v16i acci[TM][TN];
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acci[j][t][v] = (int)acc[j][t][v];  // exact: integers below 2^24
+        if constexpr (Epi::generic) {
+            gemm_i4_epilogue<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, fr, fh);
+        } else {
+            // the scale copies are older than every stage copy issued during the tile; a one-stage tile
+            // issues none
+            if (kt_count < 2) wait_vmcnt<0>();
+            gemm_i4_epilogue_rows<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, lane,
+                                            smem + done_slot * Cfg::STAGE_BYTES + wave * 4096, sc_lds);
+        }
+        const bool interior = (tm + 1) * BM <= p.M && (tn + 1) * BN <= p.N;
+        stores_pending = (ASYNC_STORES && interior) ? S - 2 : 0;
+        lds_barrier();  // every wave is done with its share of the slot
+        issue(done_slot);
+        issue_scales(tile + (int)gridDim.x < total_tiles ? tile + (int)gridDim.x : tile);
+        // the next stage's first k step is fetched again rather than kept in registers across the epilogue
+        static_for<TM + TN>([&](auto uc) { read_one(slot, IntC<0>{}, IntC<0>{}, uc); });
     }
     wait_vmcnt<0>();  // the trailing copies must land before the LDS is released
-
-    v16i acci[TM][TN];
-#pragma unroll
-    for (int j = 0; j < TM; ++j)
-#pragma unroll
-        for (int t = 0; t < TN; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acci[j][t][v] = (int)acc[j][t][v];  // exact: integers below 2^24
-    if constexpr (Epi::generic) {
-        gemm_i4_epilogue<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, fr, fh);
-    } else {
-        // the row epilogue through LDS: the ring is idle now; once every wave has left the k loop each wave
-        // takes 4 KiB of it for the transposition and 512 bytes for its channels' scales and biases
-        lds_barrier();
-        uint8_t *const scr = smem + wave * 4096;
-        float *const sc_lds = reinterpret_cast<float *>(smem + WAVES * 4096 + wave * 512);
-        {
-            int n = tn * BN + wn * Cfg::WTN + lane;  // WTN = 64: one channel per lane
-            n = n < p.N ? n : p.N - 1;
-            sc_lds[lane] = p.s_w[n];
-            sc_lds[EpiShuffle<Cfg>::BIAS_AT + lane] = p.bias ? p.bias[n] : 0.0f;
-        }
-        gemm_i4_epilogue_rows<Cfg, Epi>(p, acci, tm * BM, tn * BN, wm, wn, lane, scr, sc_lds);
-    }
 }
 
 template <class Cfg, class Epi>
@@ -1534,14 +1599,25 @@ static int launch_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    constexpr int lds = Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS;
+    static_assert(lds <= 160 * 1024, "LDS is 160 KiB per CU");
     static bool ready = false;
     if (!ready) {
         if (hipFuncSetAttribute((const void *)gemm_e3m2_kernel<Cfg, Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Cfg::LDS_BYTES) != hipSuccess)
+                                lds) != hipSuccess)
             return MKQ_ERR_HIP;
+        if (g_num_cus == 0) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+                return MKQ_ERR_HIP;
+            g_num_cus = cus;
+        }
         ready = true;
     }
-    gemm_e3m2_kernel<Cfg, Epi><<<(unsigned)tiles, Cfg::THREADS, Cfg::LDS_BYTES, st>>>(p);
+    const int64_t resident = (int64_t)g_num_cus * ((160 * 1024) / lds);
+    const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
+    gemm_e3m2_kernel<Cfg, Epi><<<grid, Cfg::THREADS, lds, st>>>(p);
     return launch_status();
 }
 

@@ -104,15 +104,27 @@ def test_float_in_requant_and_residual(mkq):
     assert np.array_equal(oracle.unpack_nibbles(to_np(r["out"]), N), ref["q"])
 
 
-def test_large_m_sampled_rows(mkq):
+@pytest.mark.parametrize("M,N,K,od,with_bias", [(16384, 4096, 1024, 2, False), (16384, 4096, 128, 1, True),
+                                                 (8200, 4104, 256, 0, True), (8200, 4104, 384, 2, False),
+                                                 (4099, 8192, 2048, 2, True)])
+@pytest.mark.parametrize("cfg", [41, 42])
+def test_large_m_sampled_rows(mkq, cfg, M, N, K, od, with_bias):
+    """More tiles than resident workgroups: every workgroup walks several tiles (one-stage tiles, ragged
+    edges in both directions, both tile shapes), checked on sampled rows."""
     import torch
-    M, K, N = 16384, 1024, 4096
-    A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, seed=9)
-    out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    mkq.mkq_linear_int4_e3m2(mkq.mkq_pack_codes_e3m2(to_dev(A)), s_x, mkq.mkq_pack_codes_e3m2(to_dev(Wc)), to_dev(s_w),
-                             None, mkq.MKQ_BF16, out=out)
-    torch.cuda.synchronize()
-    rows = np.unique(np.concatenate([[0, 255, 256, 257, M - 257, M - 1], np.random.default_rng(2).integers(0, M, 40)]))
+    A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, seed=9 + K)
+    b = np.random.default_rng(K).normal(0, 0.3, N).astype(np.float32) if with_bias else None
+    tdt = {0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[od]
+    out = torch.empty((M, N), dtype=tdt, device="cuda")
+    mkq.debug_set_gemm_config(cfg)  # 41: 256 x 256 tiles, 42: 256 x 128
+    try:
+        mkq.mkq_linear_int4_e3m2(mkq.mkq_pack_codes_e3m2(to_dev(A)), s_x, mkq.mkq_pack_codes_e3m2(to_dev(Wc)),
+                                 to_dev(s_w), None if b is None else to_dev(b), od, out=out)
+        torch.cuda.synchronize()
+    finally:
+        mkq.debug_set_gemm_config(-1)
+    rows = np.unique(np.concatenate([[0, 255, 256, 257, M - 257, M - 2, M - 1],
+                                     np.random.default_rng(2).integers(0, M, 40)]))
     got = to_np(out[torch.from_numpy(rows).cuda()]).astype(np.float32)
-    ref = oracle.linear_int4(A[rows], s_x, Wc, s_w, None, out_dtype=oracle.BF16)
+    ref = oracle.linear_int4(A[rows], s_x, Wc, s_w, b, out_dtype=od)
     assert np.array_equal(got, ref["y"])
