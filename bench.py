@@ -255,7 +255,9 @@ def main():
     print(json.dumps(out))
 
 
-LARGE_M_SHAPES = [(16384, 1024, 4096), (16384, 4096, 1024), (16384, 768, 3072), (65536, 1024, 4096)]
+# (M, K, N): BASELINE configs[4] and, last, a long-K square where the k loop outweighs the per-tile costs
+LARGE_M_SHAPES = [(16384, 1024, 4096), (16384, 4096, 1024), (16384, 768, 3072), (65536, 1024, 4096),
+                  (8192, 8192, 8192)]
 CALIBRATION_SHAPE = (16384, 4096)  # one activation tensor of the large-M sweep
 
 
@@ -273,9 +275,15 @@ def profile_launches(mkq, which, launches=5):
             for _ in range(launches):
                 mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_BF16, out=out)
             torch.cuda.synchronize()
+            # the experimental 6-bit float route of the same linear
+            a6 = mkq.mkq_pack_codes_e3m2(torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda"))
+            w6 = mkq.mkq_pack_codes_e3m2(torch.randint(-8, 8, (N, K), dtype=torch.int8, device="cuda"))
+            for _ in range(launches):
+                mkq.mkq_linear_int4_e3m2(a6, 0.01, w6, sw, None, mkq.MKQ_BF16, out=out)
+            torch.cuda.synchronize()
             done.append({"M": M, "K": K, "N": N, "launches": launches, "ops_per_launch": 2.0 * M * N * K,
                          "grid_threads": None})
-            del a, w, out
+            del a, w, out, a6, w6
     elif which == "calibration":
         M, K = CALIBRATION_SHAPE
         x = torch.randn((M, K), dtype=torch.float16, device="cuda")
