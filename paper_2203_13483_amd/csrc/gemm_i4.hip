@@ -410,7 +410,7 @@ struct EpiLines16 {
                                    (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16);
 };
 
-template <class Cfg, class Epi, class AccV>
+template <class Cfg, class Epi, bool CACHE_SCALES = true, class AccV>
 __device__ __forceinline__ void gemm_epilogue_lines16(const GemmI4Params &p, AccV (&acc)[Cfg::TM][Cfg::TN],
                                                       int m0, int n0, int wm, int wn, int lane, uint8_t *scr,
                                                       float *sc_lds)
@@ -422,22 +422,25 @@ __device__ __forceinline__ void gemm_epilogue_lines16(const GemmI4Params &p, Acc
     sc_lds[lane] = (p.s_x * sc_lds[lane]) * p.acc_unit;
     if (!p.bias) sc_lds[Sh::BIAS_AT + lane] = 0.0f;
 
-    // the lane's 32 channels: register 8h + e of tile t is channel 32t + 16h + 8fh + e
-    float sc[TN][16], bi[TN][16];
+    // the lane's 32 channels: register 8h + e of tile t is channel 32t + 16h + 8fh + e.  Their scales and
+    // biases are either held in 64 registers for the whole tile or fetched again for every 8 values.
+    auto load8 = [&](int t, int h, float (&s8)[8], float (&b8)[8]) {
 #pragma unroll
-    for (int t = 0; t < TN; ++t)
+        for (int q = 0; q < 2; ++q) {
+            const int c = 32 * t + 16 * h + 8 * fh + 4 * q;
+            const float4 s4 = *reinterpret_cast<const float4 *>(sc_lds + c);
+            const float4 b4 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c);
+            s8[4 * q] = s4.x; s8[4 * q + 1] = s4.y; s8[4 * q + 2] = s4.z; s8[4 * q + 3] = s4.w;
+            b8[4 * q] = b4.x; b8[4 * q + 1] = b4.y; b8[4 * q + 2] = b4.z; b8[4 * q + 3] = b4.w;
+        }
+    };
+    float sc[CACHE_SCALES ? TN * 2 : 1][8], bi[CACHE_SCALES ? TN * 2 : 1][8];
+    if constexpr (CACHE_SCALES) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int t = 0; t < TN; ++t)
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int c = 32 * t + 16 * h + 8 * fh + 4 * q;
-                const float4 s4 = *reinterpret_cast<const float4 *>(sc_lds + c);
-                const float4 b4 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c);
-                sc[t][8 * h + 4 * q] = s4.x; sc[t][8 * h + 4 * q + 1] = s4.y;
-                sc[t][8 * h + 4 * q + 2] = s4.z; sc[t][8 * h + 4 * q + 3] = s4.w;
-                bi[t][8 * h + 4 * q] = b4.x; bi[t][8 * h + 4 * q + 1] = b4.y;
-                bi[t][8 * h + 4 * q + 2] = b4.z; bi[t][8 * h + 4 * q + 3] = b4.w;
-            }
+            for (int h = 0; h < 2; ++h) load8(t, h, sc[2 * t + h], bi[2 * t + h]);
+    }
     // writer: 16-byte piece 4t + 2h + fh of row fr; pieces are XOR-swizzled with bits 1 .. 3 of the row so
     // that 16 consecutive rows spread one piece column over all banks.  reader: row lane / 8 + 8i, piece lane % 8.
     const int wr_base = fr * 128, wr_key = (fr >> 1) & 7;
@@ -451,11 +454,14 @@ __device__ __forceinline__ void gemm_epilogue_lines16(const GemmI4Params &p, Acc
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 uint32_t hw[4];
+                constexpr int u = CACHE_SCALES ? 1 : 0;
+                if constexpr (!CACHE_SCALES) load8(t, h, sc[0], bi[0]);
+                const float(&s8)[8] = sc[u * (2 * t + h)];
+                const float(&b8)[8] = bi[u * (2 * t + h)];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float y0 = __fmaf_rn((float)acc[j][t][8 * h + 2 * e], sc[t][8 * h + 2 * e], bi[t][8 * h + 2 * e]);
-                    float y1 = __fmaf_rn((float)acc[j][t][8 * h + 2 * e + 1], sc[t][8 * h + 2 * e + 1],
-                                         bi[t][8 * h + 2 * e + 1]);
+                    float y0 = __fmaf_rn((float)acc[j][t][8 * h + 2 * e], s8[2 * e], b8[2 * e]);
+                    float y1 = __fmaf_rn((float)acc[j][t][8 * h + 2 * e + 1], s8[2 * e + 1], b8[2 * e + 1]);
                     asm volatile("" : "+v"(y0), "+v"(y1));  // keep the binary32 rounding (no fused narrowing)
                     hw[e] = (Epi::out == MKQ_F16) ? pack2_f16(y0, y1) : pack2_bf16(y0, y1);
                 }
@@ -1057,11 +1063,16 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
                     // them (INFLIGHT stages, or one per stage of a shorter tile) may be in flight
                     if (kt_count >= INFLIGHT) wait_vmcnt<INFLIGHT * LPW>();
                     else wait_vmcnt<LPW>();
-                    // (the 16-bit line epilogue measured slower in this kernel: 82 against 71 us at M = 16384,
-                    // N = 4096, K = 1024)
-                    gemm_i4_epilogue_rows<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, lane,
-                                                    smem + done_slot * Cfg::STAGE_BYTES +
-                                                        wave * EpiShuffle<Cfg>::REGION, sc_lds);
+                    // plain 16-bit outputs of 64-channel waves take the line epilogue, without its register
+                    // cache of the scales (with it this kernel spills)
+                    if constexpr (EpiLines16<Cfg, Epi>::usable)
+                        gemm_epilogue_lines16<Cfg, Epi, false>(p, acc, tile_m * BM, tile_n * BN, wm, wn, lane,
+                                                               smem + done_slot * Cfg::STAGE_BYTES +
+                                                                   wave * EpiShuffle<Cfg>::REGION, sc_lds);
+                    else
+                        gemm_i4_epilogue_rows<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, lane,
+                                                        smem + done_slot * Cfg::STAGE_BYTES +
+                                                            wave * EpiShuffle<Cfg>::REGION, sc_lds);
                 } else {
                     gemm_i4_epilogue<Cfg, Epi>(p, acc, tile_m * BM, tile_n * BN, wm, wn, fr, fh);
                 }
