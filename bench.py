@@ -353,9 +353,9 @@ def side_measurements(mkq, event_time):
         res["large_m"].append(row)
         del a8, w8, a16, w16, out
 
-    # small M: every call reads a different weight matrix from a pool larger than the
-    # 256 MB last-level cache, so the weights always come from HBM
-    for (K, N, pool, Ms) in ((4096, 4096, 80, (1, 16, 64, 128, 512)), (8192, 8192, 24, (16, 64))):
+    # small M: every call reads a different weight matrix from a 1 GiB pool (4 x the 256 MB
+    # last-level cache), so the weights always come from HBM
+    for (K, N, pool, Ms) in ((4096, 4096, 128, (1, 16, 64, 128, 512)), (8192, 8192, 32, (16, 64))):
         ws = [torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda") for _ in range(pool)]
         sw = torch.rand(N, device="cuda") * 0.049 + 0.001
         for M in Ms:
@@ -426,6 +426,32 @@ def side_measurements(mkq, event_time):
         row["fp16_over_int4"] = row["fp16_us"] / row["int4_us"]
         row["vendor_fp16_over_int4"] = row["vendor_fp16_us"] / row["int4_us"]
         res["table2_token_counts"].append(row)
+
+    # The four linears of a layer of the paper's 4-layer student (hidden 312, FFN 1200: K is not a
+    # multiple of 32, operands are stored padded with zero codes to a multiple of 128), float activations in: quantize + GEMM
+    res["tinybert4_linears"] = []
+    H, F = 312, 1200
+    for M in (440, 2298, 4096):
+        row = {"M": M, "int4_us": 0.0, "vendor_fp16_us": 0.0}
+        for (K, N) in ((H, 3 * H), (H, H), (H, F), (F, H)):
+            x16 = torch.randn(M, K, device="cuda", dtype=torch.float16)
+            w32 = torch.randn(N, K, device="cuda") * 0.02
+            b32 = torch.zeros(N, device="cuda")
+            w4, sw = mkq.mkq_pack_weights_int4_padded(w32)
+            Kp = mkq.mkq_padded_k(K)
+            a4 = torch.empty((M, Kp // 2), dtype=torch.uint8, device="cuda")
+            o16 = torch.empty((M, N), dtype=torch.float16, device="cuda")
+
+            def lin():
+                mkq.mkq_quantize_padded(x16, 0.34, q_out=a4)
+                mkq.mkq_linear_int4(a4, 0.34, w4, sw, b32, N, Kp, mkq.MKQ_F16, out=o16)
+
+            row["int4_us"] += graph_time(lin, repeats=5) * 1e6
+            w16, b16 = w32.half(), b32.half()
+            torch.nn.functional.linear(x16, w16, b16)
+            row["vendor_fp16_us"] += graph_time(lambda: torch.nn.functional.linear(x16, w16, b16), repeats=5) * 1e6
+        row["vendor_fp16_over_int4"] = row["vendor_fp16_us"] / row["int4_us"]
+        res["tinybert4_linears"].append(row)
 
     # One BERT-base layer on padding-free batches with the batch sizes and valid-token counts of the
     # paper's Table 2 (seeded sequence lengths <= 128), in 4 bits, 8 bits and binary16

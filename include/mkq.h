@@ -104,6 +104,20 @@ size_t mkq_packed_weight_bytes(int64_t N, int64_t K);
 int mkq_pack_weights_int4(const float *W, int64_t N, int64_t K, const float *s_w_in,
                           float *s_w_out, uint8_t *Wq_out, void *stream);
 
+/* Reduction lengths that are not a multiple of 32 (the 4-layer student of section 5.2 has hidden size
+ * 312 and FFN size 1200): both operands are stored with rows padded to mkq_padded_k(K) codes, the
+ * smallest multiple of 128 >= K (whole 64-byte stages of the tile kernels), the padding codes being
+ * zero, which adds nothing to any dot product.  The padded variants of the quantizer and of the weight
+ * preparation take K % 8 == 0, compute exactly what their plain counterparts compute on the K real
+ * columns (abs-max over the real columns only) and write rows of mkq_padded_k(K) / 2 bytes;
+ * mkq_linear_int4 is then called with K = mkq_padded_k(K) on pre-quantized activations.  Same errors
+ * as the plain variants (SHAPE on K % 8 instead of K % 32). */
+int64_t mkq_padded_k(int64_t K);
+int mkq_quantize_padded(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx, float s_x,
+                        uint8_t *q_out, void *stream);
+int mkq_pack_weights_int4_padded(const float *W, int64_t N, int64_t K, const float *s_w_in,
+                                 float *s_w_out, uint8_t *Wq_out, void *stream);
+
 /* Packs already-quantized int8 codes (values in [-8, 7]; higher bits are
  * discarded) of a [rows, K] matrix into the weight / activation layout. */
 int mkq_pack_codes_int4(const int8_t *codes, int64_t rows, int64_t K, uint8_t *q_out, void *stream);

@@ -21,6 +21,7 @@ MKQ_ACT_NONE, MKQ_ACT_GELU = 0, 1
 EXPORTS = [
     "mkq_status_string", "mkq_version", "mkq_quantize", "mkq_absmax_scale",
     "mkq_packed_weight_bytes", "mkq_pack_weights_int4", "mkq_pack_codes_int4",
+    "mkq_padded_k", "mkq_quantize_padded", "mkq_pack_weights_int4_padded",
     "mkq_unpack_weights_int4", "mkq_linear_int4_workspace_bytes", "mkq_linear_int4",
     "mkq_quantize_int8", "mkq_pack_weights_int8", "mkq_linear_int8", "mkq_bert_layer_int8_workspace",
     "mkq_bert_layer_int8", "mkq_layernorm_int8", "mkq_attention_int8",
@@ -89,6 +90,9 @@ def load() -> C.CDLL:
         "mkq_percentile_scale": (ci, [vp, ci, i64, i64, i64, i64, ci, vp, vp, sz, vp]),
         "mkq_pack_weights_int4": (ci, [vp, i64, i64, vp, vp, vp, vp]),
         "mkq_pack_codes_int4": (ci, [vp, i64, i64, vp, vp]),
+        "mkq_padded_k": (i64, [i64]),
+        "mkq_quantize_padded": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
+        "mkq_pack_weights_int4_padded": (ci, [vp, i64, i64, vp, vp, vp, vp]),
         "mkq_unpack_weights_int4": (ci, [vp, i64, i64, vp, vp]),
         "mkq_linear_int4_workspace_bytes": (sz, [i64, i64, i64, ci]),
         "mkq_linear_int4": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
@@ -232,6 +236,33 @@ def mkq_pack_weights_int4(W, s_w_in=None, stream=None):
     s_w = torch.empty(N, dtype=torch.float32, device=W.device)
     _check(load().mkq_pack_weights_int4(_ptr(W), N, K, _ptr(s_w_in), _ptr(s_w), _ptr(Wq),
                                         _stream(stream)), "mkq_pack_weights_int4")
+    return Wq, s_w
+
+
+def mkq_padded_k(K: int) -> int:
+    """Smallest multiple of 128 >= K: the row length, in codes, of operands stored with zero padding."""
+    return int(load().mkq_padded_k(K))
+
+
+def mkq_quantize_padded(x, s_x: float, q_out=None, stream=None):
+    """x [M,K] float32/float16, K % 8 == 0 -> packed codes uint8 [M, mkq_padded_k(K)/2], zero codes past K."""
+    torch = _torch()
+    M, K = x.shape
+    if q_out is None:
+        q_out = torch.empty((M, mkq_padded_k(K) // 2), dtype=torch.uint8, device=x.device)
+    _check(load().mkq_quantize_padded(_ptr(x), _dtype_code(x), M, K, x.stride(0), float(s_x), _ptr(q_out),
+                                      _stream(stream)), "mkq_quantize_padded")
+    return q_out
+
+
+def mkq_pack_weights_int4_padded(W, s_w_in=None, stream=None):
+    """W [N,K] float32, K % 8 == 0 -> (Wq uint8 [N * mkq_padded_k(K)/2], s_w float32 [N])."""
+    torch = _torch()
+    N, K = W.shape
+    Wq = torch.empty(max(N * mkq_padded_k(K) // 2, 1), dtype=torch.uint8, device=W.device)
+    s_w = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(load().mkq_pack_weights_int4_padded(_ptr(W), N, K, _ptr(s_w_in), _ptr(s_w), _ptr(Wq),
+                                               _stream(stream)), "mkq_pack_weights_int4_padded")
     return Wq, s_w
 
 

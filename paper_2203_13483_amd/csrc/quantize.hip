@@ -16,18 +16,23 @@ __device__ __forceinline__ uint32_t pack8(const int (&c)[8])
     return w;
 }
 
-// Eq. 1 with a per-tensor step: x [M,K] (row stride ldx) -> packed codes [M,K/2].
+// Eq. 1 with a per-tensor step: x [M,K] (row stride ldx) -> packed codes [M,Kp/2]; codes K .. Kp-1 of a
+// row are zero (Kp >= K: a row padded to the GEMM's granularity of k adds nothing to any dot product).
 template <typename T>
 __global__ __launch_bounds__(256) void quantize_kernel(const T *__restrict__ x, int64_t M, int64_t K,
                                                        int64_t ldx, float s,
-                                                       uint32_t *__restrict__ q)
+                                                       uint32_t *__restrict__ q, int64_t Kp)
 {
-    const int64_t words_per_row = K / 8;
+    const int64_t words_per_row = Kp / 8;
     const int64_t total = M * words_per_row;
     for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < total;
          w += (int64_t)gridDim.x * blockDim.x) {
         const int64_t m = w / words_per_row;
         const int64_t kw = w - m * words_per_row;
+        if (kw * 8 >= K) {
+            q[w] = 0u;
+            continue;
+        }
         float v[8];
         load8<T>(x + m * ldx + kw * 8, v);
         int c[8];
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(256) void absmax_rows_kernel(const T *__restrict__ 
 __global__ __launch_bounds__(256) void pack_weights_kernel(const float *__restrict__ W, int64_t K,
                                                            const float *__restrict__ s_in,
                                                            float *__restrict__ s_out,
-                                                           uint32_t *__restrict__ q)
+                                                           uint32_t *__restrict__ q, int64_t Kp)
 {
     __shared__ float part[4];
     const int64_t n = blockIdx.x;
@@ -155,8 +160,12 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float *__restri
         s = (mx > 0.0f) ? mx / (float)QMAX : 1.0f;
     }
     if (threadIdx.x == 0) s_out[n] = s;
-    uint32_t *qrow = q + n * (K / 8);
-    for (int64_t k = (int64_t)threadIdx.x * 8; k < K; k += (int64_t)blockDim.x * 8) {
+    uint32_t *qrow = q + n * (Kp / 8);  // codes K .. Kp-1 are zero
+    for (int64_t k = (int64_t)threadIdx.x * 8; k < Kp; k += (int64_t)blockDim.x * 8) {
+        if (k >= K) {
+            qrow[k / 8] = 0u;
+            continue;
+        }
         float v[8];
         load8<float>(row + k, v);
         int c[8];
@@ -402,10 +411,35 @@ extern "C" int mkq_quantize(const void *x, int x_dtype, int64_t M, int64_t K, in
     const int grid = grid_for(words);
     if (x_dtype == MKQ_F32)
         quantize_kernel<float><<<grid, 256, 0, as_stream(stream)>>>(
-            (const float *)x, M, K, ldx, s_x, (uint32_t *)q_out);
+            (const float *)x, M, K, ldx, s_x, (uint32_t *)q_out, K);
     else
         quantize_kernel<__half><<<grid, 256, 0, as_stream(stream)>>>(
-            (const __half *)x, M, K, ldx, s_x, (uint32_t *)q_out);
+            (const __half *)x, M, K, ldx, s_x, (uint32_t *)q_out, K);
+    return launch_status();
+}
+
+extern "C" int64_t mkq_padded_k(int64_t K)
+{
+    return K <= 0 ? 0 : (K + 127) / 128 * 128;  // whole 64-byte stages: the fast tile kernels apply
+}
+
+extern "C" int mkq_quantize_padded(const void *x, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                                   float s_x, uint8_t *q_out, void *stream)
+{
+    if (x_dtype != MKQ_F32 && x_dtype != MKQ_F16) return MKQ_ERR_DTYPE;
+    if (M < 0 || K < 0 || (K % 8) != 0 || ldx < K || (ldx % 8) != 0) return MKQ_ERR_SHAPE;
+    if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
+    if (M == 0 || K == 0) return MKQ_OK;
+    if (!x || !q_out) return MKQ_ERR_NULL;
+    if (!aligned16(x) || !aligned16(q_out)) return MKQ_ERR_ALIGN;
+    const int64_t Kp = mkq_padded_k(K);
+    const int grid = grid_for(M * (Kp / 8));
+    if (x_dtype == MKQ_F32)
+        quantize_kernel<float><<<grid, 256, 0, as_stream(stream)>>>(
+            (const float *)x, M, K, ldx, s_x, (uint32_t *)q_out, Kp);
+    else
+        quantize_kernel<__half><<<grid, 256, 0, as_stream(stream)>>>(
+            (const __half *)x, M, K, ldx, s_x, (uint32_t *)q_out, Kp);
     return launch_status();
 }
 
@@ -451,7 +485,21 @@ extern "C" int mkq_pack_weights_int4(const float *W, int64_t N, int64_t K, const
         (reinterpret_cast<uintptr_t>(s_w_in) & 3u))
         return MKQ_ERR_ALIGN;
     pack_weights_kernel<<<(int)N, 256, 0, as_stream(stream)>>>(W, K, s_w_in, s_w_out,
-                                                               (uint32_t *)Wq_out);
+                                                               (uint32_t *)Wq_out, K);
+    return launch_status();
+}
+
+extern "C" int mkq_pack_weights_int4_padded(const float *W, int64_t N, int64_t K, const float *s_w_in,
+                                            float *s_w_out, uint8_t *Wq_out, void *stream)
+{
+    if (!W || !s_w_out || !Wq_out) return MKQ_ERR_NULL;
+    if (N <= 0 || K <= 0 || (K % 8) != 0) return MKQ_ERR_SHAPE;
+    if (N > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
+    if (!aligned16(W) || !aligned16(Wq_out) || (reinterpret_cast<uintptr_t>(s_w_out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(s_w_in) & 3u))
+        return MKQ_ERR_ALIGN;
+    pack_weights_kernel<<<(int)N, 256, 0, as_stream(stream)>>>(W, K, s_w_in, s_w_out,
+                                                               (uint32_t *)Wq_out, mkq_padded_k(K));
     return launch_status();
 }
 

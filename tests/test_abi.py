@@ -196,3 +196,21 @@ def test_padding_free_argument_errors(lib):
     lay.total_tokens, lay.next_bits = 230, 5
     assert lib.mkq_bert_layer_int4(C.byref(lay), P, mkq.MKQ_F16, None, P, None, P, 1 << 30, None) in (
         mkq.MKQ_ERR_SCALE, mkq.MKQ_ERR_DTYPE)
+
+
+def test_padded_k_argument_errors(lib):
+    assert lib.mkq_padded_k(312) == 384 and lib.mkq_padded_k(1200) == 1280
+    assert lib.mkq_padded_k(768) == 768 and lib.mkq_padded_k(8) == 128 and lib.mkq_padded_k(0) == 0
+    q = lib.mkq_quantize_padded
+    assert q(None, mkq.MKQ_F16, 4, 312, 312, 1.0, P, None) == mkq.MKQ_ERR_NULL
+    assert q(P, mkq.MKQ_BF16, 4, 312, 312, 1.0, P, None) == mkq.MKQ_ERR_DTYPE
+    assert q(P, mkq.MKQ_F32, 4, 316, 320, 1.0, P, None) == mkq.MKQ_ERR_SHAPE   # K % 8
+    assert q(P, mkq.MKQ_F32, 4, 312, 304, 1.0, P, None) == mkq.MKQ_ERR_SHAPE   # ldx < K
+    assert q(P, mkq.MKQ_F32, 4, 312, 312, 0.0, P, None) == mkq.MKQ_ERR_SCALE
+    assert q(P, mkq.MKQ_F32, 4, 312, 312, 1.0, ODD, None) == mkq.MKQ_ERR_ALIGN
+    assert q(None, mkq.MKQ_F32, 0, 312, 312, 1.0, None, None) == mkq.MKQ_OK
+    w = lib.mkq_pack_weights_int4_padded
+    assert w(None, 8, 312, None, P, P, None) == mkq.MKQ_ERR_NULL
+    assert w(P, 8, 316, None, P, P, None) == mkq.MKQ_ERR_SHAPE
+    assert w(P, 0, 312, None, P, P, None) == mkq.MKQ_ERR_SHAPE
+    assert w(P, 8, 312, None, P, ODD, None) == mkq.MKQ_ERR_ALIGN
