@@ -427,6 +427,24 @@ def side_measurements(mkq, event_time):
         row["vendor_fp16_over_int4"] = row["vendor_fp16_us"] / row["int4_us"]
         res["table2_token_counts"].append(row)
 
+    # BASELINE configs[3]: the four GEMMs of a BERT-large layer at M = 8192 (batch 16 x seq 512), int4 codes
+    # in, fused re-quantization to int4 codes out (GELU on FFN-up)
+    res["bert_large_gemms_int4_chain"] = []
+    M = 8192
+    for (name, K, N, act) in (("qkv", 1024, 3072, mkq.MKQ_ACT_NONE), ("attn_out", 1024, 1024, mkq.MKQ_ACT_NONE),
+                              ("ffn_up_gelu", 1024, 4096, mkq.MKQ_ACT_GELU), ("ffn_down", 4096, 1024, mkq.MKQ_ACT_NONE)):
+        a4 = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
+        w4 = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
+        sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+        b32 = torch.randn(N, device="cuda") * 0.01
+        o4 = torch.empty((M, N // 2), dtype=torch.uint8, device="cuda")
+        t = graph_time(lambda: mkq.mkq_linear_int4(a4, 0.01, w4, sw, b32, N, K, mkq.MKQ_I4, act=act, s_next=0.3,
+                                                   out=o4), repeats=5)
+        res["bert_large_gemms_int4_chain"].append({"linear": name, "M": M, "K": K, "N": N, "us": t * 1e6,
+                                                    "TOPS": 2.0 * M * N * K / t / 1e12,
+                                                    "frac_int8_peak": 2.0 * M * N * K / t / 1e12 / INT8_MFMA_PEAK_TOPS})
+        del a4, w4, o4
+
     # The four linears of a layer of the paper's 4-layer student (hidden 312, FFN 1200: K is not a
     # multiple of 32, operands are stored padded with zero codes to a multiple of 128), float activations in: quantize + GEMM
     res["tinybert4_linears"] = []
