@@ -295,6 +295,9 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
         sc_lds[c] = (p.s_x * sc_lds[c]) * p.acc_unit;
         if (!p.bias) sc_lds[Sh::BIAS_AT + c] = 0.0f;
     }
+    QuantStep qs4 = {}, qs8 = {};
+    if constexpr (Epi::out == MKQ_I4) qs4 = quant_step<4>(p.s_next);
+    if constexpr (Epi::out == MKQ_I8) qs8 = quant_step<8>(p.s_next);
     // writer: the lane's 8 values of unit G are pieces 4G + 2fh, 4G + 2fh + 1 of row fr
     const int wr_base = fr * 128;
     const int wr_key = fr & 7;
@@ -385,13 +388,13 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
                 } else if (Epi::out == MKQ_I8) {
                     int cd[8];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(y[e], p.s_next);
+                    for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(y[e], qs8);
                     if (ok) *reinterpret_cast<uint2 *>((uint8_t *)p.out + o) = bytes8(cd);
                 } else {
                     uint32_t packed = 0;  // Eq. 1 on the binary32 value
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        packed |= ((uint32_t)quantize_code(y[e], p.s_next) & 0xFu) << (4 * e);
+                        packed |= ((uint32_t)quantize_code_rs<4>(y[e], qs4) & 0xFu) << (4 * e);
                     if (ok) *reinterpret_cast<uint32_t *>((uint8_t *)p.out + (o >> 1)) = packed;
                 }
             }

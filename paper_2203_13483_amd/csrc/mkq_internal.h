@@ -31,6 +31,43 @@ __device__ __forceinline__ int quantize_code(float x, float s)
     return (int)__builtin_rintf(v);     // v_rndne_f32
 }
 
+// The same code for many values under one step, without a division per value.  With rs = RN(1/s),
+// q = RN(x * rs) differs from the exact quotient x/s by at most |x/s| * 2^-23 (two roundings), and the
+// correctly rounded quotient differs from it by at most |x/s| * 2^-24; inside the clamp range that is
+// less than `margin` in all.  So unless q lies within `margin` of a rounding boundary k + 1/2, the
+// correctly rounded quotient rounds to the same integer (values beyond the clamp range clamp alike);
+// the rare value that does lie that close takes the division.  For steps outside [2^-100, 2^100]
+// (where 1/s could lose precision) the threshold is negative and every value takes the division.
+struct QuantStep {
+    float s, rs, thr;
+};
+template <int BITS>
+__device__ __forceinline__ QuantStep quant_step(float s)
+{
+    constexpr float margin = (BITS == 4) ? 2.0e-6f : 3.0e-5f;  // 1.5 * 2^-23 * 9 resp. * 129, rounded up
+    QuantStep q;
+    q.s = s;
+    q.rs = 1.0f / s;
+    q.thr = (s >= 0x1p-100f && s <= 0x1p100f) ? 0.5f - margin : -1.0f;
+    return q;
+}
+template <int BITS>
+__device__ __forceinline__ int quantize_code_rs(float x, const QuantStep &q)
+{
+    constexpr float lo = (BITS == 4) ? (float)QMIN : -128.0f, hi = (BITS == 4) ? (float)QMAX : 127.0f;
+    float v = x * q.rs;
+    v = (v != v) ? 0.0f : v;
+    v = fminf(fmaxf(v, lo), hi);
+    const float r = __builtin_rintf(v);
+    if (__builtin_expect(fabsf(v - r) > q.thr, 0)) {
+        float w = x / q.s;
+        w = (w != w) ? 0.0f : w;
+        w = fminf(fmaxf(w, lo), hi);
+        return (int)__builtin_rintf(w);
+    }
+    return (int)r;
+}
+
 // Eq. 1 at 8 bits: clamp to [-128, 127]; 8 codes as 8 bytes, element 0 lowest.
 __device__ __forceinline__ int quantize_code8(float x, float s)
 {
@@ -128,26 +165,23 @@ __device__ __forceinline__ uint32_t pack2_f16(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, mkq_h2));
 }
 
-// erf in binary32 without branches: the exponential-times-polynomial form of Abramowitz &
-// Stegun 7.1.26, erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p x) for x >= 0
-// (absolute error of the formula <= 1.5e-7; v_rcp_f32 and v_exp_f32 add about 1e-7).
-__device__ __forceinline__ float erf_as(float x)
-{
-    const float ax = fabsf(x);
-    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, ax, 1.0f));
-    float p = __builtin_fmaf(1.061405429f, t, -1.453152027f);
-    p = __builtin_fmaf(p, t, 1.421413741f);
-    p = __builtin_fmaf(p, t, -0.284496736f);
-    p = __builtin_fmaf(p, t, 0.254829592f);
-    p *= t;
-    const float e = __builtin_amdgcn_exp2f(ax * ax * -1.4426950408889634f);
-    return __builtin_copysignf(__builtin_fmaf(-p, e, 1.0f), x);
-}
-
-// GELU, erf form, binary32 (activation functions stay in float32, section 5).
+// GELU, erf form, binary32 (activation functions stay in float32, section 5), without branches.
+// erf comes from the exponential-times-polynomial form of Abramowitz & Stegun 7.1.26,
+// erf(z) = 1 - (a1 t + ... + a5 t^5) exp(-z^2), t = 1 / (1 + p z) for z >= 0 (absolute error of the
+// formula <= 1.5e-7; v_rcp_f32 and v_exp_f32 add about 1e-7).  With z = |x| / sqrt(2) folded into the
+// constants, Phi(x) = 1 - u for x >= 0 and u for x < 0, u = (a1 t + ... + a5 t^5) exp(-x^2 / 2) / 2,
+// so  gelu(x) = x Phi(x) = max(x, 0) - |x| u.
 __device__ __forceinline__ float gelu_erf(float x)
 {
-    return 0.5f * x * (1.0f + erf_as(x * 0.70710678118654752440f));
+    const float ax = fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f * 0.70710678118654752440f, ax, 1.0f));
+    float p = __builtin_fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+    p = __builtin_fmaf(p, t, 0.5f * 1.421413741f);
+    p = __builtin_fmaf(p, t, 0.5f * -0.284496736f);
+    p = __builtin_fmaf(p, t, 0.5f * 0.254829592f);
+    p *= t;
+    const float e = __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.4426950408889634f));
+    return __builtin_fmaf(-ax, p * e, fmaxf(x, 0.0f));
 }
 
 }  // namespace mkq
