@@ -694,6 +694,27 @@ struct GemmI4DmaCfg : GemmI4Cfg<BM_, BN_, WGM_, WGN_, RB_> {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
 };
 
+// Exchange buffer of the K split: per pass every wave of a non-first group hands over TPP of its
+// 32x32 accumulator tiles (4 KiB each); tiles of 32x32 per wave need one pass, larger wave tiles go two
+// tiles at a time so that the buffer fits beside the groups' rings.
+template <class Cfg>
+struct KSplitXch {
+    static constexpr int TPP = (Cfg::TM * Cfg::TN >= 2) ? 2 : 1;
+    static_assert((Cfg::TM * Cfg::TN) % TPP == 0, "whole passes");
+    static constexpr int bytes(int ksplit) { return (ksplit - 1) * Cfg::WAVES * TPP * 4096; }
+    static constexpr int lds(int ksplit)
+    {
+        return ksplit * (Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS) + bytes(ksplit);
+    }
+    // waves per SIMD the register allocator may assume: the configuration's own, except for split
+    // workgroups of multi-tile waves, which are placed by their LDS footprint
+    static constexpr int waves_per_eu(int ksplit)
+    {
+        return (ksplit == 1 || Cfg::TM * Cfg::TN == 1) ? Cfg::WAVES_PER_EU
+                                                       : (160 * 1024 / lds(ksplit)) * Cfg::WAVES * ksplit / 4;
+    }
+};
+
 // log2 of the wave-priority time slice, in shader cycles (0 = off); 2^15 measured best (2-4 %)
 constexpr int PRIO_SLICE_LOG2 = 15;
 
@@ -706,12 +727,12 @@ constexpr int PRIO_SLICE_LOG2 = 15;
 // partial accumulators meet the first group's in LDS at the end of a tile and the first group
 // runs the epilogue.
 template <class Cfg, class Epi, int BITS, int KSPLIT = 1>
-__global__ __launch_bounds__(Cfg::THREADS * KSPLIT) __attribute__((amdgpu_waves_per_eu(Cfg::WAVES_PER_EU, Cfg::WAVES_PER_EU)))
+__global__ __launch_bounds__(Cfg::THREADS * KSPLIT)
+__attribute__((amdgpu_waves_per_eu(KSplitXch<Cfg>::waves_per_eu(KSPLIT), KSplitXch<Cfg>::waves_per_eu(KSPLIT))))
 void gemm_i4_dma_kernel(const GemmI4Params p)
 {
     static_assert(BITS == 4 || (BITS == 8 && Cfg::RB == 64), "8-bit operands use 64-byte stages");
-    static_assert(KSPLIT == 1 || ((KSPLIT == 2 || KSPLIT == 4) && Cfg::TM * Cfg::TN == 1),
-                  "the K split is built for 32x32 per wave");
+    static_assert(KSPLIT == 1 || KSPLIT == 2 || KSPLIT == 4, "one, two or four wave groups");
     constexpr int BM = Cfg::BM, BN = Cfg::BN, RB = Cfg::RB, CH = Cfg::CH;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     constexpr int S = Cfg::S, LPW = Cfg::LPW;
@@ -724,7 +745,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     const int grp = wave_all / Cfg::WAVES;   // K half of this wave's group (0 when KSPLIT == 1)
     const int wave = wave_all % Cfg::WAVES;
     // per group: the ring, then the scale / bias area of the row epilogue; after the groups: the
-    // exchange buffer of the K split (one 32x32 int32 tile per wave)
+    // exchange buffer of the K split
     constexpr int GROUP_LDS = Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS;
     uint8_t *const smem = smem_all + grp * GROUP_LDS;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
@@ -1037,25 +1058,39 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
             int tile_m, tile_n;
             tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
             if constexpr (KSPLIT > 1) {
-                // the other groups hand their partial sums over (16 registers per lane, 4 KiB per wave)
-                int *const xch = reinterpret_cast<int *>(smem_all + KSPLIT * GROUP_LDS) + wave * 1024 + lane * 4;
-                if (grp > 0) {
+                // the other groups hand their partial sums over, KSplitXch<Cfg>::TPP 32x32 tiles of a wave
+                // (16 registers per lane, 4 KiB per tile) per pass through the exchange buffer
+                constexpr int TPP = KSplitXch<Cfg>::TPP, PASSES = TM * TN / TPP;
+                int *const xch = reinterpret_cast<int *>(smem_all + KSPLIT * GROUP_LDS) + wave * (TPP * 1024) + lane * 4;
+                static_for<PASSES>([&](auto pc) {
+                    constexpr int pass = decltype(pc)::value;
+                    if (pass > 0) lds_barrier();  // the first group has read the previous pass
+                    if (grp > 0) {
+                        static_for<TPP>([&](auto uc) {
+                            constexpr int u = decltype(uc)::value, i = pass * TPP + u, j = i / TN, t = i % TN;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        *reinterpret_cast<int4 *>(xch + (grp - 1) * (Cfg::WAVES * 1024) + q * 256) =
-                            make_int4(acc[0][0][4 * q], acc[0][0][4 * q + 1], acc[0][0][4 * q + 2], acc[0][0][4 * q + 3]);
-                }
-                lds_barrier();
-                if (grp == 0) {
+                            for (int q = 0; q < 4; ++q)
+                                *reinterpret_cast<int4 *>(xch + (grp - 1) * (Cfg::WAVES * TPP * 1024) + u * 1024 + q * 256) =
+                                    make_int4(acc[j][t][4 * q], acc[j][t][4 * q + 1], acc[j][t][4 * q + 2],
+                                              acc[j][t][4 * q + 3]);
+                        });
+                    }
+                    lds_barrier();
+                    if (grp == 0) {
+                        static_for<TPP>([&](auto uc) {
+                            constexpr int u = decltype(uc)::value, i = pass * TPP + u, j = i / TN, t = i % TN;
 #pragma unroll
-                    for (int g = 0; g < KSPLIT - 1; ++g)
+                            for (int g = 0; g < KSPLIT - 1; ++g)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int4 t = *reinterpret_cast<const int4 *>(xch + g * (Cfg::WAVES * 1024) + q * 256);
-                            acc[0][0][4 * q] += t.x; acc[0][0][4 * q + 1] += t.y;
-                            acc[0][0][4 * q + 2] += t.z; acc[0][0][4 * q + 3] += t.w;
-                        }
-                }
+                                for (int q = 0; q < 4; ++q) {
+                                    const int4 v = *reinterpret_cast<const int4 *>(
+                                        xch + g * (Cfg::WAVES * TPP * 1024) + u * 1024 + q * 256);
+                                    acc[j][t][4 * q] += v.x; acc[j][t][4 * q + 1] += v.y;
+                                    acc[j][t][4 * q + 2] += v.z; acc[j][t][4 * q + 3] += v.w;
+                                }
+                        });
+                    }
+                });
             }
             if (grp == 0) {
                 if constexpr (ROWS_EPI) {
@@ -1280,7 +1315,7 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
     constexpr bool rows_epi = !Epi::generic && EpiShuffle<Cfg>::usable;
     constexpr size_t lds_kernel =
         KSPLIT == 1 ? Cfg::LDS_BYTES + (rows_epi ? EpiShuffle<Cfg>::EXTRA_LDS : 0)
-                    : KSPLIT * (Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS) + (KSPLIT - 1) * Cfg::WAVES * 4096;
+                    : KSplitXch<Cfg>::lds(KSPLIT);
     static_assert(lds_kernel <= 160 * 1024, "LDS is 160 KiB per CU");
     const size_t lds = lds_kernel;
     static int wgs_per_cu = 0;  // per instantiation
@@ -1340,7 +1375,7 @@ static int launch_dma_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st
     }
 }
 
-// 64x64 tiles with the k loop split between two wave groups of one workgroup.
+// Tiles with the k loop split between two wave groups of one workgroup.
 template <class Cfg, int KS>
 static int launch_ksplit_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
 {
@@ -1375,7 +1410,14 @@ static int choose_tiles(const GemmI4Params &p)
     const double ops = 2.0 * p.M * p.N * p.K;
     if (t256x128 >= 512 && ops >= 6e10) return 18;
     if (t128x64 <= 256) return 27;
-    return (t128 >= 400 || p.K >= 2048) ? 29 : 28;
+    if (t128 >= 400 || p.K >= 2048) {
+        // at most one 128x128 workgroup per CU and a long k loop: two wave groups share the tile's K
+        // (a lone wave per SIMD is bound by its own instruction stream); 6-14 % at N = 768 / 1024,
+        // K = 3072 ... 8192, M = 2560 ... 5120
+        if (t128 <= 256 && p.K >= 2048 && (p.K % 256) == 0) return 35;
+        return 29;
+    }
+    return 28;
 }
 
 int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
@@ -1400,7 +1442,7 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
         const int64_t t64 = ceil_div(p.M, 64) * ceil_div(p.N, 64);
         if (t64 <= 512) cfg = (t64 <= 256 && p.K >= 6144) ? 31 : 33;
     }
-    if ((cfg == 31 || cfg == 33) && (p.K % 256) != 0) return MKQ_ERR_UNSUPPORTED;
+    if ((cfg == 31 || cfg == 33 || cfg == 35) && (p.K % 256) != 0) return MKQ_ERR_UNSUPPORTED;
     switch (cfg) {
     case 2: return launch_gemm_i4<GemmI4Cfg<128, 128, 2, 2, 64>>(p, st);
     case 3: return launch_gemm_i4<GemmI4Cfg<64, 64, 2, 2, 64>>(p, st);
@@ -1415,6 +1457,7 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     case 29: return launch_dma_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 3>>(p, epi, st);
     case 31: return launch_ksplit_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>, 2>(p, epi, st);
     case 33: return launch_ksplit_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 3>, 2>(p, epi, st);
+    case 35: return launch_ksplit_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 3>, 2>(p, epi, st);
     default: return MKQ_ERR_UNSUPPORTED;
     }
 }

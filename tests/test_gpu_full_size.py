@@ -171,3 +171,24 @@ def test_padding_free_token_counts(mkq, M, K, N):
     r = mkq.mkq_linear_int8(to_dev(A8), 0.01, to_dev(W8), to_dev(s_w), to_dev(b), mkq.MKQ_F16)
     ref = oracle.linear_int4(A8, 0.01, W8, s_w, b, out_dtype=oracle.F16, qmin=-128, qmax=127)
     assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+
+
+@pytest.mark.parametrize("M,K,N", [(4096, 3072, 768), (4099, 4096, 1024), (2560, 4096, 1024)])
+def test_ffn_down_shapes_split_k_tiles_sampled_rows(mkq, M, K, N):
+    """FFN-down of a BERT-base / BERT-large layer at M around 4096: at most one 128 x 128 tile per CU and
+    a long k loop, which the automatic choice runs with two wave groups sharing the tile's K; binary16
+    residual and output as in the layer."""
+    import torch
+    A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, seed=K + M)
+    rng = np.random.default_rng(M)
+    b = rng.normal(0, 0.3, N).astype(np.float32)
+    res = rng.normal(0, 1, (M, N)).astype(np.float16)
+    a_d = _pack_rows_on_device(mkq, A)
+    w_d = mkq.mkq_pack_codes_int4(to_dev(Wc)).reshape(-1)
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    mkq.mkq_linear_int4(a_d, s_x, w_d, to_dev(s_w), to_dev(b), N, K, mkq.MKQ_F16, residual=to_dev(res), out=out)
+    torch.cuda.synchronize()
+    rows = _sample_rows(M, rng)
+    got = to_np(out[torch.from_numpy(rows).cuda()]).astype(np.float32)
+    ref = oracle.linear_int4(A[rows], s_x, Wc, s_w, b, residual=res[rows].astype(np.float32), out_dtype=oracle.F16)
+    assert np.array_equal(got, ref["y"])

@@ -155,8 +155,8 @@ def test_deterministic_and_no_out_of_bounds_writes(mkq):
     assert np.array_equal(first, to_np(r2["out"]))
 
 
-ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29, 31, 33]
-K_GROUPS = {31: 2, 33: 2}  # configurations that split the k loop between wave groups
+ALL_CFGS = [2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29, 31, 33, 35]
+K_GROUPS = {31: 2, 33: 2, 35: 2}  # configurations that split the k loop between wave groups
 
 
 @pytest.mark.parametrize("cfg", ALL_CFGS)
