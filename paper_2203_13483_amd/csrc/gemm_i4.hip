@@ -1440,7 +1440,9 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     // nothing over two: what is left is launch, first-load latency and the epilogue)
     if (g_forced_cfg < 0 && cfg == 27 && (p.K % 256) == 0 && p.K >= 512) {
         const int64_t t64 = ceil_div(p.M, 64) * ceil_div(p.N, 64);
-        if (t64 <= 512) cfg = (t64 <= 256 && p.K >= 6144) ? 31 : 33;
+        // (between one and two workgroups per CU the split pays only for a long k loop: at K = 768 the
+        // unsplit tiles are 10 % faster there)
+        if (t64 <= 256 || (t64 <= 512 && p.K >= 2048)) cfg = (t64 <= 256 && p.K >= 6144) ? 31 : 33;
     }
     if ((cfg == 31 || cfg == 33 || cfg == 35) && (p.K % 256) != 0) return MKQ_ERR_UNSUPPORTED;
     switch (cfg) {
