@@ -138,7 +138,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (--gpus 1); data-parallel sharding over "
-              "tokens is described in DESIGN.md but not built.", file=sys.stderr)
+              "tokens is described in the design notes but not built.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
