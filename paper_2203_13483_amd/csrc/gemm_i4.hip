@@ -1182,6 +1182,15 @@ __global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(cons
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[tb][v] = 0;
 
+    // The epilogue's per-channel scales and biases are first touched here, by the waves that will run
+    // it, so that their round trip to memory overlaps the weight stream instead of following it.
+    float touched = 0.0f;
+    if (wave < 2) {
+        int n = n0 + fr;
+        n = n < p.N ? n : p.N - 1;
+        touched = p.s_w[n] + (p.bias ? p.bias[n] : 0.0f);
+    }
+
     // chunks of UG groups, the next chunk's loads in flight while this one is multiplied
     constexpr int NL = 4 * UG;  // 16-byte loads per chunk per operand row
     uint4 fw[2][NL], fa[2][TB][NL];
@@ -1220,6 +1229,7 @@ __global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(cons
         }
     }
 
+    asm volatile("" ::"v"(touched));  // (keeps the early loads)
     // reduce over the 8 waves, two token blocks per pass through LDS
 #pragma unroll
     for (int pass = 0; pass < (TB + 1) / 2; ++pass) {
