@@ -1271,7 +1271,9 @@ static int launch_skinny(const GemmI4Params &p, hipStream_t st)
 
 static int run_gemm_i4_skinny(const GemmI4Params &p, hipStream_t st)
 {
-    if (p.M <= 32) return launch_skinny<1, 2>(p, st);
+    // long rows: one group per chunk keeps the wave under 128 registers, so two workgroups share a CU and
+    // one's ramp and reduction overlap the other's stream (4-6 % at K >= 8192, a loss of 3 % at K = 4096)
+    if (p.M <= 32) return p.K >= 8192 ? launch_skinny<1, 1>(p, st) : launch_skinny<1, 2>(p, st);
     if (p.M <= 64) return launch_skinny<2, 2>(p, st);
     if (p.M <= 96) return launch_skinny<3, 1>(p, st);
     return launch_skinny<4, 1>(p, st);

@@ -222,7 +222,7 @@ def test_persistent_pipeline_over_many_tiles(mkq, cfg, out_name):
 
 
 @pytest.mark.parametrize("M", [1, 16, 33, 64, 100, 128])
-@pytest.mark.parametrize("N,K", [(200, 256), (40, 512), (768, 768), (328, 4096), (96, 2304)])
+@pytest.mark.parametrize("N,K", [(200, 256), (40, 512), (768, 768), (328, 4096), (96, 2304), (72, 8192), (40, 10240)])
 def test_few_token_streaming_path(mkq, M, N, K):
     """M <= 128 takes the weight-streaming kernel (K split over 8 waves, reduced in LDS)."""
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M * 7 + N)
