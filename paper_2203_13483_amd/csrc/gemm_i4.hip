@@ -1792,7 +1792,10 @@ int run_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
     // (two 4-wave workgroups per CU) overlap one tile's epilogue with the other's k loop
     if (g_forced_cfg == 41) return launch_e3m2_by_epilogue<E3CfgT<256, 4, 3>>(p, st);
     if (g_forced_cfg == 42) return launch_e3m2_by_epilogue<E3CfgT<128, 2, 2>>(p, st);
-    if (p.K >= 2048) return launch_e3m2_by_epilogue<E3CfgT<256, 4, 3>>(p, st);
+    // (with a short k loop the large tile wins only when every workgroup walks many tiles: 8 % at
+    // M = 65536, N = 4096, K = 1024, sixteen tiles per CU)
+    const int64_t t256 = ceil_div(p.M, 256) * ceil_div(p.N, 256);
+    if (p.K >= 2048 || t256 >= 2048) return launch_e3m2_by_epilogue<E3CfgT<256, 4, 3>>(p, st);
     return launch_e3m2_by_epilogue<E3CfgT<128, 2, 2>>(p, st);
 }
 

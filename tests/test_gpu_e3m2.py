@@ -106,8 +106,8 @@ def test_float_in_requant_and_residual(mkq):
 
 @pytest.mark.parametrize("M,N,K,od,with_bias", [(16384, 4096, 1024, 2, False), (16384, 4096, 128, 1, True),
                                                  (8200, 4104, 256, 0, True), (8200, 4104, 384, 2, False),
-                                                 (4099, 8192, 2048, 2, True)])
-@pytest.mark.parametrize("cfg", [41, 42])
+                                                 (4099, 8192, 2048, 2, True), (65536, 2048, 256, 2, False)])
+@pytest.mark.parametrize("cfg", [41, 42, -1])
 def test_large_m_sampled_rows(mkq, cfg, M, N, K, od, with_bias):
     """More tiles than resident workgroups: every workgroup walks several tiles (one-stage tiles, ragged
     edges in both directions, both tile shapes), checked on sampled rows."""
@@ -116,7 +116,7 @@ def test_large_m_sampled_rows(mkq, cfg, M, N, K, od, with_bias):
     b = np.random.default_rng(K).normal(0, 0.3, N).astype(np.float32) if with_bias else None
     tdt = {0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[od]
     out = torch.empty((M, N), dtype=tdt, device="cuda")
-    mkq.debug_set_gemm_config(cfg)  # 41: 256 x 256 tiles, 42: 256 x 128
+    mkq.debug_set_gemm_config(cfg)  # 41: 256 x 256 tiles, 42: 256 x 128, -1: the library's own choice
     try:
         mkq.mkq_linear_int4_e3m2(mkq.mkq_pack_codes_e3m2(to_dev(A)), s_x, mkq.mkq_pack_codes_e3m2(to_dev(Wc)),
                                  to_dev(s_w), None if b is None else to_dev(b), od, out=out)
