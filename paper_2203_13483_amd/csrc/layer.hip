@@ -70,12 +70,12 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
             if (q && q_bits == 8) {
                 int cd[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(o[e], s_next);
+                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
                 reinterpret_cast<uint2 *>(q)[(int64_t)row * chunks + c] = bytes8(cd);
             } else if (q) {
                 uint32_t packed = 0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
+                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
                 q[(int64_t)row * chunks + c] = packed;
             }
         }
@@ -160,12 +160,12 @@ __global__ __launch_bounds__(256) void layernorm_half_kernel(const uint16_t *__r
             if (q && q_bits == 8) {
                 int cd[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(o[e], s_next);
+                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
                 reinterpret_cast<uint2 *>(q)[(int64_t)row * chunks + c] = bytes8(cd);
             } else if (q) {
                 uint32_t packed = 0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
+                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
                 q[(int64_t)row * chunks + c] = packed;
             }
         }
@@ -316,12 +316,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
             if (qout && q_bits == 8) {
                 int cd[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(o[e], s_next);
+                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
                 *reinterpret_cast<uint2 *>(qout + off) = bytes8(cd);
             } else if (qout) {
                 uint32_t packed = 0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code(o[e], s_next) & 0xFu) << (4 * e);
+                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
                 *reinterpret_cast<uint32_t *>(qout + (off >> 1)) = packed;
             }
         }
