@@ -25,6 +25,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const T *__restrict__ x, 
 {
     const int64_t words_per_row = Kp / 8;
     const int64_t total = M * words_per_row;
+    const QuantStep qs = quant_step<4>(s);  // the division's decision without dividing every value
     for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < total;
          w += (int64_t)gridDim.x * blockDim.x) {
         const int64_t m = w / words_per_row;
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const T *__restrict__ x, 
         load8<T>(x + m * ldx + kw * 8, v);
         int c[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] = quantize_code(v[i], s);
+        for (int i = 0; i < 8; ++i) c[i] = quantize_code_rs<4>(v[i], qs);
         q[w] = pack8(c);
     }
 }
@@ -57,13 +58,14 @@ __global__ __launch_bounds__(256) void quantize_contig_kernel(const T *__restric
     float v0[8], v1[8];
     load8<T>(x + (int64_t)w0 * 8, v0);
     load8<T>(x + (int64_t)(two ? w1 : w0) * 8, v1);
+    const QuantStep qs = quant_step<4>(s);
     int c[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) c[i] = quantize_code(v0[i], s);
+    for (int i = 0; i < 8; ++i) c[i] = quantize_code_rs<4>(v0[i], qs);
     q[w0] = pack8(c);
     if (two) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] = quantize_code(v1[i], s);
+        for (int i = 0; i < 8; ++i) c[i] = quantize_code_rs<4>(v1[i], qs);
         q[w1] = pack8(c);
     }
 }

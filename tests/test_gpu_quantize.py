@@ -104,3 +104,17 @@ def test_pack_weights_given_scales_and_pack_codes(mkq):
     packed = mkq.mkq_pack_codes_int4(to_dev(c))
     assert np.array_equal(to_np(packed), oracle.pack_nibbles(c))
     assert np.array_equal(to_np(mkq.mkq_unpack_weights_int4(packed, 50, 224)), c)
+
+
+@pytest.mark.parametrize("s", [0.34, 1.0 / 3.0, 0.1, 0.0173, 7.0, 2.0 ** -20, 3.0e4])
+def test_quantize_around_every_rounding_boundary(mkq, s):
+    """Values a few ulps either side of every boundary (k + 1/2) s, and exact ties where they are
+    representable: the kernel decides most codes from a reciprocal and must agree with the division."""
+    s32 = np.float32(s)
+    b = (np.arange(-10, 10) + 0.5)[:, None] * np.float64(s32)
+    x = (b * (1.0 + np.arange(-12, 13)[None, :] * 2.0 ** -24)).astype(np.float32).ravel()
+    x = np.concatenate([x, np.nextafter(x, np.float32(np.inf)), np.nextafter(x, np.float32(-np.inf))])
+    pad = (-x.size) % 32
+    x = np.concatenate([x, np.zeros(pad, np.float32)]).reshape(1, -1)
+    q = to_np(mkq.mkq_quantize(to_dev(x), float(s32)))
+    assert np.array_equal(q, oracle.pack_nibbles(oracle.quantize(x, s32)))
