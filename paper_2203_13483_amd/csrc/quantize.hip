@@ -224,6 +224,7 @@ __global__ __launch_bounds__(256) void quantize8_kernel(const T *__restrict__ x,
 {
     const int64_t groups_per_row = K / 8;
     const int64_t total = M * groups_per_row;
+    const QuantStep qs = quant_step<8>(s);
     for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total;
          g += (int64_t)gridDim.x * blockDim.x) {
         const int64_t m = g / groups_per_row;
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(256) void quantize8_kernel(const T *__restrict__ x,
         load8<T>(x + m * ldx + kg * 8, v);
         int c[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] = quantize_code8(v[i], s);
+        for (int i = 0; i < 8; ++i) c[i] = quantize_code_rs<8>(v[i], qs);
         q[g] = bytes8(c);
     }
 }

@@ -367,3 +367,16 @@ def test_mixed_4bit_and_8bit_layers_follow_each_other(mkq):
             # handing them to the next layer equals letting that layer quantize... not exactly (binary16
             # rounding of h_out), so the next layer is simply fed the codes, as a deployed model would
         x, q_in, x_ref = out, q_next, got
+
+
+@pytest.mark.parametrize("s", [0.021, 1.0 / 3.0, 0.1, 2.0 ** -20, 300.0])
+def test_quantize_int8_around_every_rounding_boundary(mkq, s):
+    """Values a few ulps either side of every boundary (k + 1/2) s of the 8-bit range: the kernel decides
+    most codes from a reciprocal and must agree with the division."""
+    s32 = np.float32(s)
+    b = (np.arange(-131, 131) + 0.5)[:, None] * np.float64(s32)
+    x = (b * (1.0 + np.arange(-6, 7)[None, :] * 2.0 ** -24)).astype(np.float32).ravel()
+    x = np.concatenate([x, np.nextafter(x, np.float32(np.inf)), np.nextafter(x, np.float32(-np.inf))])
+    x = np.concatenate([x, np.zeros((-x.size) % 64, np.float32)]).reshape(1, -1)
+    q = to_np(mkq.mkq_quantize_int8(to_dev(x), float(s32)))
+    assert np.array_equal(q, oracle.quantize(x, s32, **Q8))
