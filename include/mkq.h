@@ -136,7 +136,29 @@ typedef struct mkq_epilogue {
     uint8_t *q_out;       /* NULL, or [M, N/2] packed codes of the binary32 result under s_next, written
                              in addition to a float `out` */
     int32_t *acc_out;     /* NULL, or [M, N] raw int32 accumulators (for parity checks) */
+    void *splitk_scratch; /* NULL, or a scratch area prepared by mkq_splitk_scratch_init (see there): lets a
+                             linear with few tokens split K across workgroups to fill the chip */
+    size_t splitk_scratch_bytes;
 } mkq_epilogue;
+
+/* Scratch of a K split across workgroups.  Few tokens against a weight matrix with few output channels
+ * give too few workgroups to fill 256 compute units; the reduction over K is then cut into slices that
+ * different workgroups sum (int32 addition is associative: the accumulators are the same bit for bit),
+ * their partial sums meeting in this area.  It is device memory owned by the caller, at least
+ * mkq_splitk_scratch_bytes() bytes (a constant: 16 KiB of ticket counters, then 16 MiB for partial sums),
+ * 16-byte aligned.  mkq_splitk_scratch_init clears the counters and must have run once (on any stream,
+ * ordered before the first linear that uses the area) after the area was allocated; every linear leaves the
+ * counters cleared again.  Two linears that may run at the same time need two areas.  A linear given no
+ * area, or whose partial sums would not fit, runs without the split -- same results, fewer workgroups.
+ * Errors: NULL, ALIGN, WORKSPACE (area too small), HIP. */
+size_t mkq_splitk_scratch_bytes(void);
+int mkq_splitk_scratch_init(void *scratch, size_t scratch_bytes, void *stream);
+
+/* Once-per-device setup of every kernel of the library (dynamic LDS limits, occupancy queries) for the
+ * device that is current.  Optional: each kernel is otherwise set up, under a lock, the first time it is
+ * launched on a device.  Call it before capturing launches into a HIP graph if no eager call has run yet.
+ * Errors: HIP. */
+int mkq_init(void);
 
 /* The quantized linear layer  y = x W^T + b  with both operands in 4 bits
  * (the int4 matrix multiplication of sections 1 and 5.4 applied to the linears
@@ -147,7 +169,9 @@ typedef struct mkq_epilogue {
  *     out      = narrow(y)  or  codes(y; s_next) packed     (Eq. 1 again)
  *   a        [M, K]: packed codes (a_dtype == MKQ_I4, rows of K/2 bytes) or float
  *            activations (MKQ_F32 / MKQ_F16), which are first quantized with s_x
- *            into `workspace`
+ *            into `workspace` by a launch of mkq_quantize's kernel that precedes the
+ *            GEMM (two launches: inside one launch the hand-over between the
+ *            quantizing and the multiplying workgroups cost more than the second launch)
  *   Wq, s_w  from mkq_pack_weights_int4;  bias [N] binary32 or NULL
  *   out      [M, N] of out_dtype (F32, F16, BF16) or [M, N/2] bytes (I4); may be
  *            NULL when epi->q_out or epi->acc_out is the only result wanted
@@ -160,6 +184,27 @@ size_t mkq_linear_int4_workspace_bytes(int64_t M, int64_t N, int64_t K, int a_dt
 int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,
                     const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
                     const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Few tokens (M <= 128): the linear is one pass over the weights and is bound by how fast they stream from
+ * HBM.  Canonical rows, K/2 bytes apart, are a poor stream (32 rows fetched side by side, a power-of-two
+ * pitch apart, land on the same few memory channels), so weights that serve few tokens can be kept in a
+ * second layout in which the bytes that the chip reads at one moment lie next to each other: the 32 channels
+ * of panel q (q = 0 .. P-1, P = ceil(N / 32)) and the 64 codes of k position g (g = 0 .. K/64 - 1) form a
+ * block of 1 KiB = 64 pieces of 16 bytes; the block is number g P' + q, where P' = P if P is odd, else P + 1
+ * (all panels of one k position, one unused block when P is even, then the next k position: an odd pitch keeps
+ * the k positions that a wave has in flight off each other's memory channels); piece l of a block is bytes
+ * [32 g + 16 (l / 32), + 16) of the canonical row of channel 32 q + r(l % 32), where
+ * r(i) = 16 (i / 16) + 8 ((i / 4) % 2) + 4 ((i / 8) % 2) + i % 4; channels past N and the unused block are
+ * zero.  mkq_stream_weight_bytes(N, K) = 32 P' K / 2.
+ *   mkq_repack_weights_int4_stream   canonical (from mkq_pack_weights_int4) -> streaming layout; K % 64 == 0
+ *   mkq_linear_int4_stream           mkq_linear_int4 on weights in the streaming layout: same arguments, same
+ *                                    results bit for bit; M <= 128 and K % 256 == 0 (else UNSUPPORTED)
+ * Errors: as mkq_linear_int4. */
+size_t mkq_stream_weight_bytes(int64_t N, int64_t K);
+int mkq_repack_weights_int4_stream(const uint8_t *Wq, int64_t N, int64_t K, uint8_t *Wq_stream_out, void *stream);
+int mkq_linear_int4_stream(const void *a, int a_dtype, float s_x, const uint8_t *Wq_stream, const float *s_w,
+                           const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                           const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream);
 
 /* The same linear with both operands in 8 bits (the int8 column of Table 2 in
  * section 5.4; the 8-bit layers of the mixed 4/8-bit models of section 4.2).  Eq. 1

@@ -1,0 +1,50 @@
+/*
+ * mkq_tuning.h -- tuning interface of libmkq: the linears of mkq.h with the kernel configuration chosen by
+ * the caller instead of by the library.  Not needed to use the library; benchmarks sweep it and tests use it
+ * to reach every kernel variant at small sizes and to check the library's own choice against the others.
+ * Nothing here keeps state: the choice is an argument of the call.
+ */
+#ifndef MKQ_TUNING_H
+#define MKQ_TUNING_H
+
+#include "mkq.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* mkq_linear_int4 (section 3.1 Eq. 1 and the linears of section 3.2; same arguments, same results) with
+ *   config    -1 = the library's choice; otherwise one kernel configuration by number:
+ *             2, 3         register-staged generic kernel, 128x128 / 64x64 tiles (any K % 32 == 0)
+ *             11 .. 29     ring kernel tile shapes (K % 128 == 0): 11 256x256/8 waves, 12 128x128 four-stage,
+ *                          14 64x64 eight-stage, 18 256x128, 19 128x256, 20 256x128 with 32-byte stages,
+ *                          27 64x64, 28 128x64, 29 128x128 three-stage
+ *             31, 33, 35   ring kernel with K split between two wave groups of a workgroup (K % 256 == 0):
+ *                          64x64 four-stage, 64x64 three-stage, 128x128
+ *             30           first few-token kernel (M <= 128, K % 256 == 0; waves split K, operands through registers)
+ *             50           few-token weight-streaming kernel (M <= 128, K % 256 == 0)
+ *   k_slices  0 = the library's choice; otherwise the number of K slices across workgroups of configuration
+ *             50 (needs epi->splitk_scratch; clamped to what K and the scratch area allow)
+ * A configuration that does not apply to the arguments returns MKQ_ERR_UNSUPPORTED before anything is enqueued. */
+int mkq_tuning_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,
+                           const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                           const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream,
+                           int config, int k_slices);
+
+/* mkq_linear_int4_stream with the number of 256-code stages that a wave keeps in flight (0 = the library's
+ * choice; 2, 3, 4 or 6) and the number of K slices across workgroups (0 = the library's choice). */
+int mkq_tuning_linear_int4_stream(const void *a, int a_dtype, float s_x, const uint8_t *Wq_stream, const float *s_w,
+                                  const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                                  const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream,
+                                  int prefetch_stages, int k_slices);
+
+/* mkq_linear_int4_e3m2 with config -1 (the library's choice), 41 (256x256 tiles, eight waves) or
+ * 42 (256x128 tiles, four waves, two workgroups per compute unit). */
+int mkq_tuning_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,
+                                const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                                const mkq_epilogue *epi, void *stream, int config);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MKQ_TUNING_H */

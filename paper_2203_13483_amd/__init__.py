@@ -29,6 +29,9 @@ EXPORTS = [
     "mkq_quantize_e3m2", "mkq_pack_codes_e3m2", "mkq_pack_weights_e3m2", "mkq_linear_int4_e3m2",
     "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
     "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
+    "mkq_splitk_scratch_bytes", "mkq_splitk_scratch_init", "mkq_init",
+    "mkq_tuning_linear_int4", "mkq_tuning_linear_int4_e3m2", "mkq_tuning_linear_int4_stream",
+    "mkq_stream_weight_bytes", "mkq_repack_weights_int4_stream", "mkq_linear_int4_stream",
 ]
 
 
@@ -40,7 +43,8 @@ class MkqError(RuntimeError):
 
 class Epilogue(C.Structure):
     _fields_ = [("act", C.c_int), ("residual", C.c_void_p), ("residual_dtype", C.c_int),
-                ("s_next", C.c_float), ("q_out", C.c_void_p), ("acc_out", C.c_void_p)]
+                ("s_next", C.c_float), ("q_out", C.c_void_p), ("acc_out", C.c_void_p),
+                ("splitk_scratch", C.c_void_p), ("splitk_scratch_bytes", C.c_size_t)]
 
 
 class BertLayerParams(C.Structure):
@@ -97,6 +101,18 @@ def load() -> C.CDLL:
         "mkq_linear_int4_workspace_bytes": (sz, [i64, i64, i64, ci]),
         "mkq_linear_int4": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
                                  C.POINTER(Epilogue), vp, sz, vp]),
+        "mkq_tuning_linear_int4": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
+                                        C.POINTER(Epilogue), vp, sz, vp, ci, ci]),
+        "mkq_tuning_linear_int4_e3m2": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp, ci]),
+        "mkq_tuning_linear_int4_stream": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
+                                               C.POINTER(Epilogue), vp, sz, vp, ci, ci]),
+        "mkq_linear_int4_stream": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
+                                        C.POINTER(Epilogue), vp, sz, vp]),
+        "mkq_stream_weight_bytes": (sz, [i64, i64]),
+        "mkq_repack_weights_int4_stream": (ci, [vp, i64, i64, vp, vp]),
+        "mkq_splitk_scratch_bytes": (sz, []),
+        "mkq_splitk_scratch_init": (ci, [vp, sz, vp]),
+        "mkq_init": (ci, []),
         "mkq_quantize_int8": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
         "mkq_pack_weights_int8": (ci, [vp, i64, i64, vp, vp, vp, vp]),
         "mkq_linear_int8": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp]),
@@ -122,13 +138,6 @@ def load() -> C.CDLL:
         fn.restype, fn.argtypes = res, args
     _lib = lib
     return lib
-
-
-def debug_set_gemm_config(cfg: int) -> None:
-    """Tuning hook: force one tile configuration of the int4 GEMM (-1 = automatic)."""
-    fn = load().mkq_debug_set_gemm_config
-    fn.restype, fn.argtypes = None, [C.c_int]
-    fn(int(cfg))
 
 
 def status_string(status: int) -> str:
@@ -287,14 +296,37 @@ def mkq_linear_int4_workspace_bytes(M: int, N: int, K: int, a_dtype: int) -> int
     return int(load().mkq_linear_int4_workspace_bytes(M, N, K, a_dtype))
 
 
+def mkq_init() -> None:
+    _check(load().mkq_init(), "mkq_init")
+
+
+def mkq_splitk_scratch_bytes() -> int:
+    return int(load().mkq_splitk_scratch_bytes())
+
+
+def mkq_splitk_scratch_init(scratch=None, device="cuda", stream=None):
+    """A scratch area for K splits across workgroups, counters cleared (allocated here when not passed in)."""
+    torch = _torch()
+    if scratch is None:
+        scratch = torch.empty(mkq_splitk_scratch_bytes(), dtype=torch.uint8, device=device)
+    _check(load().mkq_splitk_scratch_init(_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)),
+           "mkq_splitk_scratch_init")
+    return scratch
+
+
 def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int = MKQ_F32, *,
                     a_is_codes: bool | None = None, act: int = MKQ_ACT_NONE, residual=None,
                     s_next: float = 0.0, want_q: bool = False, want_acc: bool = False,
-                    out=None, workspace=None, stream=None):
+                    out=None, workspace=None, stream=None, splitk_scratch=None,
+                    config: int | None = None, k_slices: int = 0, w_stream: bool = False,
+                    prefetch_stages: int = 0):
     """The quantized linear.  ``a`` is packed codes (uint8 [M,K/2]) or float [M,K].
 
     Returns a dict with ``out`` (float tensor, or uint8 [M,N/2] for MKQ_I4) and
     optionally ``q`` (packed codes under s_next) and ``acc`` (int32 [M,N]).
+    ``config`` / ``k_slices`` call mkq_tuning_linear_int4 (the kernel configuration chosen by the caller).
+    ``w_stream``: Wq is in the streaming layout (mkq_linear_int4_stream; ``prefetch_stages`` / ``k_slices``
+    call its tuning variant).
     """
     torch = _torch()
     if a_is_codes is None:
@@ -310,15 +342,54 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
     epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
                    residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
                    s_next=float(s_next), q_out=q.data_ptr() if q is not None else None,
-                   acc_out=acc.data_ptr() if acc is not None else None)
+                   acc_out=acc.data_ptr() if acc is not None else None,
+                   splitk_scratch=splitk_scratch.data_ptr() if splitk_scratch is not None else None,
+                   splitk_scratch_bytes=(splitk_scratch.numel() * splitk_scratch.element_size()
+                                         if splitk_scratch is not None else 0))
     need = mkq_linear_int4_workspace_bytes(M, N, K, a_dtype)
     if need and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(load().mkq_linear_int4(_ptr(a), a_dtype, float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias),
-                                  M, N, K, _ptr(out), int(out_dtype), C.byref(epi), _ptr(workspace),
-                                  ws_bytes, _stream(stream)), "mkq_linear_int4")
+    if w_stream:
+        if not prefetch_stages and not k_slices:
+            _check(load().mkq_linear_int4_stream(_ptr(a), a_dtype, float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias),
+                                                 M, N, K, _ptr(out), int(out_dtype), C.byref(epi), _ptr(workspace),
+                                                 ws_bytes, _stream(stream)), "mkq_linear_int4_stream")
+        else:
+            _check(load().mkq_tuning_linear_int4_stream(_ptr(a), a_dtype, float(s_x), _ptr(Wq), _ptr(s_w),
+                                                        _ptr(bias), M, N, K, _ptr(out), int(out_dtype),
+                                                        C.byref(epi), _ptr(workspace), ws_bytes, _stream(stream),
+                                                        int(prefetch_stages), int(k_slices)),
+                   "mkq_tuning_linear_int4_stream")
+    elif config is None and not k_slices:
+        _check(load().mkq_linear_int4(_ptr(a), a_dtype, float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias),
+                                      M, N, K, _ptr(out), int(out_dtype), C.byref(epi), _ptr(workspace),
+                                      ws_bytes, _stream(stream)), "mkq_linear_int4")
+    else:
+        _check(load().mkq_tuning_linear_int4(_ptr(a), a_dtype, float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias),
+                                             M, N, K, _ptr(out), int(out_dtype), C.byref(epi), _ptr(workspace),
+                                             ws_bytes, _stream(stream), -1 if config is None else int(config),
+                                             int(k_slices)), "mkq_tuning_linear_int4")
     return {"out": out, "q": q, "acc": acc}
+
+
+def mkq_linear_int4_stream(a, s_x, Wq_stream, s_w, bias, N, K, out_dtype=MKQ_F32, **kw):
+    """mkq_linear_int4 on weights in the streaming layout (M <= 128)."""
+    return mkq_linear_int4(a, s_x, Wq_stream, s_w, bias, N, K, out_dtype, w_stream=True, **kw)
+
+
+def mkq_stream_weight_bytes(N: int, K: int) -> int:
+    return int(load().mkq_stream_weight_bytes(N, K))
+
+
+def mkq_repack_weights_int4_stream(Wq, N: int, K: int, out=None, stream=None):
+    """Canonical packed weights -> the streaming layout (uint8 [mkq_stream_weight_bytes(N, K)])."""
+    torch = _torch()
+    if out is None:
+        out = torch.empty(mkq_stream_weight_bytes(N, K), dtype=torch.uint8, device=Wq.device)
+    _check(load().mkq_repack_weights_int4_stream(_ptr(Wq), N, K, _ptr(out), _stream(stream)),
+           "mkq_repack_weights_int4_stream")
+    return out
 
 
 def mkq_quantize_int8(x, s_x: float, q_out=None, stream=None):
@@ -391,8 +462,9 @@ def mkq_pack_weights_e3m2(W, s_w_in=None, stream=None):
 
 def mkq_linear_int4_e3m2(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, act: int = MKQ_ACT_NONE,
                          residual=None, s_next: float = 0.0, want_q: bool = False, want_acc: bool = False,
-                         out=None, stream=None):
-    """The 4-bit linear on E3M2 containers: a uint8 [M, 3K/4], Wq uint8 [N, 3K/4]."""
+                         out=None, stream=None, config: int | None = None):
+    """The 4-bit linear on E3M2 containers: a uint8 [M, 3K/4], Wq uint8 [N, 3K/4].
+    ``config`` calls mkq_tuning_linear_int4_e3m2."""
     torch = _torch()
     M, K = a.shape[0], a.shape[1] * 4 // 3
     N = Wq.shape[0]
@@ -406,8 +478,13 @@ def mkq_linear_int4_e3m2(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32,
                    residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
                    s_next=float(s_next), q_out=q.data_ptr() if q is not None else None,
                    acc_out=acc.data_ptr() if acc is not None else None)
-    _check(load().mkq_linear_int4_e3m2(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
-                                       int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int4_e3m2")
+    if config is None:
+        _check(load().mkq_linear_int4_e3m2(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
+                                           int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int4_e3m2")
+    else:
+        _check(load().mkq_tuning_linear_int4_e3m2(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K,
+                                                  _ptr(out), int(out_dtype), C.byref(epi), _stream(stream),
+                                                  int(config)), "mkq_tuning_linear_int4_e3m2")
     return {"out": out, "q": q, "acc": acc}
 
 

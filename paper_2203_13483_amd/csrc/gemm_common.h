@@ -110,5 +110,23 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Resident workgroups of a persistent kernel on the current device: CUs x workgroups per CU.  The
+// per-device setup (dynamic LDS limit, occupancy query) runs once per kernel instantiation and device.
+template <class K>
+inline int resident_workgroups(PerDeviceOnce &once, K kernel, int threads, size_t lds, int max_per_cu, int64_t *resident)
+{
+    const int wgs = once.get([&]() -> int {
+        if (lds > 65536 &&
+            hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return -1;
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, threads, lds) != hipSuccess || occ < 1) return -1;
+        return occ > max_per_cu ? max_per_cu : occ;
+    });
+    int cus = 0;
+    if (wgs <= 0 || !device_cus(&cus)) return MKQ_ERR_HIP;
+    *resident = (int64_t)cus * wgs;
+    return MKQ_OK;
+}
 
 }  // namespace mkq

@@ -269,24 +269,16 @@ __global__ __launch_bounds__(Cfg::THREADS * KSPLIT) void gemm_f16_kernel(const G
 }
 
 template <class Cfg, int KSPLIT = 1>
-static int launch_gemm_f16(const GemmF16Params &p, hipStream_t st)
+static int launch_gemm_f16(const GemmF16Params &p, hipStream_t st, bool setup_only = false)
 {
     const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
     constexpr size_t lds = KSPLIT * Cfg::LDS_BYTES + (KSPLIT - 1) * Cfg::WAVES * 4096;
     static_assert(lds <= 160 * 1024, "LDS is 160 KiB per CU");
-    static int resident = 0;
-    if (resident == 0) {
-        if (lds > 65536 && hipFuncSetAttribute((const void *)gemm_f16_kernel<Cfg, KSPLIT>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return MKQ_ERR_HIP;
-        int occ = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_f16_kernel<Cfg, KSPLIT>, Cfg::THREADS * KSPLIT, lds) != hipSuccess ||
-            occ < 1 || hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-            return MKQ_ERR_HIP;
-        resident = occ * cus;
-    }
+    static PerDeviceOnce once;  // per instantiation
+    int64_t resident = 0;
+    const int rc = resident_workgroups(once, gemm_f16_kernel<Cfg, KSPLIT>, Cfg::THREADS * KSPLIT, lds, 1 << 20, &resident);
+    if (rc != MKQ_OK || setup_only) return rc;
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
     gemm_f16_kernel<Cfg, KSPLIT><<<grid, Cfg::THREADS * KSPLIT, lds, st>>>(p);
     return launch_status();
@@ -301,6 +293,17 @@ int run_gemm_f16(const GemmF16Params &p, hipStream_t st)
     // wave groups (four-stage rings), beyond that a three-stage ring lets three workgroups share a CU
     if (t64 <= 256 && (p.K % 128) == 0 && p.K >= 256) return launch_gemm_f16<GemmF16Cfg<64, 64, 2, 2, 4>, 2>(p, st);
     return launch_gemm_f16<GemmF16Cfg<64, 64, 2, 2, 3>>(p, st);
+}
+
+// once-per-device setup of every instantiation (nothing is launched)
+int setup_gemm_f16()
+{
+    GemmF16Params p = {};
+    p.M = p.N = p.K = 256;
+    int rc = launch_gemm_f16<GemmF16Cfg<128, 128, 2, 2, 4>>(p, nullptr, true);
+    if (rc == MKQ_OK) rc = launch_gemm_f16<GemmF16Cfg<64, 64, 2, 2, 4>, 2>(p, nullptr, true);
+    if (rc == MKQ_OK) rc = launch_gemm_f16<GemmF16Cfg<64, 64, 2, 2, 3>>(p, nullptr, true);
+    return rc;
 }
 
 }  // namespace mkq

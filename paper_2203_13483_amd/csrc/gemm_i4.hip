@@ -23,232 +23,16 @@
 // W is the MFMA "A" operand and the activations the "B" operand; W rows are read
 // in a permuted order so that a lane ends up with runs of 8 consecutive output
 // channels of one token and stores them with one or two vector stores.
-#include "gemm_common.h"
+#include "gemm_i4_params.h"
+#include "mkq_tuning.h"
 
 namespace mkq {
 
-struct GemmI4Params {
-    const uint8_t *A;   // [M, K/2]
-    const uint8_t *W;   // [N, K/2]
-    int M, N, K;
-    float s_x;
-    const float *s_w;   // [N]
-    const float *bias;  // [N] or null
-    const void *residual;
-    int residual_dtype;
-    int act;
-    void *out;          // [M,N] float type, or [M,N/2] bytes
-    int out_dtype;      // MKQ_F32/F16/BF16/I4, or -1 for none
-    float s_next;
-    uint8_t *q_out;     // extra packed codes, or null
-    int32_t *acc_out;   // raw accumulators, or null
-    // What the int32 accumulator holds: 2^acc_shift * sum(a*w).  The 4-bit path feeds the
-    // matrix core 16*code on both sides (shift 8); the 8-bit path feeds the codes themselves.
-    int acc_shift;
-    float acc_unit;     // 2^-acc_shift, folded into the per-channel scale (exact)
-};
-
-// Widen two packed words (16 codes) to four int8x4 words (values 16*code).
-__device__ __forceinline__ v4i widen(uint32_t w0, uint32_t w1)
-{
-    v4i r;
-    r.x = (int)((w0 << 4) & 0xF0F0F0F0u);
-    r.y = (int)(w0 & 0xF0F0F0F0u);
-    r.z = (int)((w1 << 4) & 0xF0F0F0F0u);
-    r.w = (int)(w1 & 0xF0F0F0F0u);
-    return r;
-}
-
-template <int BM_, int BN_, int WGM_, int WGN_, int RB_>
-struct GemmI4Cfg {
-    static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, RB = RB_;
-    static constexpr int THREADS = WGM * WGN * 64;
-    static constexpr int WTM = BM / WGM, WTN = BN / WGN;  // per-wave tile (tokens x channels)
-    static constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wave
-    static constexpr int CH = RB / 16;                    // 16-byte chunks per LDS row
-    static constexpr int ROUNDS = RB / 32;                // ds_read_b128 per fragment per stage
-    static constexpr int STAGE_BYTES = (BM + BN) * RB;
-    static constexpr int A_PER_T = BM * CH / THREADS, W_PER_T = BN * CH / THREADS;
-    static_assert((BM * CH) % THREADS == 0 && (BN * CH) % THREADS == 0, "tile/threads mismatch");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32");
-};
-
-// Compile-time description of an epilogue.  The fast kernels are instantiated for the
-// few combinations the encoder layer and the benchmarks use, so that the fully
-// unrolled per-tile epilogue stays a few KiB of code; EpiGeneric reads every option
-// from the parameter block at run time (and also handles N % 8 != 0, the raw
-// accumulator output and the extra code output).
-template <int OUT, bool RES16, bool GELU>
-struct EpiFixed {
-    static constexpr bool generic = false;
-    static constexpr int out = OUT;
-    static constexpr bool res16 = RES16, gelu = GELU;
-};
-struct EpiGeneric {
-    static constexpr bool generic = true;
-    static constexpr int out = MKQ_F32;
-    static constexpr bool res16 = false, gelu = false;
-};
-
-// Epilogue of one finished tile (m0, n0 = its first token / channel; wm, wn = the
-// wave's position in the workgroup; fr = lane % 32, fh = lane / 32).
-// Register v of a lane holds channel 16*(v/8) + 8*fh + v%8 of its 32-channel tile,
-// token fr of its 32-token tile.
-template <class Cfg, class Epi>
-__device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&acc)[Cfg::TM][Cfg::TN],
-                                                 int m0, int n0, int wm, int wn, int fr, int fh)
-{
-    constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    const int out_dtype = Epi::generic ? p.out_dtype : Epi::out;
-    const bool has_res = Epi::generic ? (p.residual != nullptr) : Epi::res16;
-    const bool res_f32 = Epi::generic ? (p.residual_dtype == MKQ_F32) : false;
-    const bool gelu = Epi::generic ? (p.act == MKQ_ACT_GELU) : Epi::gelu;
-    const bool vec_ok = Epi::generic ? ((p.N % 8) == 0) : true;
-    int32_t *const acc_out = Epi::generic ? p.acc_out : nullptr;
-    uint8_t *const q_extra = Epi::generic ? p.q_out : nullptr;
-    const bool need_y = (out_dtype >= 0) || q_extra;
-    static_for<TN>([&](auto tc) {
-        constexpr int t = decltype(tc)::value;
-        static_for<2>([&](auto Gc) {
-            constexpr int G = decltype(Gc)::value;
-            // keep the scheduler from hoisting every unit's loads to the top (register spills)
-            __builtin_amdgcn_sched_barrier(0);
-            const int nb = n0 + wn * Cfg::WTN + t * 32 + 16 * G + 8 * fh;
-            if (nb >= p.N) return;
-            const int nvalid = (p.N - nb) < 8 ? (p.N - nb) : 8;
-            float sc[8], bi[8];
-            if (vec_ok) {
-                const float4 s0 = *reinterpret_cast<const float4 *>(p.s_w + nb);
-                const float4 s1 = *reinterpret_cast<const float4 *>(p.s_w + nb + 4);
-                sc[0] = s0.x; sc[1] = s0.y; sc[2] = s0.z; sc[3] = s0.w;
-                sc[4] = s1.x; sc[5] = s1.y; sc[6] = s1.z; sc[7] = s1.w;
-                if (p.bias) {
-                    const float4 b0 = *reinterpret_cast<const float4 *>(p.bias + nb);
-                    const float4 b1 = *reinterpret_cast<const float4 *>(p.bias + nb + 4);
-                    bi[0] = b0.x; bi[1] = b0.y; bi[2] = b0.z; bi[3] = b0.w;
-                    bi[4] = b1.x; bi[5] = b1.y; bi[6] = b1.z; bi[7] = b1.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) bi[e] = 0.0f;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int n = (e < nvalid) ? nb + e : nb;
-                    sc[e] = p.s_w[n];
-                    bi[e] = p.bias ? p.bias[n] : 0.0f;
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sc[e] = (p.s_x * sc[e]) * p.acc_unit;  // power of two: exact
-            static_for<TM>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                __builtin_amdgcn_sched_barrier(0);
-                const int m = m0 + wm * Cfg::WTM + j * 32 + fr;
-                if (m >= p.M) return;
-                const int64_t o = (int64_t)m * p.N + nb;
-                int a[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) a[e] = acc[j][t][8 * G + e];
-
-                if (acc_out) {
-                    if (vec_ok) {
-                        *reinterpret_cast<int4 *>(acc_out + o) = make_int4(a[0] >> p.acc_shift, a[1] >> p.acc_shift, a[2] >> p.acc_shift, a[3] >> p.acc_shift);
-                        *reinterpret_cast<int4 *>(acc_out + o + 4) = make_int4(a[4] >> p.acc_shift, a[5] >> p.acc_shift, a[6] >> p.acc_shift, a[7] >> p.acc_shift);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) acc_out[o + e] = a[e] >> p.acc_shift;
-                    }
-                }
-                if (!need_y) return;
-
-                float y[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    y[e] = __fmaf_rn((float)a[e], sc[e], bi[e]);
-                    // keep the binary32 rounding: without this the compiler folds the fma and a
-                    // later narrowing into one v_fma_mixlo_f16, which rounds only once
-                    asm volatile("" : "+v"(y[e]));
-                }
-                if (has_res) {
-                    if (res_f32) {
-                        const float *r = (const float *)p.residual + o;
-                        if (vec_ok) {
-                            const float4 r0 = *reinterpret_cast<const float4 *>(r);
-                            const float4 r1 = *reinterpret_cast<const float4 *>(r + 4);
-                            y[0] += r0.x; y[1] += r0.y; y[2] += r0.z; y[3] += r0.w;
-                            y[4] += r1.x; y[5] += r1.y; y[6] += r1.z; y[7] += r1.w;
-                        } else {
-                            for (int e = 0; e < nvalid; ++e) y[e] += r[e];
-                        }
-                    } else {
-                        const uint16_t *r = (const uint16_t *)p.residual + o;
-                        if (vec_ok) {
-                            const uint4 rr = *reinterpret_cast<const uint4 *>(r);
-                            const uint32_t rwd[4] = {rr.x, rr.y, rr.z, rr.w};
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                y[2 * e] += half_bits_to_float((uint16_t)(rwd[e] & 0xFFFFu));
-                                y[2 * e + 1] += half_bits_to_float((uint16_t)(rwd[e] >> 16));
-                            }
-                        } else {
-                            for (int e = 0; e < nvalid; ++e) y[e] += half_bits_to_float(r[e]);
-                        }
-                    }
-                }
-                if (gelu) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) y[e] = gelu_erf(y[e]);
-                }
-
-                if (out_dtype == MKQ_F32) {
-                    float *dst = (float *)p.out + o;
-                    if (vec_ok) {
-                        *reinterpret_cast<float4 *>(dst) = make_float4(y[0], y[1], y[2], y[3]);
-                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(y[4], y[5], y[6], y[7]);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) dst[e] = y[e];
-                    }
-                } else if (out_dtype == MKQ_F16 || out_dtype == MKQ_BF16) {
-                    uint32_t h[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        h[e] = (out_dtype == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1])
-                                                      : pack2_bf16(y[2 * e], y[2 * e + 1]);
-                    uint16_t *dst = (uint16_t *)p.out + o;
-                    if (vec_ok) {
-                        *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(h[e >> 1] >> (16 * (e & 1)));
-                    }
-                }
-                if (out_dtype == MKQ_I8) {  // Eq. 1 at 8 bits, one byte per code
-                    int cd[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(y[e], p.s_next);
-                    uint8_t *qdst = (uint8_t *)p.out + o;
-                    if (vec_ok) {
-                        *reinterpret_cast<uint2 *>(qdst) = bytes8(cd);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) qdst[e] = (uint8_t)cd[e];
-                    }
-                }
-                if (out_dtype == MKQ_I4 || q_extra) {
-                    // Eq. 1 on the binary32 value.  N is even and nb % 8 == 0, so o is even.
-                    uint32_t packed = 0;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        packed |= ((uint32_t)quantize_code(y[e], p.s_next) & 0xFu) << (4 * e);
-                    uint8_t *qdst = (out_dtype == MKQ_I4 ? (uint8_t *)p.out : q_extra) + (o >> 1);
-                    if (vec_ok) {
-                        *reinterpret_cast<uint32_t *>(qdst) = packed;
-                    } else {
-                        for (int e = 0; e < nvalid / 2; ++e) qdst[e] = (uint8_t)(packed >> (8 * e));
-                    }
-                }
-            });
-        });
-    });
-}
+// few-token weight-streaming kernel (gemm_i4_stream.hip)
+bool gemm_i4_stream_ok(const GemmI4Params &p);
+int run_gemm_i4_stream(const GemmI4Params &p, const SplitKScratch *scr, int forced_ks, hipStream_t st);
+int setup_gemm_i4_stream(const GemmI4Params &p, hipStream_t st);
+int run_gemm_i4_wstream(const GemmI4Params &p, const SplitKScratch *scr, int forced_ks, int variant, hipStream_t st);
 
 // Epilogue of the ring kernel through LDS, for the compile-time epilogues.  In the MFMA
 // result layout a lane owns 8 consecutive channels of one token, so a direct store
@@ -1265,6 +1049,7 @@ __global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(cons
 template <int TB, int UG>
 static int launch_skinny(const GemmI4Params &p, hipStream_t st)
 {
+    if (p.setup_only) return MKQ_OK;
     gemm_i4_skinny_kernel<TB, UG><<<(unsigned)ceil_div(p.N, 32), SkinnyCfg::THREADS, 0, st>>>(p);
     return launch_status();
 }
@@ -1279,32 +1064,14 @@ static int run_gemm_i4_skinny(const GemmI4Params &p, hipStream_t st)
     return launch_skinny<4, 1>(p, st);
 }
 
-static int g_num_cus = 0;
-
 template <class Cfg, bool FULL>
 static int launch_one(const GemmI4Params &p, int64_t tiles, hipStream_t st)
 {
     const size_t lds = 2 * (size_t)Cfg::STAGE_BYTES;
-    static int wgs_per_cu = 0;  // per instantiation
-    if (wgs_per_cu == 0) {
-        if (lds > 65536 &&
-            hipFuncSetAttribute((const void *)gemm_i4_kernel<Cfg, FULL>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return MKQ_ERR_HIP;
-        int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_kernel<Cfg, FULL>, Cfg::THREADS, lds) !=
-                hipSuccess || occ < 1)
-            return MKQ_ERR_HIP;
-        if (g_num_cus == 0) {
-            int dev = 0, cus = 0;
-            if (hipGetDevice(&dev) != hipSuccess ||
-                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-                return MKQ_ERR_HIP;
-            g_num_cus = cus;
-        }
-        wgs_per_cu = occ > 2 ? 2 : occ;
-    }
-    const int64_t resident = (int64_t)g_num_cus * wgs_per_cu;
+    static PerDeviceOnce once;  // per instantiation
+    int64_t resident = 0;
+    const int rc = resident_workgroups(once, gemm_i4_kernel<Cfg, FULL>, Cfg::THREADS, lds, 2, &resident);
+    if (rc != MKQ_OK || p.setup_only) return rc;
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
     gemm_i4_kernel<Cfg, FULL><<<grid, Cfg::THREADS, lds, st>>>(p);
     return launch_status();
@@ -1330,26 +1097,11 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
                     : KSplitXch<Cfg>::lds(KSPLIT);
     static_assert(lds_kernel <= 160 * 1024, "LDS is 160 KiB per CU");
     const size_t lds = lds_kernel;
-    static int wgs_per_cu = 0;  // per instantiation
-    if (wgs_per_cu == 0) {
-        if (lds > 65536 &&
-            hipFuncSetAttribute((const void *)gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return MKQ_ERR_HIP;
-        int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT>, Cfg::THREADS * KSPLIT, lds) !=
-                hipSuccess || occ < 1)
-            return MKQ_ERR_HIP;
-        if (g_num_cus == 0) {
-            int dev = 0, cus = 0;
-            if (hipGetDevice(&dev) != hipSuccess ||
-                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-                return MKQ_ERR_HIP;
-            g_num_cus = cus;
-        }
-        wgs_per_cu = occ;
-    }
-    const int64_t resident = (int64_t)g_num_cus * wgs_per_cu;
+    static PerDeviceOnce once;  // per instantiation
+    int64_t resident = 0;
+    const int rc = resident_workgroups(once, gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT>, Cfg::THREADS * KSPLIT, lds,
+                                       1 << 20, &resident);
+    if (rc != MKQ_OK || p.setup_only) return rc;
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
     gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT><<<grid, Cfg::THREADS * KSPLIT, lds, st>>>(p);
     return launch_status();
@@ -1402,8 +1154,6 @@ static int launch_ksplit_by_epilogue(const GemmI4Params &p, int epi, hipStream_t
     }
 }
 
-static int g_forced_cfg = -1;  // tuning hook, see mkq_debug_set_gemm_config
-
 using DmaBig8 = GemmI4DmaCfg<256, 256, 2, 4, 64, 5>;   // 2 waves per SIMD, 128x64 per wave
 using DmaMid = GemmI4DmaCfg<128, 128, 2, 2, 64, 4>;    // 64 KiB LDS: two workgroups per CU
 using DmaSmall = GemmI4DmaCfg<64, 64, 2, 2, 64, 8>;
@@ -1432,13 +1182,21 @@ static int choose_tiles(const GemmI4Params &p)
     return 28;
 }
 
-int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
+// forced_cfg: -1 = the library's own choice, otherwise one configuration by number (tuning interface);
+// scr: scratch of a K split across workgroups, or null; forced_ks: 0 = automatic.
+int run_gemm_i4(const GemmI4Params &p, hipStream_t st, int forced_cfg, const SplitKScratch *scr, int forced_ks)
 {
-    int cfg = g_forced_cfg;
+    int cfg = forced_cfg;
     const bool dma_ok = (p.K % 128) == 0;  // whole 64-byte stages
     const int epi = classify_epilogue(p);
-    if (cfg < 0 && p.M <= 64 && (p.K % 256) == 0) return run_gemm_i4_skinny(p, st);
+    if (cfg == 50) return gemm_i4_stream_ok(p) ? run_gemm_i4_stream(p, scr, forced_ks, st) : MKQ_ERR_UNSUPPORTED;
     if (cfg == 30) return (p.M <= 128 && (p.K % 256) == 0) ? run_gemm_i4_skinny(p, st) : MKQ_ERR_UNSUPPORTED;
+    // Few tokens on canonical weights: up to 64 tokens the register kernel (the faster of the two at every
+    // measured size); 65 .. 128 tokens against a large weight matrix the ring kernel with its shared
+    // activation stages (60 instead of 88 us at K = N = 16384), against a small one the tile kernels.
+    if (cfg < 0 && p.M <= 64 && (p.K % 256) == 0) return run_gemm_i4_skinny(p, st);
+    if (cfg < 0 && gemm_i4_stream_ok(p) && (int64_t)p.N * p.K >= ((int64_t)1 << 27))
+        return run_gemm_i4_stream(p, scr, forced_ks, st);
     if (cfg < 0) {
         if (!dma_ok) {
             cfg = 3;
@@ -1450,7 +1208,7 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st)
     // few 64x64 tiles (at most two workgroups per CU) and a k loop long enough to halve: two wave
     // groups per workgroup, with the deeper ring when the k loop is very long (four groups gain
     // nothing over two: what is left is launch, first-load latency and the epilogue)
-    if (g_forced_cfg < 0 && cfg == 27 && (p.K % 256) == 0 && p.K >= 512) {
+    if (forced_cfg < 0 && cfg == 27 && (p.K % 256) == 0 && p.K >= 512) {
         const int64_t t64 = ceil_div(p.M, 64) * ceil_div(p.N, 64);
         // (between one and two workgroups per CU the split pays only for a long k loop: at K = 768 the
         // unsplit tiles are 10 % faster there)
@@ -1490,12 +1248,12 @@ static int launch_i8_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
     }
 }
 
-int run_gemm_i8(const GemmI4Params &p, hipStream_t st)
+int run_gemm_i8(const GemmI4Params &p, hipStream_t st, int forced_cfg = -1)
 {
     if ((p.K % 64) != 0) return MKQ_ERR_UNSUPPORTED;
     int epi = classify_epilogue(p);
     if (epi == EPI_I4 || epi == EPI_I4_GELU) epi = EPI_GENERIC;
-    switch (choose_tiles(p)) {
+    switch (forced_cfg >= 0 ? forced_cfg : choose_tiles(p)) {
     case 18: return launch_i8_by_epilogue<GemmI4DmaCfg<256, 128, 2, 2, 64, 3>>(p, epi, st);
     case 29: return launch_i8_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 3>>(p, epi, st);
     case 28: return launch_i8_by_epilogue<GemmI4DmaCfg<128, 64, 2, 2, 64, 3>>(p, epi, st);
@@ -1755,21 +1513,10 @@ static int launch_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
     constexpr int lds = Cfg::LDS_BYTES + EpiShuffle<Cfg>::EXTRA_LDS;
     static_assert(lds <= 160 * 1024, "LDS is 160 KiB per CU");
-    static bool ready = false;
-    if (!ready) {
-        if (hipFuncSetAttribute((const void *)gemm_e3m2_kernel<Cfg, Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds) != hipSuccess)
-            return MKQ_ERR_HIP;
-        if (g_num_cus == 0) {
-            int dev = 0, cus = 0;
-            if (hipGetDevice(&dev) != hipSuccess ||
-                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-                return MKQ_ERR_HIP;
-            g_num_cus = cus;
-        }
-        ready = true;
-    }
-    const int64_t resident = (int64_t)g_num_cus * ((160 * 1024) / lds);
+    static PerDeviceOnce once;  // per instantiation
+    int64_t resident = 0;
+    const int rc = resident_workgroups(once, gemm_e3m2_kernel<Cfg, Epi>, Cfg::THREADS, lds, (160 * 1024) / lds, &resident);
+    if (rc != MKQ_OK || p.setup_only) return rc;
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
     gemm_e3m2_kernel<Cfg, Epi><<<grid, Cfg::THREADS, lds, st>>>(p);
     return launch_status();
@@ -1786,12 +1533,12 @@ static int launch_e3m2_by_epilogue(const GemmI4Params &p, hipStream_t st)
     }
 }
 
-int run_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
+int run_gemm_e3m2(const GemmI4Params &p, hipStream_t st, int forced_cfg)
 {
     // 256 x 256 tiles (one 8-wave workgroup per CU) make the fewest global->LDS requests per MFMA; 256 x 128
     // (two 4-wave workgroups per CU) overlap one tile's epilogue with the other's k loop
-    if (g_forced_cfg == 41) return launch_e3m2_by_epilogue<E3CfgT<256, 4, 3>>(p, st);
-    if (g_forced_cfg == 42) return launch_e3m2_by_epilogue<E3CfgT<128, 2, 2>>(p, st);
+    if (forced_cfg == 41) return launch_e3m2_by_epilogue<E3CfgT<256, 4, 3>>(p, st);
+    if (forced_cfg == 42) return launch_e3m2_by_epilogue<E3CfgT<128, 2, 2>>(p, st);
     // (with a short k loop the large tile wins only when every workgroup walks many tiles: 8 % at
     // M = 65536, N = 4096, K = 1024, sixteen tiles per CU)
     const int64_t t256 = ceil_div(p.M, 256) * ceil_div(p.N, 256);
@@ -1803,10 +1550,6 @@ int run_gemm_e3m2(const GemmI4Params &p, hipStream_t st)
 
 using namespace mkq;
 
-// Tuning hook (not part of the public header): force one tile configuration of the
-// int4 GEMM (-1 = automatic choice).
-extern "C" void mkq_debug_set_gemm_config(int cfg) { mkq::g_forced_cfg = cfg; }
-
 extern "C" size_t mkq_linear_int4_workspace_bytes(int64_t M, int64_t N, int64_t K, int a_dtype)
 {
     (void)N;
@@ -1814,10 +1557,31 @@ extern "C" size_t mkq_linear_int4_workspace_bytes(int64_t M, int64_t N, int64_t 
     return ((size_t)M * (size_t)(K / 2) + 255) & ~(size_t)255;
 }
 
-extern "C" int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq,
-                               const float *s_w, const float *bias, int64_t M, int64_t N, int64_t K,
-                               void *out, int out_dtype, const mkq_epilogue *epi, void *workspace,
-                               size_t workspace_bytes, void *stream)
+extern "C" size_t mkq_splitk_scratch_bytes(void) { return SPLITK_STATE_BYTES + MKQ_SPLITK_PARTIAL_BYTES; }
+
+namespace mkq {
+
+__global__ void clear_words_kernel(unsigned *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// Splits a scratch area into ticket counters and room for partial sums.
+static bool splitk_area(void *scratch, size_t bytes, SplitKScratch *out)
+{
+    if (!scratch || bytes <= SPLITK_STATE_BYTES + 65536) return false;
+    out->counters = reinterpret_cast<unsigned *>(scratch);
+    out->partials = reinterpret_cast<int32_t *>(reinterpret_cast<uint8_t *>(scratch) + SPLITK_STATE_BYTES);
+    out->partial_bytes = bytes - SPLITK_STATE_BYTES;
+    return true;
+}
+
+// The linear on validated-or-not arguments; scr = scratch of a K split across workgroups or null.
+static int linear_int4_run(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,
+                           const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                           const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream,
+                           const SplitKScratch *scr, int forced_cfg, int forced_ks, bool stream_layout = false)
 {
     const bool want_q = epi && epi->q_out;
     const bool want_acc = epi && epi->acc_out;
@@ -1849,16 +1613,11 @@ extern "C" int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint
     if (K >= 131072 || M > 0x7FFFFFFF || N > 0x7FFFFFFF || M * (K / 2) > 0xFFFFFFFFLL ||
         N * (K / 2) > 0xFFFFFFFFLL)
         return MKQ_ERR_UNSUPPORTED;
-
-    const uint8_t *codes = (const uint8_t *)a;
-    if (a_dtype != MKQ_I4) {
-        const int rc = mkq_quantize(a, a_dtype, M, K, K, s_x, (uint8_t *)workspace, stream);
-        if (rc != MKQ_OK) return rc;
-        codes = (const uint8_t *)workspace;
-    }
+    if (stream_layout && (M > 128 || (K % 256) != 0)) return MKQ_ERR_UNSUPPORTED;
 
     GemmI4Params p;
-    p.A = codes; p.W = Wq; p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.A = (a_dtype == MKQ_I4) ? (const uint8_t *)a : (const uint8_t *)workspace;
+    p.W = Wq; p.M = (int)M; p.N = (int)N; p.K = (int)K;
     p.s_x = s_x; p.s_w = s_w; p.bias = bias;
     p.residual = epi ? epi->residual : nullptr;
     p.residual_dtype = epi ? epi->residual_dtype : MKQ_F32;
@@ -1869,7 +1628,143 @@ extern "C" int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint
     p.acc_out = epi ? epi->acc_out : nullptr;
     p.acc_shift = 8;
     p.acc_unit = 0.00390625f;
-    return run_gemm_i4(p, as_stream(stream));
+    // the kernel that will run is set up (and a forced configuration that does not apply is refused)
+    // before anything is enqueued
+    auto run = [&]() {
+        return stream_layout ? run_gemm_i4_wstream(p, scr, forced_ks, forced_cfg, as_stream(stream))
+                             : run_gemm_i4(p, as_stream(stream), forced_cfg, scr, forced_ks);
+    };
+    p.setup_only = true;
+    int rc = run();
+    if (rc != MKQ_OK) return rc;
+    p.setup_only = false;
+    if (a_dtype != MKQ_I4) {
+        rc = mkq_quantize(a, a_dtype, M, K, K, s_x, (uint8_t *)workspace, stream);
+        if (rc != MKQ_OK) return rc;
+    }
+    return run();
+}
+
+// scratch area named by the epilogue options, if any
+static int epilogue_scratch(const mkq_epilogue *epi, SplitKScratch *scr, bool *have)
+{
+    *have = false;
+    if (epi && epi->splitk_scratch) {
+        if (!aligned16(epi->splitk_scratch)) return MKQ_ERR_ALIGN;
+        if (epi->splitk_scratch_bytes < mkq_splitk_scratch_bytes()) return MKQ_ERR_WORKSPACE;
+        *have = splitk_area(epi->splitk_scratch, epi->splitk_scratch_bytes, scr);
+    }
+    return MKQ_OK;
+}
+
+}  // namespace mkq
+
+namespace mkq {
+int setup_gemm_f16();  // gemm_f16.hip
+}
+
+extern "C" int mkq_init(void)
+{
+    GemmI4Params p = {};
+    p.M = p.N = 256; p.K = 1024;
+    p.setup_only = true;
+    int rc = setup_gemm_i4_stream(p, nullptr);
+    for (int cfg : {2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29, 31, 33, 35}) {
+        // one pass per epilogue class: the parameter block is made to classify as each in turn
+        for (int e = 0; e < 7 && rc == MKQ_OK; ++e) {
+            GemmI4Params q = p;
+            q.out = &q; q.s_next = 1.0f;
+            q.out_dtype = e == 0 ? MKQ_F16 : e == 1 ? MKQ_BF16 : e == 2 ? MKQ_F32 : e == 3 ? MKQ_F16 : MKQ_I4;
+            if (e == 3) { q.residual = &q; q.residual_dtype = MKQ_F16; }
+            if (e == 4) q.act = MKQ_ACT_GELU;
+            if (e == 6) q.acc_out = reinterpret_cast<int32_t *>(&q);
+            rc = run_gemm_i4(q, nullptr, cfg, nullptr, 0);
+            if (cfg < 10) break;  // the register-staged kernel has one epilogue
+        }
+    }
+    for (int cfg : {18, 29, 28, 27}) {  // the four tile shapes of the 8-bit path
+        for (int e = 0; e < 6 && rc == MKQ_OK; ++e) {
+            GemmI4Params q = p;
+            q.out = &q; q.s_next = 1.0f;
+            q.out_dtype = e == 0 ? MKQ_F16 : e == 1 ? MKQ_BF16 : e == 2 ? MKQ_F32 : e == 3 ? MKQ_F16 : e == 4 ? MKQ_I8 : MKQ_F32;
+            if (e == 3) { q.residual = &q; q.residual_dtype = MKQ_F16; }
+            if (e == 4) q.act = MKQ_ACT_GELU;
+            if (e == 5) q.acc_out = reinterpret_cast<int32_t *>(&q);
+            rc = run_gemm_i8(q, nullptr, cfg);
+        }
+    }
+    for (int cfg : {41, 42}) {
+        for (int e = 0; e < 4 && rc == MKQ_OK; ++e) {
+            GemmI4Params q = p;
+            q.out = &q;
+            q.out_dtype = e == 0 ? MKQ_F16 : e == 1 ? MKQ_BF16 : MKQ_F32;
+            if (e == 3) q.acc_out = reinterpret_cast<int32_t *>(&q);
+            rc = run_gemm_e3m2(q, nullptr, cfg);
+        }
+    }
+    if (rc == MKQ_OK) rc = setup_gemm_f16();
+    return rc;
+}
+
+extern "C" int mkq_splitk_scratch_init(void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (!scratch) return MKQ_ERR_NULL;
+    if (!aligned16(scratch)) return MKQ_ERR_ALIGN;
+    if (scratch_bytes < mkq_splitk_scratch_bytes()) return MKQ_ERR_WORKSPACE;
+    clear_words_kernel<<<SPLITK_MAX_TILES / 256, 256, 0, as_stream(stream)>>>((unsigned *)scratch, SPLITK_MAX_TILES);
+    return launch_status();
+}
+
+extern "C" int mkq_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq,
+                               const float *s_w, const float *bias, int64_t M, int64_t N, int64_t K,
+                               void *out, int out_dtype, const mkq_epilogue *epi, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    SplitKScratch scr;
+    bool have = false;
+    const int rc = epilogue_scratch(epi, &scr, &have);
+    if (rc != MKQ_OK) return rc;
+    return linear_int4_run(a, a_dtype, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, epi, workspace, workspace_bytes,
+                           stream, have ? &scr : nullptr, -1, 0);
+}
+
+extern "C" int mkq_linear_int4_stream(const void *a, int a_dtype, float s_x, const uint8_t *Wq_stream,
+                                      const float *s_w, const float *bias, int64_t M, int64_t N, int64_t K,
+                                      void *out, int out_dtype, const mkq_epilogue *epi, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    SplitKScratch scr;
+    bool have = false;
+    const int rc = epilogue_scratch(epi, &scr, &have);
+    if (rc != MKQ_OK) return rc;
+    return linear_int4_run(a, a_dtype, s_x, Wq_stream, s_w, bias, M, N, K, out, out_dtype, epi, workspace,
+                           workspace_bytes, stream, have ? &scr : nullptr, 0, 0, true);
+}
+
+extern "C" int mkq_tuning_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,
+                                      const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                                      const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream,
+                                      int config, int k_slices)
+{
+    SplitKScratch scr;
+    bool have = false;
+    const int rc = epilogue_scratch(epi, &scr, &have);
+    if (rc != MKQ_OK) return rc;
+    return linear_int4_run(a, a_dtype, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, epi, workspace, workspace_bytes,
+                           stream, have ? &scr : nullptr, config, k_slices);
+}
+
+extern "C" int mkq_tuning_linear_int4_stream(const void *a, int a_dtype, float s_x, const uint8_t *Wq_stream,
+                                             const float *s_w, const float *bias, int64_t M, int64_t N, int64_t K,
+                                             void *out, int out_dtype, const mkq_epilogue *epi, void *workspace,
+                                             size_t workspace_bytes, void *stream, int prefetch_stages, int k_slices)
+{
+    SplitKScratch scr;
+    bool have = false;
+    const int rc = epilogue_scratch(epi, &scr, &have);
+    if (rc != MKQ_OK) return rc;
+    return linear_int4_run(a, a_dtype, s_x, Wq_stream, s_w, bias, M, N, K, out, out_dtype, epi, workspace,
+                           workspace_bytes, stream, have ? &scr : nullptr, prefetch_stages, k_slices, true);
 }
 
 extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w,
@@ -1915,9 +1810,9 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
     return run_gemm_i8(p, as_stream(stream));
 }
 
-extern "C" int mkq_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,
-                                    const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
-                                    const mkq_epilogue *epi, void *stream)
+static int linear_int4_e3m2_run(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,
+                                const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                                const mkq_epilogue *epi, void *stream, int forced_cfg)
 {
     const bool want_q = epi && epi->q_out;
     const bool want_acc = epi && epi->acc_out;
@@ -1957,5 +1852,19 @@ extern "C" int mkq_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *
     p.acc_out = epi ? epi->acc_out : nullptr;
     p.acc_shift = 0;
     p.acc_unit = 1.0f;
-    return run_gemm_e3m2(p, as_stream(stream));
+    return run_gemm_e3m2(p, as_stream(stream), forced_cfg);
+}
+
+extern "C" int mkq_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,
+                                    const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                                    const mkq_epilogue *epi, void *stream)
+{
+    return linear_int4_e3m2_run(a, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, epi, stream, -1);
+}
+
+extern "C" int mkq_tuning_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,
+                                           const float *bias, int64_t M, int64_t N, int64_t K, void *out,
+                                           int out_dtype, const mkq_epilogue *epi, void *stream, int config)
+{
+    return linear_int4_e3m2_run(a, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, epi, stream, config);
 }

@@ -510,6 +510,14 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
     if (!p->Wq_qkv || !p->Wq_ao || !p->Wq_up || !p->Wq_down || !p->sw_qkv || !p->sw_ao || !p->sw_up ||
         !p->sw_down)
         return MKQ_ERR_NULL;
+    if (!p->ln1_gamma || !p->ln1_beta || !p->ln2_gamma || !p->ln2_beta) return MKQ_ERR_NULL;
+    // every pointer the sub-steps will check, checked here: nothing is enqueued for a call that fails
+    const void *const ptrs[] = {h_in, h_out, q_in, q_out_next, p->Wq_qkv, p->Wq_ao, p->Wq_up, p->Wq_down,
+                                p->sw_qkv, p->sw_ao, p->sw_up, p->sw_down, p->b_qkv, p->b_ao, p->b_up, p->b_down,
+                                p->ln1_gamma, p->ln1_beta, p->ln2_gamma, p->ln2_beta};
+    for (const void *q : ptrs)
+        if (q && !aligned16(q)) return MKQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(p->cu_seqlens) & 3u) return MKQ_ERR_ALIGN;
     if (!workspace || workspace_bytes < L.total || !aligned16(workspace)) return MKQ_ERR_WORKSPACE;
 
     const int64_t M = layer_tokens(p), H = p->hidden, F = p->ffn;
@@ -530,7 +538,7 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
     rc = attention_run(ws + L.qkv, p->batch, p->seq, H, p->heads, nullptr, p->sx_ao, ws + L.c1, bits, stream,
                        p->cu_seqlens);
     if (rc != MKQ_OK) return rc;
-    mkq_epilogue e;
+    mkq_epilogue e = {};
     e.act = MKQ_ACT_NONE; e.residual = h_in; e.residual_dtype = h_dtype; e.s_next = 0.0f;
     e.q_out = nullptr; e.acc_out = nullptr;
     rc = layer_linear(bits, ws + L.c1, p->sx_ao, p->Wq_ao, p->sw_ao, p->b_ao, M, H, H, ws + L.u, MKQ_F16, &e, stream);

@@ -6,6 +6,8 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "mkq.h"
 
 namespace mkq {
@@ -18,6 +20,45 @@ inline bool scale_ok(float s) { return s > 0.0f && s < __builtin_inff(); }
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MKQ_OK : MKQ_ERR_HIP; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Per-device, once-only setup values (dynamic LDS limits, resident workgroups per CU, CU counts).
+// One object per kernel instantiation; get() runs `init` the first time it is called with a given
+// device current and returns its (positive) result from then on; a result <= 0 is an error and is
+// not cached.  Safe to call from several threads.
+constexpr int MAX_DEVICES = 64;
+struct PerDeviceOnce {
+    std::mutex mu;
+    int val[MAX_DEVICES] = {};
+    template <class F>
+    int get(F &&init)
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return -1;
+        std::lock_guard<std::mutex> lock(mu);
+        if (val[dev] <= 0) {
+            const int v = init();
+            if (v <= 0) return v < 0 ? v : -1;
+            val[dev] = v;
+        }
+        return val[dev];
+    }
+};
+
+// Compute units of the current device; false if the runtime cannot say.
+inline bool device_cus(int *cus)
+{
+    static PerDeviceOnce once;
+    const int v = once.get([]() -> int {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return -1;
+        return n;
+    });
+    if (v <= 0) return false;
+    *cus = v;
+    return true;
+}
 
 // ---- device utilities ------------------------------------------------------
 

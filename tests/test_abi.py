@@ -23,13 +23,17 @@ def lib():
 
 
 def test_header_symbols_are_exported(lib):
-    text = open(os.path.join(ROOT, "include", "mkq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = sorted(set(re.findall(r"\b(mkq_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        found = set(re.findall(r"\b(mkq_[a-z0-9_]+)\s*\(", text))
+        assert found, header
+        for n in found:
+            assert hasattr(lib, n), f"{n} declared in {header} but not exported"
+        names |= found
     assert len(names) >= 17
-    for n in names:
-        assert hasattr(lib, n), f"{n} declared in mkq.h but not exported"
-    assert sorted(mkq.EXPORTS) == names
+    assert sorted(mkq.EXPORTS) == sorted(names)
 
 
 def test_status_strings(lib):

@@ -116,13 +116,10 @@ def test_large_m_sampled_rows(mkq, cfg, M, N, K, od, with_bias):
     b = np.random.default_rng(K).normal(0, 0.3, N).astype(np.float32) if with_bias else None
     tdt = {0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[od]
     out = torch.empty((M, N), dtype=tdt, device="cuda")
-    mkq.debug_set_gemm_config(cfg)  # 41: 256 x 256 tiles, 42: 256 x 128, -1: the library's own choice
-    try:
-        mkq.mkq_linear_int4_e3m2(mkq.mkq_pack_codes_e3m2(to_dev(A)), s_x, mkq.mkq_pack_codes_e3m2(to_dev(Wc)),
-                                 to_dev(s_w), None if b is None else to_dev(b), od, out=out)
-        torch.cuda.synchronize()
-    finally:
-        mkq.debug_set_gemm_config(-1)
+    # 41: 256 x 256 tiles, 42: 256 x 128, -1: the library's own choice
+    mkq.mkq_linear_int4_e3m2(mkq.mkq_pack_codes_e3m2(to_dev(A)), s_x, mkq.mkq_pack_codes_e3m2(to_dev(Wc)),
+                             to_dev(s_w), None if b is None else to_dev(b), od, out=out, config=cfg)
+    torch.cuda.synchronize()
     rows = np.unique(np.concatenate([[0, 255, 256, 257, M - 257, M - 2, M - 1],
                                      np.random.default_rng(2).integers(0, M, 40)]))
     got = to_np(out[torch.from_numpy(rows).cuda()]).astype(np.float32)

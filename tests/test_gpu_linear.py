@@ -168,12 +168,8 @@ def test_every_tile_configuration(mkq, cfg, M, N, K):
         pytest.skip("the k split needs a whole number of stages per wave group")
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg + M)
     ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.BF16, s_next=0.7)
-    mkq.debug_set_gemm_config(cfg)
-    try:
-        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16, want_acc=True, want_q=True, s_next=0.7)
-        acc, out, q = to_np(r["acc"]), to_np(r["out"]), to_np(r["q"])
-    finally:
-        mkq.debug_set_gemm_config(-1)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16, want_acc=True, want_q=True, s_next=0.7, config=cfg)
+    acc, out, q = to_np(r["acc"]), to_np(r["out"]), to_np(r["q"])
     assert np.array_equal(acc, ref["acc"])
     assert np.array_equal(out.astype(np.float32), ref["y"])
     assert np.array_equal(q, oracle.pack_nibbles(ref["q"]))
@@ -190,11 +186,7 @@ def test_single_stage_tiles_and_f16_residual(mkq, cfg, K):
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=cfg + K)
     res = np.random.default_rng(K).normal(0, 1, (M, N)).astype(np.float16)
     ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, residual=res.astype(np.float32), out_dtype=oracle.F16)
-    mkq.debug_set_gemm_config(cfg)
-    try:
-        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, residual=to_dev(res))
-    finally:
-        mkq.debug_set_gemm_config(-1)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, residual=to_dev(res), config=cfg)
     assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
 
 
@@ -209,29 +201,107 @@ def test_persistent_pipeline_over_many_tiles(mkq, cfg, out_name):
         ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.BF16)
     else:
         ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, s_next=0.9)
-    mkq.debug_set_gemm_config(cfg)
-    try:
-        if out_name == "bf16":
-            r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16)
-            assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
-        else:
-            r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=0.9)
-            assert np.array_equal(to_np(r["out"]), oracle.pack_nibbles(ref["q"]))
-    finally:
-        mkq.debug_set_gemm_config(-1)
+    if out_name == "bf16":
+        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16, config=cfg)
+        assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    else:
+        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=0.9, config=cfg)
+        assert np.array_equal(to_np(r["out"]), oracle.pack_nibbles(ref["q"]))
 
 
 @pytest.mark.parametrize("M", [1, 16, 33, 64, 100, 128])
 @pytest.mark.parametrize("N,K", [(200, 256), (40, 512), (768, 768), (328, 4096), (96, 2304), (72, 8192), (40, 10240)])
-def test_few_token_streaming_path(mkq, M, N, K):
-    """M <= 128 takes the weight-streaming kernel (K split over 8 waves, reduced in LDS)."""
+def test_few_token_register_path(mkq, M, N, K):
+    """Configuration 30: the first few-token kernel (K split over 8 waves, reduced in LDS)."""
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M * 7 + N)
     ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.F16, s_next=0.8)
-    mkq.debug_set_gemm_config(30)
-    try:
-        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, want_acc=True, want_q=True, s_next=0.8)
-    finally:
-        mkq.debug_set_gemm_config(-1)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, want_acc=True, want_q=True, s_next=0.8, config=30)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"]))
+
+
+@pytest.fixture(scope="module")
+def scratch(mkq):
+    return mkq.mkq_splitk_scratch_init()
+
+
+# k_slices: 0 = the library's choice, 1 = no split, others forced (clamped to K / 256)
+@pytest.mark.parametrize("k_slices", [0, 1, 2, 3, 5, 16])
+@pytest.mark.parametrize("M", [1, 16, 33, 64, 65, 100, 128])
+@pytest.mark.parametrize("N,K", [(200, 256), (40, 512), (768, 768), (328, 4096), (130, 2304), (72, 8192),
+                                 (1100, 1280), (4096, 2048)])
+def test_few_token_streaming_path(mkq, scratch, M, N, K, k_slices):
+    """M <= 128 takes the weight-streaming kernel: 128-channel workgroups (N not a multiple of 128, of 32,
+    of 8), K slices across workgroups with remainders (K / 256 not a multiple of the slice count), the
+    last-ticket reduction, and the counters left clear for the next call (every case shares one area)."""
+    if K % 256:
+        pytest.skip("the streaming kernel needs whole 128-byte row groups")
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M * 7 + N)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.F16, s_next=0.8)
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, want_acc=True, want_q=True, s_next=0.8,
+             splitk_scratch=scratch, config=50, k_slices=k_slices)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"]))
+    import torch
+    assert int(scratch[:16384].view(torch.int32).abs().sum()) == 0, "ticket counters not cleared"
+
+
+def test_few_token_default_route_and_no_scratch(mkq, scratch):
+    """The library's own route for M <= 128 with and without a scratch area gives identical bits."""
+    M, N, K = 48, 1000, 4096
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=5)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.BF16)
+    r0 = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16, want_acc=True)
+    r1 = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_BF16, want_acc=True, splitk_scratch=scratch)
+    for r in (r0, r1):
+        assert np.array_equal(to_np(r["acc"]), ref["acc"])
+        assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+
+
+def _stream_layout(packed, N, K):
+    """The streaming layout written out from its definition in the header: piece l of block g * pitch + q
+    is bytes [32 g + 16 (l // 32), + 16) of the canonical row of channel 32 q + r(l % 32); pitch = the number
+    of panels made odd."""
+    rows = packed.reshape(N, K // 2)
+    panels = (N + 31) // 32
+    out = np.zeros((K // 64, panels | 1, 64, 16), np.uint8)
+    for l in range(64):
+        i = l % 32
+        r = 16 * (i // 16) + 8 * ((i // 4) % 2) + 4 * ((i // 8) % 2) + i % 4
+        for q in range(panels):
+            n = 32 * q + r
+            if n < N:
+                out[:, q, l, :] = rows[n].reshape(K // 64, 2, 16)[:, l // 32, :]
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("N,K", [(32, 64), (64, 64), (100, 256), (130, 1280), (768, 768 + 256)])
+def test_stream_layout_repack(mkq, N, K):
+    rng = np.random.default_rng(N + K)
+    packed = rng.integers(0, 256, N * K // 2, dtype=np.uint8)
+    got = to_np(mkq.mkq_repack_weights_int4_stream(to_dev(packed), N, K))
+    assert got.size == mkq.mkq_stream_weight_bytes(N, K) == (((N + 31) // 32) | 1) * 32 * K // 2
+    assert np.array_equal(got, _stream_layout(packed, N, K))
+
+
+@pytest.mark.parametrize("prefetch,k_slices", [(0, 0), (2, 1), (3, 2), (4, 3), (6, 5), (4, 16)])
+@pytest.mark.parametrize("M", [1, 16, 33, 64, 65, 100, 128])
+@pytest.mark.parametrize("N,K", [(200, 256), (40, 512), (768, 768), (328, 4096), (130, 2304), (72, 8192),
+                                 (1100, 1280), (4096, 2048)])
+def test_few_token_linear_on_streaming_layout(mkq, scratch, M, N, K, prefetch, k_slices):
+    """mkq_linear_int4_stream: same bits as the oracle's linear on the canonical codes, for every prefetch
+    depth, with and without K slices across workgroups, ragged N (partial panels, partial 128-channel tiles)."""
+    if K % 256:
+        pytest.skip("the streaming kernel needs whole 128-byte row groups")
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M * 5 + N)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.F16, s_next=0.8)
+    a_d = mkq.mkq_pack_codes_int4(to_dev(A))
+    w_s = mkq.mkq_repack_weights_int4_stream(mkq.mkq_pack_codes_int4(to_dev(Wc)).reshape(-1), N, K)
+    r = mkq.mkq_linear_int4_stream(a_d, s_x, w_s, to_dev(s_w), to_dev(bias), N, K, mkq.MKQ_F16, want_acc=True,
+                                   want_q=True, s_next=0.8, splitk_scratch=scratch, prefetch_stages=prefetch,
+                                   k_slices=k_slices)
     assert np.array_equal(to_np(r["acc"]), ref["acc"])
     assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
     assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"]))
