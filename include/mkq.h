@@ -206,6 +206,20 @@ int mkq_linear_int4_stream(const void *a, int a_dtype, float s_x, const uint8_t 
                            const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
                            const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or carry a scratch area around -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: mkq_linear_int4_stream on packed codes
+ * (a is [M, K/2] bytes; no workspace) with the scratch of the K split taken from an area that is part of
+ * the library's code object (16 KiB of ticket counters + 16 MiB for partial sums, per GPU, held until the
+ * process ends) instead of epi->splitk_scratch, which is ignored.  Nothing is allocated or freed.  Same
+ * results as mkq_linear_int4_stream, bit for bit.  A problem whose K split would need more room for partial
+ * sums than the area has (ceil(N / 128) * slices * 16 KiB * ceil(M / 32) rounded up to 1, 2 or 4 > 16 MiB,
+ * or N > 524288) is refused with MKQ_ERR_UNSUPPORTED and nothing runs.  All calls on one GPU share the area:
+ * calls that may overlap in time on one GPU (two streams, two threads) race; calls ordered on one stream
+ * do not.  Other errors: as mkq_linear_int4. */
+int mkq_linear_int4_stream_static(const uint8_t *a, float s_x, const uint8_t *Wq_stream, const float *s_w,
+                                  const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
+                                  const mkq_epilogue *epi, void *stream);
+
 /* The same linear with both operands in 8 bits (the int8 column of Table 2 in
  * section 5.4; the 8-bit layers of the mixed 4/8-bit models of section 4.2).  Eq. 1
  * with k = 8: codes in [-128, 127], one byte each, row-major, K-contiguous.

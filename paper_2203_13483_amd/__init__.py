@@ -32,6 +32,7 @@ EXPORTS = [
     "mkq_splitk_scratch_bytes", "mkq_splitk_scratch_init", "mkq_init",
     "mkq_tuning_linear_int4", "mkq_tuning_linear_int4_e3m2", "mkq_tuning_linear_int4_stream",
     "mkq_stream_weight_bytes", "mkq_repack_weights_int4_stream", "mkq_linear_int4_stream",
+    "mkq_linear_int4_stream_static",
 ]
 
 
@@ -108,6 +109,7 @@ def load() -> C.CDLL:
                                                C.POINTER(Epilogue), vp, sz, vp, ci, ci]),
         "mkq_linear_int4_stream": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
                                         C.POINTER(Epilogue), vp, sz, vp]),
+        "mkq_linear_int4_stream_static": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp]),
         "mkq_stream_weight_bytes": (sz, [i64, i64]),
         "mkq_repack_weights_int4_stream": (ci, [vp, i64, i64, vp, vp]),
         "mkq_splitk_scratch_bytes": (sz, []),
@@ -376,6 +378,23 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
 def mkq_linear_int4_stream(a, s_x, Wq_stream, s_w, bias, N, K, out_dtype=MKQ_F32, **kw):
     """mkq_linear_int4 on weights in the streaming layout (M <= 128)."""
     return mkq_linear_int4(a, s_x, Wq_stream, s_w, bias, N, K, out_dtype, w_stream=True, **kw)
+
+
+def mkq_linear_int4_stream_static(a, s_x: float, Wq_stream, s_w, bias, N: int, K: int, out_dtype: int = MKQ_F32, *,
+                                  act: int = MKQ_ACT_NONE, residual=None, s_next: float = 0.0, out=None,
+                                  q_out=None, acc_out=None, stream=None):
+    """mkq_linear_int4_stream on packed codes with the library's own scratch: nothing is allocated by the C
+    call (outputs are the caller's: ``out`` and, optionally, ``q_out`` / ``acc_out`` must be passed in)."""
+    M = a.shape[0]
+    epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
+                   residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
+                   s_next=float(s_next), q_out=q_out.data_ptr() if q_out is not None else None,
+                   acc_out=acc_out.data_ptr() if acc_out is not None else None,
+                   splitk_scratch=None, splitk_scratch_bytes=0)
+    _check(load().mkq_linear_int4_stream_static(_ptr(a), float(s_x), _ptr(Wq_stream), _ptr(s_w), _ptr(bias), M, N, K,
+                                                _ptr(out), int(out_dtype), C.byref(epi), _stream(stream)),
+           "mkq_linear_int4_stream_static")
+    return out
 
 
 def mkq_stream_weight_bytes(N: int, K: int) -> int:

@@ -33,6 +33,7 @@ bool gemm_i4_stream_ok(const GemmI4Params &p);
 int run_gemm_i4_stream(const GemmI4Params &p, const SplitKScratch *scr, int forced_ks, hipStream_t st);
 int setup_gemm_i4_stream(const GemmI4Params &p, hipStream_t st);
 int run_gemm_i4_wstream(const GemmI4Params &p, const SplitKScratch *scr, int forced_ks, int variant, hipStream_t st);
+int gemm_i4_stream_slices(const GemmI4Params &p, const SplitKScratch *scr, int forced_ks);
 
 // Epilogue of the ring kernel through LDS, for the compile-time epilogues.  In the MFMA
 // result layout a lane owns 8 consecutive channels of one token, so a direct store
@@ -1581,7 +1582,8 @@ static bool splitk_area(void *scratch, size_t bytes, SplitKScratch *out)
 static int linear_int4_run(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,
                            const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
                            const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream,
-                           const SplitKScratch *scr, int forced_cfg, int forced_ks, bool stream_layout = false)
+                           const SplitKScratch *scr, int forced_cfg, int forced_ks, bool stream_layout = false,
+                           bool check_only = false)
 {
     const bool want_q = epi && epi->q_out;
     const bool want_acc = epi && epi->acc_out;
@@ -1614,6 +1616,7 @@ static int linear_int4_run(const void *a, int a_dtype, float s_x, const uint8_t 
         N * (K / 2) > 0xFFFFFFFFLL)
         return MKQ_ERR_UNSUPPORTED;
     if (stream_layout && (M > 128 || (K % 256) != 0)) return MKQ_ERR_UNSUPPORTED;
+    if (check_only) return MKQ_OK;
 
     GemmI4Params p;
     p.A = (a_dtype == MKQ_I4) ? (const uint8_t *)a : (const uint8_t *)workspace;
@@ -1663,6 +1666,31 @@ namespace mkq {
 int setup_gemm_f16();  // gemm_f16.hip
 }
 
+// Scratch of the entry point that allocates nothing (mkq_linear_int4_stream_static): ticket counters, then
+// room for partial sums.  One copy per GPU, at its own address on each, held until the process ends; zero
+// when the code object is loaded, and every call leaves the counters zero again.
+static __device__ __align__(256) unsigned char scratch[SPLITK_STATE_BYTES + MKQ_SPLITK_PARTIAL_BYTES];
+
+namespace mkq {
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle:
+// the address that kernels may use comes from hipGetSymbolAddress, once per device.
+static int static_scratch(void **ptr_out)
+{
+    static std::mutex mu;
+    static void *ptr[MAX_DEVICES] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return MKQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return MKQ_ERR_HIP;
+        ptr[dev] = q;
+    }
+    *ptr_out = ptr[dev];
+    return MKQ_OK;
+}
+}  // namespace mkq
+
 extern "C" int mkq_init(void)
 {
     GemmI4Params p = {};
@@ -1703,6 +1731,8 @@ extern "C" int mkq_init(void)
         }
     }
     if (rc == MKQ_OK) rc = setup_gemm_f16();
+    void *scratch_ptr = nullptr;
+    if (rc == MKQ_OK) rc = static_scratch(&scratch_ptr);
     return rc;
 }
 
@@ -1739,6 +1769,32 @@ extern "C" int mkq_linear_int4_stream(const void *a, int a_dtype, float s_x, con
     if (rc != MKQ_OK) return rc;
     return linear_int4_run(a, a_dtype, s_x, Wq_stream, s_w, bias, M, N, K, out, out_dtype, epi, workspace,
                            workspace_bytes, stream, have ? &scr : nullptr, 0, 0, true);
+}
+
+extern "C" int mkq_linear_int4_stream_static(const uint8_t *a, float s_x, const uint8_t *Wq_stream, const float *s_w,
+                                             const float *bias, int64_t M, int64_t N, int64_t K, void *out,
+                                             int out_dtype, const mkq_epilogue *epi, void *stream)
+{
+    // argument errors first, as everywhere; then the limits of the static area; only then the device
+    int rc = linear_int4_run(a, MKQ_I4, s_x, Wq_stream, s_w, bias, M, N, K, out, out_dtype, epi, nullptr, 0, stream,
+                             nullptr, 0, 0, true, true);
+    if (rc != MKQ_OK || M == 0) return rc;
+    // the K split that mkq_linear_int4_stream would choose with room to spare must fit the static area
+    GemmI4Params shape = {};
+    shape.M = (int)M; shape.N = (int)N; shape.K = (int)K;
+    SplitKScratch unbounded = {reinterpret_cast<unsigned *>(16), reinterpret_cast<int32_t *>(16), (size_t)1 << 60};
+    const int tb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
+    const int64_t tiles_n = ceil_div(N, 128);
+    if (tiles_n > SPLITK_MAX_TILES) return MKQ_ERR_UNSUPPORTED;
+    const int64_t ks = gemm_i4_stream_slices(shape, &unbounded, 0);
+    if (ks > 1 && ks * tiles_n * 4 * tb * 4096 > (int64_t)MKQ_SPLITK_PARTIAL_BYTES) return MKQ_ERR_UNSUPPORTED;
+    void *area = nullptr;
+    rc = static_scratch(&area);
+    if (rc != MKQ_OK) return rc;
+    SplitKScratch scr;
+    if (!splitk_area(area, SPLITK_STATE_BYTES + MKQ_SPLITK_PARTIAL_BYTES, &scr)) return MKQ_ERR_HIP;
+    return linear_int4_run(a, MKQ_I4, s_x, Wq_stream, s_w, bias, M, N, K, out, out_dtype, epi, nullptr, 0, stream, &scr,
+                           0, 0, true);
 }
 
 extern "C" int mkq_tuning_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,

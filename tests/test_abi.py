@@ -218,3 +218,42 @@ def test_padded_k_argument_errors(lib):
     assert w(P, 8, 316, None, P, P, None) == mkq.MKQ_ERR_SHAPE
     assert w(P, 0, 312, None, P, P, None) == mkq.MKQ_ERR_SHAPE
     assert w(P, 8, 312, None, P, ODD, None) == mkq.MKQ_ERR_ALIGN
+
+
+def test_static_scratch_entry_point_limits(lib):
+    """mkq_linear_int4_stream_static refuses, before anything runs, what its fixed scratch cannot serve."""
+    f = lib.mkq_linear_int4_stream_static
+    f.argtypes = [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                  C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+    assert f(P, 1.0, P, P, None, 129, 256, 256, P, mkq.MKQ_F16, None, None) == mkq.MKQ_ERR_UNSUPPORTED   # M > 128
+    assert f(P, 1.0, P, P, None, 16, 256, 128, P, mkq.MKQ_F16, None, None) == mkq.MKQ_ERR_UNSUPPORTED    # K % 256
+    # 600000 channels: more 128-channel tiles than ticket counters
+    assert f(P, 1.0, P, P, None, 16, 600000, 256, P, mkq.MKQ_F16, None, None) == mkq.MKQ_ERR_UNSUPPORTED
+    # 128 tokens x 12800 channels x K = 4096: three K slices of 100 tiles x 64 KiB = 18.75 MiB of partial sums
+    assert f(P, 1.0, P, P, None, 128, 12800, 4096, P, mkq.MKQ_F16, None, None) == mkq.MKQ_ERR_UNSUPPORTED
+    assert f(P, 1.0, P, P, None, -1, 256, 256, P, mkq.MKQ_F16, None, None) == mkq.MKQ_ERR_SHAPE
+    assert f(None, 1.0, P, P, None, 16, 256, 256, P, mkq.MKQ_F16, None, None) == mkq.MKQ_ERR_NULL
+    assert f(P, 0.0, P, P, None, 16, 256, 256, P, mkq.MKQ_F16, None, None) == mkq.MKQ_ERR_SCALE
+
+
+def test_splitk_scratch_and_stream_layout_argument_errors(lib):
+    assert lib.mkq_splitk_scratch_bytes() == 16384 + (16 << 20)
+    assert lib.mkq_splitk_scratch_init(None, 1 << 30, None) == mkq.MKQ_ERR_NULL
+    assert lib.mkq_splitk_scratch_init(ODD, 1 << 30, None) == mkq.MKQ_ERR_ALIGN
+    assert lib.mkq_splitk_scratch_init(P, 1024, None) == mkq.MKQ_ERR_WORKSPACE
+    assert lib.mkq_stream_weight_bytes(100, 256) == 5 * 32 * 128     # 4 panels -> pitch 5
+    assert lib.mkq_stream_weight_bytes(96, 256) == 3 * 32 * 128      # 3 panels, already odd
+    r = lib.mkq_repack_weights_int4_stream
+    assert r(None, 64, 64, P, None) == mkq.MKQ_ERR_NULL
+    assert r(P, 64, 96, P, None) == mkq.MKQ_ERR_SHAPE                 # K % 64
+    assert r(ODD, 64, 64, P, None) == mkq.MKQ_ERR_ALIGN
+    epi = mkq.Epilogue(splitk_scratch=0x1000, splitk_scratch_bytes=4096)
+    f = lib.mkq_linear_int4_stream
+    assert f(P, mkq.MKQ_I4, 1.0, P, P, None, 16, 256, 256, P, mkq.MKQ_F16, C.byref(epi), None, 0, None) == mkq.MKQ_ERR_WORKSPACE
+    assert f(P, mkq.MKQ_I4, 1.0, P, P, None, 129, 256, 256, P, mkq.MKQ_F16, None, None, 0, None) == mkq.MKQ_ERR_UNSUPPORTED
+    assert f(P, mkq.MKQ_I4, 1.0, P, P, None, 16, 256, 128, P, mkq.MKQ_F16, None, None, 0, None) == mkq.MKQ_ERR_UNSUPPORTED
+    t = lib.mkq_tuning_linear_int4
+    # a forced configuration that does not apply is refused before anything is enqueued
+    assert t(P, mkq.MKQ_I4, 1.0, P, P, None, 512, 256, 256, P, mkq.MKQ_F16, None, None, 0, None, 50, 0) == mkq.MKQ_ERR_UNSUPPORTED
+    assert t(P, mkq.MKQ_I4, 1.0, P, P, None, 512, 256, 96, P, mkq.MKQ_F16, None, None, 0, None, 18, 0) == mkq.MKQ_ERR_UNSUPPORTED
+    assert t(P, mkq.MKQ_I4, 1.0, P, P, None, 512, 256, 256, P, mkq.MKQ_F16, None, None, 0, None, 999, 0) == mkq.MKQ_ERR_UNSUPPORTED
