@@ -248,4 +248,255 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
     });
 }
 
+// Epilogue of the ring kernel through LDS, for the compile-time epilogues.  In the MFMA
+// result layout a lane owns 8 consecutive channels of one token, so a direct store
+// instruction writes 32 rows x 32 bytes and every lane needs the scales of its own
+// channels for each 8-value unit.  Here a wave instead drops one 32-token x 32-channel
+// accumulator tile at a time, as raw int32, into a wave-private LDS area (rows of 128
+// bytes, 16-byte pieces XOR-swizzled so that writes and reads are bank-conflict free)
+// and reads it back transposed: lane l then owns channels 8*(l%4) .. +7 of rows l/4
+// and l/4 + 16, i.e. the same 8 channels for the whole pass, dequantizes (and adds the
+// residual, applies GELU, re-quantizes) and stores 16 rows x 64 contiguous bytes per
+// instruction (128 for binary32, 16 for codes).  The per-channel scales and biases of
+// the wave's WTN channels are copied to LDS (sc_lds, wave-private, beyond the ring)
+// while the tile's last k stages run, so the epilogue issues no global loads that
+// would have to wait, in order, behind every copy in flight.
+// scr: wave-private LDS, 4 KiB, not in use by the ring.
+template <class Cfg>
+struct EpiShuffle {
+    static constexpr int REGION = Cfg::STAGE_BYTES / Cfg::WAVES;   // a wave's share of an idle ring slot
+    // per wave, beyond the ring: s_w then bias, each a whole number of 64-lane copies
+    static constexpr int NSL = (Cfg::WTN + 63) / 64;
+    static constexpr int BIAS_AT = NSL * 64;                       // in floats
+    static constexpr int SCALE_BYTES = 2 * BIAS_AT * 4;
+    static constexpr int EXTRA_LDS = Cfg::WAVES * SCALE_BYTES;
+    static constexpr bool usable = REGION >= 4096 && Cfg::RB == 64 &&
+                                   (Cfg::LDS_BYTES + EXTRA_LDS) * Cfg::WGS_PER_CU <= 160 * 1024;
+};
+
+template <class Cfg, class Epi>
+__device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16i (&acc)[Cfg::TM][Cfg::TN],
+                                                      int m0, int n0, int wm, int wn, int lane, uint8_t *scr,
+                                                      float *sc_lds)
+{
+    using Sh = EpiShuffle<Cfg>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, WTN = Cfg::WTN;
+    const int fr = lane & 31, fh = lane >> 5;
+    const int nw = n0 + wn * WTN;      // first channel of the wave
+    const int rrow = lane >> 2;        // reader: rows rrow and rrow + 16
+    const int pc = lane & 3;           // reader: channels 8 * pc .. + 7 of the 32-channel tile
+
+    // sc_lds holds s_w then bias of the wave's WTN channels.  Fold s_x and the accumulator's
+    // power-of-two unit (exact) into the scales once; no bias -> zeros.
+#pragma unroll
+    for (int c = lane; c < WTN; c += 64) {
+        sc_lds[c] = (p.s_x * sc_lds[c]) * p.acc_unit;
+        if (!p.bias) sc_lds[Sh::BIAS_AT + c] = 0.0f;
+    }
+    QuantStep qs4 = {}, qs8 = {};
+    if constexpr (Epi::out == MKQ_I4) qs4 = quant_step<4>(p.s_next);
+    if constexpr (Epi::out == MKQ_I8) qs8 = quant_step<8>(p.s_next);
+    // writer: the lane's 8 values of unit G are pieces 4G + 2fh, 4G + 2fh + 1 of row fr
+    const int wr_base = fr * 128;
+    const int wr_key = fr & 7;
+    // reader: pieces 2pc, 2pc + 1 of its two rows
+    int rd_off[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = rrow + 16 * i;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) rd_off[i][h] = r * 128 + (((2 * pc + h) ^ (r & 7)) * 16);
+    }
+
+    static_for<TN>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        const int c0 = t * 32 + 8 * pc;  // first of the reader lane's channels, wave-relative
+        const int n = nw + c0;
+        const float4 s0 = *reinterpret_cast<const float4 *>(sc_lds + c0);
+        const float4 s1 = *reinterpret_cast<const float4 *>(sc_lds + c0 + 4);
+        const float4 b0 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0);
+        const float4 b1 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c0 + 4);
+        const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        const float bi[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+        static_for<TM>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            __builtin_amdgcn_sched_barrier(0);
+            // write the raw tile
+#pragma unroll
+            for (int G = 0; G < 2; ++G)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    *reinterpret_cast<int4 *>(scr + wr_base + (((4 * G + 2 * fh + h) ^ wr_key) * 16)) =
+                        make_int4(acc[j][t][8 * G + 4 * h], acc[j][t][8 * G + 4 * h + 1],
+                                  acc[j][t][8 * G + 4 * h + 2], acc[j][t][8 * G + 4 * h + 3]);
+            // read it back row-wise
+            int4 raw[2][2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) raw[i][h] = *reinterpret_cast<const int4 *>(scr + rd_off[i][h]);
+            const int mbase = m0 + wm * Cfg::WTM + j * 32 + rrow;
+            uint4 res[2];
+            if (Epi::res16) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int m = mbase + 16 * i;
+                    res[i] = (m < p.M && n < p.N)
+                                 ? *reinterpret_cast<const uint4 *>((const uint16_t *)p.residual + (int64_t)m * p.N + n)
+                                 : make_uint4(0, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int a[8] = {raw[i][0].x, raw[i][0].y, raw[i][0].z, raw[i][0].w,
+                                  raw[i][1].x, raw[i][1].y, raw[i][1].z, raw[i][1].w};
+                float y[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    y[e] = __fmaf_rn((float)a[e], sc[e], bi[e]);
+                    asm volatile("" : "+v"(y[e]));  // keep the binary32 rounding (no fused narrowing)
+                }
+                if (Epi::res16) {
+                    const uint32_t rwd[4] = {res[i].x, res[i].y, res[i].z, res[i].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        y[2 * e] += half_bits_to_float((uint16_t)(rwd[e] & 0xFFFFu));
+                        y[2 * e + 1] += half_bits_to_float((uint16_t)(rwd[e] >> 16));
+                    }
+                }
+                if (Epi::gelu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) y[e] = gelu_erf(y[e]);
+                }
+                const int m = mbase + 16 * i;
+                const bool ok = m < p.M && n < p.N;  // N % 8 == 0: a lane's 8 channels are all in or all out
+                const int64_t o = (int64_t)m * p.N + n;
+                if (Epi::out == MKQ_F32) {
+                    if (ok) {
+                        float *dst = (float *)p.out + o;
+                        *reinterpret_cast<float4 *>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(y[4], y[5], y[6], y[7]);
+                    }
+                } else if (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16) {
+                    uint32_t hw[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        hw[e] = (Epi::out == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1]) : pack2_bf16(y[2 * e], y[2 * e + 1]);
+                    if (ok) *reinterpret_cast<uint4 *>((uint16_t *)p.out + o) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                } else if (Epi::out == MKQ_I8) {
+                    int cd[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(y[e], qs8);
+                    if (ok) *reinterpret_cast<uint2 *>((uint8_t *)p.out + o) = bytes8(cd);
+                } else {
+                    uint32_t packed = 0;  // Eq. 1 on the binary32 value
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        packed |= ((uint32_t)quantize_code_rs<4>(y[e], qs4) & 0xFu) << (4 * e);
+                    if (ok) *reinterpret_cast<uint32_t *>((uint8_t *)p.out + (o >> 1)) = packed;
+                }
+            }
+        });
+    });
+}
+
+// Row epilogue for 16-bit outputs of waves that own 64 channels (TN = 2); accumulators are int32 or binary32
+// holding exact integers.  Values are dequantized and narrowed in the MFMA register layout first, so the
+// transposition moves 2 bytes per value instead of 4, and a 32-token block is laid out as rows of 128
+// bytes (64 channels): every store instruction then writes 8 whole 128-byte lines.
+// scr: wave-private LDS, 4 KiB; sc_lds: s_w then bias of the wave's 64 channels (as for the row epilogue).
+template <class Cfg, class Epi>
+struct EpiLines16 {
+    static constexpr bool usable = !Epi::generic && !Epi::res16 && !Epi::gelu && Cfg::TN == 2 && Cfg::WTN == 64 &&
+                                   (Epi::out == MKQ_F16 || Epi::out == MKQ_BF16);
+};
+
+template <class Cfg, class Epi, bool CACHE_SCALES = true, class AccV>
+__device__ __forceinline__ void gemm_epilogue_lines16(const GemmI4Params &p, AccV (&acc)[Cfg::TM][Cfg::TN],
+                                                      int m0, int n0, int wm, int wn, int lane, uint8_t *scr,
+                                                      float *sc_lds)
+{
+    using Sh = EpiShuffle<Cfg>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    static_assert(EpiLines16<Cfg, Epi>::usable, "64 channels per wave, plain 16-bit outputs");
+    const int fr = lane & 31, fh = lane >> 5;
+    sc_lds[lane] = (p.s_x * sc_lds[lane]) * p.acc_unit;
+    if (!p.bias) sc_lds[Sh::BIAS_AT + lane] = 0.0f;
+
+    // the lane's 32 channels: register 8h + e of tile t is channel 32t + 16h + 8fh + e.  Their scales and
+    // biases are either held in 64 registers for the whole tile or fetched again for every 8 values.
+    auto load8 = [&](int t, int h, float (&s8)[8], float (&b8)[8]) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c = 32 * t + 16 * h + 8 * fh + 4 * q;
+            const float4 s4 = *reinterpret_cast<const float4 *>(sc_lds + c);
+            const float4 b4 = *reinterpret_cast<const float4 *>(sc_lds + Sh::BIAS_AT + c);
+            s8[4 * q] = s4.x; s8[4 * q + 1] = s4.y; s8[4 * q + 2] = s4.z; s8[4 * q + 3] = s4.w;
+            b8[4 * q] = b4.x; b8[4 * q + 1] = b4.y; b8[4 * q + 2] = b4.z; b8[4 * q + 3] = b4.w;
+        }
+    };
+    float sc[CACHE_SCALES ? TN * 2 : 1][8], bi[CACHE_SCALES ? TN * 2 : 1][8];
+    if constexpr (CACHE_SCALES) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) load8(t, h, sc[2 * t + h], bi[2 * t + h]);
+    }
+    // writer: 16-byte piece 4t + 2h + fh of row fr; pieces are XOR-swizzled with bits 1 .. 3 of the row so
+    // that 16 consecutive rows spread one piece column over all banks.  reader: row lane / 8 + 8i, piece lane % 8.
+    const int wr_base = fr * 128, wr_key = (fr >> 1) & 7;
+    const int rrow = lane >> 3, rq = lane & 7;
+    const int n = n0 + wn * 64 + 8 * rq;
+    static_for<TM>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                uint32_t hw[4];
+                constexpr int u = CACHE_SCALES ? 1 : 0;
+                if constexpr (!CACHE_SCALES) load8(t, h, sc[0], bi[0]);
+                const float(&s8)[8] = sc[u * (2 * t + h)];
+                const float(&b8)[8] = bi[u * (2 * t + h)];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float y0 = __fmaf_rn((float)acc[j][t][8 * h + 2 * e], s8[2 * e], b8[2 * e]);
+                    float y1 = __fmaf_rn((float)acc[j][t][8 * h + 2 * e + 1], s8[2 * e + 1], b8[2 * e + 1]);
+                    asm volatile("" : "+v"(y0), "+v"(y1));  // keep the binary32 rounding (no fused narrowing)
+                    hw[e] = (Epi::out == MKQ_F16) ? pack2_f16(y0, y1) : pack2_bf16(y0, y1);
+                }
+                *reinterpret_cast<uint4 *>(scr + wr_base + (((4 * t + 2 * h + fh) ^ wr_key) * 16)) =
+                    make_uint4(hw[0], hw[1], hw[2], hw[3]);
+            }
+        const int mbase = m0 + wm * Cfg::WTM + j * 32 + rrow;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = rrow + 8 * i;
+            const uint4 v = *reinterpret_cast<const uint4 *>(scr + r * 128 + ((rq ^ ((r >> 1) & 7)) * 16));
+            const int m = mbase + 8 * i;
+            if (m < p.M && n < p.N) *reinterpret_cast<uint4 *>((uint16_t *)p.out + (int64_t)m * p.N + n) = v;
+        }
+    });
+}
+
+// Epilogue combinations with a dedicated instantiation of the fast kernels.
+enum { EPI_F16 = 0, EPI_BF16, EPI_F32, EPI_F16_RES16, EPI_I4_GELU, EPI_I4, EPI_I8_GELU, EPI_GENERIC };
+
+inline int classify_epilogue(const GemmI4Params &p)
+{
+    if ((p.N % 8) != 0 || p.acc_out || p.q_out) return EPI_GENERIC;
+    const bool res16 = p.residual && p.residual_dtype == MKQ_F16;
+    const bool gelu = p.act == MKQ_ACT_GELU;
+    if (p.residual && !res16) return EPI_GENERIC;
+    if (p.out_dtype == MKQ_F16 && !gelu) return res16 ? EPI_F16_RES16 : EPI_F16;
+    if (res16) return EPI_GENERIC;
+    if (p.out_dtype == MKQ_BF16 && !gelu) return EPI_BF16;
+    if (p.out_dtype == MKQ_F32 && !gelu) return EPI_F32;
+    if (p.out_dtype == MKQ_I4) return gelu ? EPI_I4_GELU : EPI_I4;
+    if (p.out_dtype == MKQ_I8 && gelu && !p.residual) return EPI_I8_GELU;
+    return EPI_GENERIC;
+}
+
+
 }  // namespace mkq
