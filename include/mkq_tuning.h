@@ -44,6 +44,22 @@ int mkq_tuning_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, 
                                 const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,
                                 const mkq_epilogue *epi, void *stream, int config);
 
+/* Measured ceilings, printed by the benchmark beside every roofline fraction (they compute nothing of the
+ * method).  All enqueue one kernel on `stream`; the caller times it.
+ *   mkq_measure_stream    kind 0: read `bytes` from src (dst: 16 bytes, never written in practice), 1: write
+ *                         `bytes` to dst, 2: copy src -> dst.  bytes % 16 == 0.  Device pointers, 16-byte aligned.
+ *   mkq_measure_mfma_i8   a register-only loop of v_mfma_i32_32x32x32_i8, 8 independent accumulator tiles per
+ *                         wave, two workgroups of four waves per compute unit, `iters` rounds; the operands
+ *                         (6 x 16 bytes per lane) are read once from `operands`, which the caller fills with bytes
+ *                         of the kind the GEMM multiplies (16 * code) -- the chip's clock under a matrix load
+ *                         depends on the data.  mkq_measure_mfma_i8_operand_bytes() = the size it reads;
+ *                         mkq_measure_mfma_i8_ops(iters) = integer operations of one launch (0 on error).
+ * Errors: NULL, ALIGN, SHAPE, DTYPE (kind), WORKSPACE (operands too small), HIP. */
+int mkq_measure_stream(int kind, const void *src, void *dst, size_t bytes, void *stream);
+size_t mkq_measure_mfma_i8_operand_bytes(void);
+int64_t mkq_measure_mfma_i8_ops(int iters);
+int mkq_measure_mfma_i8(const void *operands, size_t operand_bytes, int iters, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

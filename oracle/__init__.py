@@ -22,11 +22,18 @@ F32, F16, BF16 = 0, 1, 2
 ACT_NONE, ACT_GELU = 0, 1
 
 
+CFLAGS = ["-O2", "-march=native", "-fopenmp", "-ffp-contract=off"]
+
+
+def build_flags() -> str:
+    """The compiler and flags the oracle is built with (quoted beside its timing)."""
+    return "gcc " + " ".join(CFLAGS)
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no HIP, no BLAS).  Returns the library path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-march=native", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        cmd = ["gcc", *CFLAGS, "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

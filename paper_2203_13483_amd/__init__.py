@@ -33,6 +33,7 @@ EXPORTS = [
     "mkq_tuning_linear_int4", "mkq_tuning_linear_int4_e3m2", "mkq_tuning_linear_int4_stream",
     "mkq_stream_weight_bytes", "mkq_repack_weights_int4_stream", "mkq_linear_int4_stream",
     "mkq_linear_int4_stream_static",
+    "mkq_measure_stream", "mkq_measure_mfma_i8_operand_bytes", "mkq_measure_mfma_i8_ops", "mkq_measure_mfma_i8",
 ]
 
 
@@ -110,6 +111,10 @@ def load() -> C.CDLL:
         "mkq_linear_int4_stream": (ci, [vp, ci, f32, vp, vp, vp, i64, i64, i64, vp, ci,
                                         C.POINTER(Epilogue), vp, sz, vp]),
         "mkq_linear_int4_stream_static": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp]),
+        "mkq_measure_stream": (ci, [ci, vp, vp, sz, vp]),
+        "mkq_measure_mfma_i8_operand_bytes": (sz, []),
+        "mkq_measure_mfma_i8_ops": (i64, [ci]),
+        "mkq_measure_mfma_i8": (ci, [vp, sz, ci, vp, vp]),
         "mkq_stream_weight_bytes": (sz, [i64, i64]),
         "mkq_repack_weights_int4_stream": (ci, [vp, i64, i64, vp, vp]),
         "mkq_splitk_scratch_bytes": (sz, []),
@@ -395,6 +400,17 @@ def mkq_linear_int4_stream_static(a, s_x: float, Wq_stream, s_w, bias, N: int, K
                                                 _ptr(out), int(out_dtype), C.byref(epi), _stream(stream)),
            "mkq_linear_int4_stream_static")
     return out
+
+
+def mkq_measure_stream(kind: int, src, dst, nbytes: int, stream=None):
+    _check(load().mkq_measure_stream(int(kind), _ptr(src), _ptr(dst), int(nbytes), _stream(stream)), "mkq_measure_stream")
+
+
+def mkq_measure_mfma_i8(operands, iters: int, sink, stream=None):
+    """One launch of the register-only int8 MFMA loop; returns the integer operations it performs."""
+    _check(load().mkq_measure_mfma_i8(_ptr(operands), operands.numel() * operands.element_size(), int(iters),
+                                      _ptr(sink), _stream(stream)), "mkq_measure_mfma_i8")
+    return int(load().mkq_measure_mfma_i8_ops(int(iters)))
 
 
 def mkq_stream_weight_bytes(N: int, K: int) -> int:

@@ -475,7 +475,13 @@ __device__ __forceinline__ void gemm_epilogue_lines16(const GemmI4Params &p, Acc
             const int r = rrow + 8 * i;
             const uint4 v = *reinterpret_cast<const uint4 *>(scr + r * 128 + ((rq ^ ((r >> 1) & 7)) * 16));
             const int m = mbase + 8 * i;
-            if (m < p.M && n < p.N) *reinterpret_cast<uint4 *>((uint16_t *)p.out + (int64_t)m * p.N + n) = v;
+            // (streaming store: the output is written once and not read by this kernel; kept out of the way of
+            // the operand panels that other tiles re-read from L2)
+            if (m < p.M && n < p.N) {
+                typedef unsigned v4u __attribute__((ext_vector_type(4)));
+                __builtin_nontemporal_store(v4u{v.x, v.y, v.z, v.w},
+                                            reinterpret_cast<v4u *>((uint16_t *)p.out + (int64_t)m * p.N + n));
+            }
         }
     });
 }
