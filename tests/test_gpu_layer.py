@@ -10,6 +10,7 @@ import pytest
 import oracle
 from paper_2203_13483_amd import workloads as wl
 from helpers import RTOL, assert_codes_match_with_tie_band, assert_float_close, to_dev, to_np
+from layer_checks import LayerBuffers, attention_code_band, check_layer_stagewise, codes_match
 
 pytestmark = pytest.mark.gpu
 
@@ -54,8 +55,10 @@ def test_attention(mkq, B, S, heads):
     ref = oracle.attention(qkv.astype(np.float32), B, S, H, heads, p_dtype=oracle.F16)
     assert_float_close(to_np(ctx).astype(np.float32), ref, RTOL[1], "attention")
     got = oracle.unpack_nibbles(to_np(q), H)
-    assert_codes_match_with_tie_band(got, oracle.quantize(ref, s_next), ref, s_next, band=2.0 ** -6,
-                                     max_frac=2e-3, what="attention codes")
+    for b in range(B):  # the band of every element: what one binary16 unit of every probability can move it
+        rows = slice(b * S, (b + 1) * S)
+        codes_match(got[rows], oracle.quantize(ref[rows], s_next), ref[rows], s_next,
+                    attention_code_band(qkv[rows].astype(np.float32), S, H, heads, s_next), "attention codes")
     # the probabilities of one query sum to one: with v = 1 the context is 1
     ones = qkv.copy()
     ones[:, 2 * H:] = 1.0
@@ -149,8 +152,10 @@ def test_bert_layer_int4_stagewise_and_end_to_end(mkq, B, S, hidden, heads, ffn)
     r = oracle.linear_int4(c0, q["sx_qkv"], q["w_qkv"], q["sw_qkv"], q["b_qkv"], out_dtype=oracle.F16)
     assert np.array_equal(qkv, r["y"])
     ctx_ref = oracle.attention(qkv, B, S, hidden, heads, p_dtype=oracle.F16)
-    assert_codes_match_with_tie_band(c1, oracle.quantize(ctx_ref, q["sx_ao"]), ctx_ref, q["sx_ao"], band=2.0 ** -6,
-                                     max_frac=2e-3, what="context codes")
+    for b in range(B):
+        rows = slice(b * S, (b + 1) * S)
+        codes_match(c1[rows], oracle.quantize(ctx_ref[rows], q["sx_ao"]), ctx_ref[rows], q["sx_ao"],
+                    attention_code_band(qkv[rows], S, hidden, heads, q["sx_ao"]), "context codes")
     r = oracle.linear_int4(c1, q["sx_ao"], q["w_ao"], q["sw_ao"], q["b_ao"], residual=hf, out_dtype=oracle.F16)
     assert np.array_equal(u, r["y"])
     h1_ref = oracle.layernorm(u, p["ln1_gamma"], p["ln1_beta"], p["ln_eps"])
@@ -218,8 +223,8 @@ def test_attention_over_ragged_sequences(mkq, batch, total, max_seq, heads):
         rows = slice(cu[b], cu[b + 1])
         ref = oracle.attention(qkv[rows].astype(np.float32), 1, int(lens[b]), H, heads, p_dtype=oracle.F16)
         assert_float_close(got[rows], ref, RTOL[1], f"sequence {b} of length {lens[b]}")
-        assert_codes_match_with_tie_band(codes[rows], oracle.quantize(ref, s_next), ref, s_next, band=2.0 ** -6,
-                                         max_frac=5e-3, what="context codes")
+        codes_match(codes[rows], oracle.quantize(ref, s_next), ref, s_next,
+                    attention_code_band(qkv[rows].astype(np.float32), int(lens[b]), H, heads, s_next), "context codes")
     # equal lengths that are a multiple of 32 reproduce the fixed-length entry point exactly
     S = 64
     qkv2 = _f16(rng.normal(0, 1.0, (3 * S, 3 * H)))
@@ -262,9 +267,15 @@ def test_layers_on_a_padding_free_batch(mkq, kind):
             packed[nm] = pack(to_dev(p["W_" + nm])) + (to_dev(p["b_" + nm]),)
         cls = mkq.BertLayerInt4 if kind == "int4" else mkq.BertLayerInt8
         layer = cls(batch, 100, hidden, heads, ffn, packed, sx, ln, p["ln_eps"], cu_seqlens=cud, total_tokens=total)
-    ws = torch.empty(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
     out = to_np(layer(to_dev(h), ws)).astype(np.float32)
     assert out.shape == (total, hidden)
+    if kind != "fp16":
+        # every stage of every sequence against the oracle fed the GPU's own previous stage: a wrong row range
+        # at a sequence seam or one bad head shows in the stage where it happens
+        buf = LayerBuffers(to_np(ws), layer.layout, total, hidden, ffn, 4 if kind == "int4" else 8)
+        check_layer_stagewise(buf, base, h.astype(np.float32), out, [(int(cu[b]), int(lens[b])) for b in range(batch)],
+                              what=kind + " ragged")
     for b in range(batch):
         rows = slice(cu[b], cu[b + 1])
         q = dict(base, batch=1, seq=int(lens[b]))

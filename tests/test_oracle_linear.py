@@ -321,3 +321,30 @@ def test_zero_weight_layer_reduces_to_two_layernorms():
     h1 = oracle.layernorm(h, p["ln1_gamma"], p["ln1_beta"], p["ln_eps"])
     ref = oracle.layernorm(h1, p["ln2_gamma"], p["ln2_beta"], p["ln_eps"])
     np.testing.assert_allclose(out, ref, rtol=1e-6, atol=1e-6)
+
+
+def test_attention_with_probabilities_narrowed_before_the_value_product():
+    """The p_dtype = F16 branch (softmax probabilities rounded to binary16 BEFORE P.v, as a 16-bit matrix
+    unit consumes them) against torch in float64: softmax -> .half() -> matmul.  The same data distinguish it
+    from narrowing nothing and from narrowing the context instead."""
+    import torch
+    B, S, heads = 2, 48, 3
+    H = heads * 64
+    rng = np.random.default_rng(31)
+    qkv = rng.normal(0, 1.2, (B * S, 3 * H)).astype(np.float16).astype(np.float32)
+    got = oracle.attention(qkv, B, S, H, heads, p_dtype=oracle.F16)
+    t = torch.from_numpy(qkv).double().reshape(B, S, 3, heads, 64)
+    q, k, v = (t[:, :, i].permute(0, 2, 1, 3) for i in range(3))  # [B, heads, S, 64]
+    p = torch.softmax(q @ k.transpose(-1, -2) / 8.0, dim=-1)
+    narrowed_p = (p.half().double() @ v).permute(0, 2, 1, 3).reshape(B * S, H).numpy()
+    plain = (p @ v).permute(0, 2, 1, 3).reshape(B * S, H).numpy()
+    narrowed_ctx = torch.from_numpy(plain).half().double().numpy()
+    # binary64 -> binary16 in one rounding on the torch side; the oracle may round through binary32 first: the two
+    # agree except where that double rounding lands on a binary16 tie (one unit of one probability, at most)
+    err = np.abs(got - narrowed_p)
+    assert err.max() < 2.0 ** -10 * np.abs(qkv[:, 2 * H:]).max() / 4 and np.mean(err > 1e-6) < 1e-3
+    assert np.sqrt((err ** 2).mean()) < 2e-7
+    # the placement of the narrowing is visible at this size: the other two placements are 100x further away
+    assert np.sqrt(((got - plain) ** 2).mean()) > 2e-5
+    assert np.sqrt(((got - narrowed_ctx) ** 2).mean()) > 2e-5
+    assert np.allclose(oracle.attention(qkv, B, S, H, heads, p_dtype=oracle.F32), plain, rtol=0, atol=2e-6)
