@@ -1,0 +1,62 @@
+"""The library's own choice of kernel configuration against every configuration it could have picked, at the
+benchmark's shapes: the automatic choice must not be more than 5 % (plus timer noise) slower than the fastest
+forced configuration.  A timing test: medians of graph replays, on an otherwise idle GPU."""
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+CONFIGS = [11, 12, 14, 18, 19, 20, 27, 28, 29, 31, 33, 35]
+# (M, K, N): BERT-base layer GEMMs at M = 1024 and 4096, BERT-large at M = 8192, the large-M sweep at M = 16384
+SHAPES = ([(M, K, N) for M in (1024, 4096) for (K, N) in ((768, 2304), (768, 768), (768, 3072), (3072, 768))]
+          + [(8192, 1024, 3072), (8192, 1024, 1024), (8192, 1024, 4096), (8192, 4096, 1024)]
+          + [(16384, 1024, 4096), (16384, 4096, 1024), (16384, 768, 3072)])
+
+
+def _time(fn, rep=10, samples=7):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(rep):
+            fn()
+    ts = []
+    for _ in range(samples):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g.replay()
+        e0.record()
+        g.replay()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) / (2 * rep))
+    return sorted(ts)[len(ts) // 2]
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_automatic_choice_is_within_five_percent_of_the_best(M, K, N):
+    import torch
+    import paper_2203_13483_amd as mkq
+    mkq.load()
+    a = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda")
+    w = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
+    sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+
+    def run(cfg):
+        return lambda: mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_F16, out=out, config=cfg)
+
+    times = {}
+    for cfg in CONFIGS:
+        try:
+            run(cfg)()
+        except mkq.MkqError as e:
+            assert e.status == mkq.MKQ_ERR_UNSUPPORTED
+            continue
+        times[cfg] = _time(run(cfg))
+    auto = _time(run(None))
+    best_cfg = min(times, key=times.get)
+    auto = min(auto, _time(run(None)))  # (second sample: the clock moves between measurements)
+    print(f"M={M} K={K} N={N}: automatic {auto * 1e3:.2f} us, best forced {best_cfg}: {times[best_cfg] * 1e3:.2f} us; "
+          + " ".join(f"{c}:{t * 1e3:.1f}" for c, t in sorted(times.items())))
+    assert auto <= 1.05 * times[best_cfg] + 0.0003, (auto, best_cfg, times[best_cfg])
