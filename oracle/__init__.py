@@ -23,6 +23,23 @@ ACT_NONE, ACT_GELU = 0, 1
 
 
 CFLAGS = ["-O2", "-march=native", "-fopenmp", "-ffp-contract=off"]
+# MKQ_ORACLE_SANITIZE=undefined: the same source built with the undefined-behaviour sanitizer (any report aborts
+# the process); the CPU test tier runs the oracle's pins once more under it.  (The address sanitizer needs its
+# runtime loaded before anything else, which a library loaded into Python cannot arrange: it runs in the
+# stand-alone driver sanitize_driver.c instead.)
+_SANITIZE = os.environ.get("MKQ_ORACLE_SANITIZE", "")
+if _SANITIZE:
+    assert _SANITIZE == "undefined", "MKQ_ORACLE_SANITIZE: only 'undefined' can be loaded into Python"
+    CFLAGS = ["-O1", "-g", "-fopenmp", "-ffp-contract=off", "-fsanitize=undefined", "-fno-sanitize-recover=all"]
+    _LIB = os.path.join(_HERE, "libmkq_oracle_ubsan.so")
+
+
+def build_sanitizer_driver(out_path: str) -> str:
+    """Compile sanitize_driver.c (with the oracle inside it) under the address and undefined-behaviour sanitizers."""
+    cmd = ["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fopenmp",
+           "-ffp-contract=off", "-Wall", "-Wextra", "-o", out_path, os.path.join(_HERE, "sanitize_driver.c"), "-lm"]
+    subprocess.run(cmd, check=True)
+    return out_path
 
 
 def build_flags() -> str:
