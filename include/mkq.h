@@ -373,12 +373,16 @@ int mkq_layernorm(const void *x, int64_t M, int64_t D, const float *gamma, const
 
 /* Attention core of section 3.2 on a fused binary16 qkv buffer [batch*seq, 3*hidden]:
  * ctx binary16 [batch*seq, hidden] (may be NULL) and/or q_out packed codes under s_next.
- * Currently d_k == 64, seq % 32 == 0, seq <= 128 (anything else: UNSUPPORTED). */
+ * Scores are scaled by 1/sqrt(d_k), d_k = hidden / heads; the softmax runs in binary32 and its normalized
+ * probabilities are narrowed to binary16 before they multiply v.
+ * d_k even and <= 64, hidden % 8 == 0, seq <= 4096 (anything else: UNSUPPORTED).  d_k == 64 with
+ * seq <= 128 takes a kernel that holds all keys of a (sequence, head) at once; everything else one that
+ * walks the keys in blocks of 128, twice (row maximum and denominator, then the weighted sum). */
 int mkq_attention(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads,
                   void *ctx, float s_next, uint8_t *q_out, void *stream);
 
 /* Attention over a padding-free batch: qkv [total_tokens, 3*hidden], sequence b = rows
- * cu_seqlens[b] .. cu_seqlens[b+1] - 1 (device array [batch + 1]), each at most max_seq <= 128 rows
+ * cu_seqlens[b] .. cu_seqlens[b+1] - 1 (device array [batch + 1]), each at most max_seq <= 4096 rows
  * (any length; an empty sequence is skipped).  q_out: codes of q_bits (4: [total, hidden/2] bytes,
  * 8: [total, hidden] bytes) or NULL.  Errors as mkq_attention, plus DTYPE for q_bits. */
 int mkq_attention_varlen(const void *qkv, const int32_t *cu_seqlens, int64_t batch, int64_t max_seq,

@@ -1568,6 +1568,9 @@ extern "C" int mkq_tuning_linear_int4_stream(const void *a, int a_dtype, float s
                                              void *out, int out_dtype, const mkq_epilogue *epi, void *workspace,
                                              size_t workspace_bytes, void *stream, int prefetch_stages, int k_slices)
 {
+    if (prefetch_stages != 0 && prefetch_stages != 2 && prefetch_stages != 3 && prefetch_stages != 4 &&
+        prefetch_stages != 6)
+        return MKQ_ERR_UNSUPPORTED;
     SplitKScratch scr;
     bool have = false;
     const int rc = epilogue_scratch(epi, &scr, &have);

@@ -195,9 +195,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_stream_kernel(const Gemm
 // memory channels.
 __host__ __device__ inline int stream_pitch_panels(int N) { return ((N + 31) / 32) | 1; }
 
-template <int TB_, int P_, int DIAG_ = 0>
+template <int TB_, int P_>
 struct WStreamCfg {
-    static constexpr int TB = TB_, P = P_, DIAG = DIAG_;
+    static constexpr int TB = TB_, P = P_;
     static constexpr int WAVES = 4, THREADS = 256, BN = 128;
     static constexpr int STAGE_BYTES = 32 * TB * 128;  // activations only
     static constexpr int LPW = 4 + TB;                 // per wave per stage: 4 weight loads, TB activation copies
@@ -255,7 +255,6 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_wstream_kernel(const Gem
 #pragma unroll
         for (int r = 0; r < 4; ++r) fw[j][r] = wp[(size_t)(4 * g + r) * block_pitch];
         const uint8_t *ak = p.A + (size_t)g * 128;
-        if constexpr (Cfg::DIAG < 2)
         static_for<TB>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             dma_copy16<i * 4096>(ak, aoff[i], lds0 + j * Cfg::STAGE_BYTES + wave * 1024);
@@ -285,28 +284,19 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i4_wstream_kernel(const Gem
         static_for<P>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             const int t = it * P + j;
-            if constexpr (Cfg::DIAG < 2) {
-                wait_vmcnt<(P - 2) * LPW>();
-                lds_barrier();
-            }
+            wait_vmcnt<(P - 2) * LPW>();
+            lds_barrier();
             issue(IntC<(j + P - 1) % P>{}, t + P - 1);
             const uint32_t live = t < steps ? 0xFFFFFFFFu : 0u;
             const uint8_t *st = smem + j * Cfg::STAGE_BYTES;
-            if constexpr (Cfg::DIAG >= 1) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    acc[0][0][0] ^= fw[j][r].x & live; acc[0][0][1] ^= fw[j][r].y; acc[0][0][2] ^= fw[j][r].z; acc[0][0][3] ^= fw[j][r].w;
-                }
-            } else {
+            for (int r = 0; r < 4; ++r) {
+                const v4i w0 = widen(fw[j][r].x & live, fw[j][r].y & live), w1 = widen(fw[j][r].z & live, fw[j][r].w & live);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const v4i w0 = widen(fw[j][r].x & live, fw[j][r].y & live), w1 = widen(fw[j][r].z & live, fw[j][r].w & live);
-#pragma unroll
-                    for (int tb = 0; tb < TB; ++tb) {
-                        const uint4 fa = *reinterpret_cast<const uint4 *>(st + rdA[r] + 4096 * tb);
-                        acc[tb][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w0, widen(fa.x, fa.y), acc[tb][0], 0, 0, 0);
-                        acc[tb][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, widen(fa.z, fa.w), acc[tb][0], 0, 0, 0);
-                    }
+                for (int tb = 0; tb < TB; ++tb) {
+                    const uint4 fa = *reinterpret_cast<const uint4 *>(st + rdA[r] + 4096 * tb);
+                    acc[tb][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w0, widen(fa.x, fa.y), acc[tb][0], 0, 0, 0);
+                    acc[tb][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, widen(fa.z, fa.w), acc[tb][0], 0, 0, 0);
                 }
             }
         });
@@ -393,9 +383,6 @@ int run_gemm_i4_wstream(const GemmI4Params &p, const SplitKScratch *scr, int for
         if (variant == 2) return launch_wstream<WStreamCfg<1, 2>>(p, sk, st);
         if (variant == 3) return launch_wstream<WStreamCfg<1, 3>>(p, sk, st);
         if (variant == 6) return launch_wstream<WStreamCfg<1, 6>>(p, sk, st);
-        if (variant == 14) return launch_wstream<WStreamCfg<1, 4, 1>>(p, sk, st);
-        if (variant == 24) return launch_wstream<WStreamCfg<1, 4, 2>>(p, sk, st);
-        if (variant == 26) return launch_wstream<WStreamCfg<1, 6, 2>>(p, sk, st);
         return launch_wstream<WStreamCfg<1, 4>>(p, sk, st);
     }
     if (p.M <= 64) {

@@ -4,6 +4,8 @@
 // BERT layer in the int4 and in the binary16 baseline flavour.
 #include "gemm_common.h"
 
+#include <type_traits>
+
 namespace mkq {
 
 // ---------------------------------------------------------------------------------
@@ -327,6 +329,221 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
         }
 }
 
+// ---------------------------------------------------------------------------------
+// Attention core for any sequence length and any even head size d_k <= DKP (DKP = 32 or 64; the head
+// dimensions d_k .. DKP-1 are zero in the staged q, k, v and never stored).  One workgroup per (sequence,
+// head, block of 128 queries); the keys go through LDS in blocks of 128, twice:
+//   pass 1  S^T = K Q^T / sqrt(d_k) per key block, running row maximum and denominator of the softmax
+//   pass 2  the same scores again, P = exp(S - max) / denominator in binary32, narrowed to binary16, and
+//           O^T += V^T P^T
+// so the probabilities that meet V are the normalized ones, as in the one-block kernel above (an online
+// softmax would narrow unnormalized ones).  VEC = 8: 16-byte accesses (d_k % 8 == 0); VEC = 2: 4-byte ones.
+template <int DKP, int VEC>
+__global__ __launch_bounds__(256) void attention_blocks_kernel(const uint16_t *__restrict__ qkv, int seq_fixed,
+                                                               int hidden, int heads, int dk, int q_blocks,
+                                                               uint16_t *__restrict__ ctx, float s_next,
+                                                               uint8_t *__restrict__ qout, int q_bits, int q_pitch,
+                                                               const int32_t *__restrict__ cu_seqlens)
+{
+    constexpr int ROWB = DKP * 2;  // bytes of a staged q or k row
+    constexpr int CH = DKP / 8;    // its 16-byte chunks
+    constexpr int VROW = 256;      // V^T row: 128 keys
+    __shared__ __attribute__((aligned(16))) uint8_t sQ[128 * ROWB];
+    __shared__ __attribute__((aligned(16))) uint8_t sK[128 * ROWB];
+    __shared__ __attribute__((aligned(16))) uint8_t sVt[DKP * VROW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 31, fh = lane >> 5;
+    const int qb = blockIdx.x % q_blocks, bh = blockIdx.x / q_blocks;
+    const int b = bh / heads, head = bh % heads;
+    const int64_t row0 = cu_seqlens ? (int64_t)cu_seqlens[b] : (int64_t)b * seq_fixed;
+    const int seq = cu_seqlens ? (cu_seqlens[b + 1] - cu_seqlens[b]) : seq_fixed;
+    const int q_base = qb * 128;
+    if (q_base >= seq) return;  // the whole workgroup: no barrier has been passed
+    const int ld = 3 * hidden;
+    const int key_blocks = (seq + 127) / 128;
+
+    using Piece = typename std::conditional<VEC == 8, uint4, uint32_t>::type;
+    constexpr int PER_T = 128 * DKP / VEC / 256;  // pieces of one 128-row block per thread
+    // rows r_base .. r_base + 127 of the sequence (clamped to its last row), columns col + head * dk + [0, DKP)
+    auto load_block = [&](Piece (&v)[PER_T], int r_base, int col) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+            const int idx = tid + i * 256;
+            const int r = idx / (DKP / VEC), d = (idx % (DKP / VEC)) * VEC;
+            int rr = r_base + r;
+            rr = rr < seq ? rr : seq - 1;
+            if (d < dk) v[i] = *reinterpret_cast<const Piece *>(qkv + (row0 + rr) * ld + col + head * dk + d);
+            else v[i] = Piece{};
+        }
+    };
+    auto store_rows = [&](uint8_t *dst, const Piece (&v)[PER_T]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+            const int idx = tid + i * 256;
+            const int r = idx / (DKP / VEC), d = (idx % (DKP / VEC)) * VEC;
+            *reinterpret_cast<Piece *>(dst + r * ROWB + (((d >> 3) ^ swz<CH>(r & 15)) * 16) + (d & 7) * 2) = v[i];
+        }
+    };
+    auto store_transposed = [&](const Piece (&v)[PER_T]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+            const int idx = tid + i * 256;
+            const int r = idx / (DKP / VEC), d0 = (idx % (DKP / VEC)) * VEC;
+            uint32_t w[VEC / 2];
+            if constexpr (VEC == 8) { w[0] = v[i].x; w[1] = v[i].y; w[2] = v[i].z; w[3] = v[i].w; }
+            else w[0] = v[i];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int d = d0 + e;
+                *reinterpret_cast<uint16_t *>(sVt + d * VROW + (((r >> 3) ^ (d & 15)) * 16) + (r & 7) * 2) =
+                    (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+    };
+
+    const bool active = q_base + wave * 32 < seq;  // this wave has queries
+    const int qrow = wave * 32 + fr;                // within the block
+    const float scale = 1.0f / sqrtf((float)dk);
+    // scores of key block kb (transposed): register v of tile kt is key kb*128 + kt*32 + 16*(v/8) + 8*fh + v%8
+    auto scores = [&](v16f (&sc)[4], int kb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[kt][v] = 0.0f;
+#pragma unroll
+        for (int ds = 0; ds < DKP / 16; ++ds) {
+            const int c = ds * 2 + fh;
+            const v8h qf = *reinterpret_cast<const v8h *>(sQ + qrow * ROWB + ((c ^ swz<CH>(qrow & 15)) * 16));
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                const int krow = kt * 32 + w_row_perm(fr);
+                const v8h kf = *reinterpret_cast<const v8h *>(sK + krow * ROWB + ((c ^ swz<CH>(krow & 15)) * 16));
+                sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf, sc[kt], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = kb * 128 + kt * 32 + 16 * (v / 8) + 8 * fh + (v % 8);
+                sc[kt][v] = (key < seq) ? sc[kt][v] * scale : -3.0e38f;
+            }
+    };
+
+    Piece ld0[PER_T], ld1[PER_T];
+    load_block(ld0, q_base, 0);
+    load_block(ld1, 0, hidden);
+    store_rows(sQ, ld0);
+    store_rows(sK, ld1);
+    __syncthreads();
+
+    // pass 1: row maximum and denominator (each lane sums its half of the keys; the halves meet at the end)
+    float mx = -3.0e38f, den = 0.0f;
+    for (int kb = 0; kb < key_blocks; ++kb) {
+        if (kb > 0) {
+            load_block(ld1, kb * 128, hidden);
+            __syncthreads();  // every wave is done with the previous block
+            store_rows(sK, ld1);
+            __syncthreads();
+        }
+        if (active) {
+            v16f sc[4];
+            scores(sc, kb);
+            float bm = -3.0e38f;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) bm = fmaxf(bm, sc[kt][v]);
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            const float m_new = fmaxf(mx, bm);
+            float part = 0.0f;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) part += exp2f((sc[kt][v] - m_new) * 1.4426950408889634f);
+            den = den * exp2f((mx - m_new) * 1.4426950408889634f) + part;
+            mx = m_new;
+        }
+    }
+    den += __shfl_xor(den, 32, 64);
+    const float inv = 1.0f / den;
+
+    // pass 2: O^T = V^T P^T over the key blocks
+    constexpr int DT = DKP / 32;
+    v16f ot[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ot[dt][v] = 0.0f;
+    for (int kb = 0; kb < key_blocks; ++kb) {
+        load_block(ld0, kb * 128, 2 * hidden);
+        if (key_blocks > 1) load_block(ld1, kb * 128, hidden);
+        __syncthreads();
+        store_transposed(ld0);
+        if (key_blocks > 1) store_rows(sK, ld1);  // one block: the keys are still there
+        __syncthreads();
+        if (active) {
+            v16f sc[4];
+            scores(sc, kb);
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int st = 0; st < 2; ++st) {
+                    v8h pf;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        pf[e] = (_Float16)(exp2f((sc[kt][8 * st + e] - mx) * 1.4426950408889634f) * inv);
+                    const int kc = (2 * kt + st) * 2 + fh;  // chunk of 8 keys
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const int d = dt * 32 + w_row_perm(fr);
+                        const v8h vf = *reinterpret_cast<const v8h *>(sVt + d * VROW + ((kc ^ (d & 15)) * 16));
+                        ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, ot[dt], 0, 0, 0);
+                    }
+                }
+        }
+    }
+
+    if (q_base + qrow >= seq) return;
+    const int64_t orow = row0 + q_base + qrow;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+            const int d0 = dt * 32 + 16 * G + 8 * fh;
+            if (d0 >= dk) continue;
+            const int nvalid = (dk - d0) < 8 ? (dk - d0) : 8;  // even
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = ot[dt][8 * G + e];
+            const uint32_t h[4] = {pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7])};
+            if (ctx) {
+                uint16_t *dst = ctx + orow * hidden + head * dk + d0;
+                if constexpr (VEC == 8) *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+                else
+                    for (int e = 0; e < nvalid / 2; ++e) reinterpret_cast<uint32_t *>(dst)[e] = h[e];
+            }
+            const int64_t qo = orow * q_pitch + head * dk + d0;  // in codes
+            if (qout && q_bits == 8) {
+                int cd[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
+                const uint2 pk = bytes8(cd);
+                if constexpr (VEC == 8) *reinterpret_cast<uint2 *>(qout + qo) = pk;
+                else
+                    for (int e = 0; e < nvalid; ++e) qout[qo + e] = (uint8_t)((e < 4 ? pk.x : pk.y) >> (8 * (e & 3)));
+            } else if (qout) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
+                if constexpr (VEC == 8) *reinterpret_cast<uint32_t *>(qout + (qo >> 1)) = packed;
+                else
+                    for (int e = 0; e < nvalid / 2; ++e) qout[(qo >> 1) + e] = (uint8_t)(packed >> (8 * e));
+            }
+        }
+}
+
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 }  // namespace mkq
@@ -381,24 +598,48 @@ extern "C" int mkq_layernorm_int8(const void *x, int64_t M, int64_t D, const flo
     return layernorm_run(x, M, D, gamma, beta, eps, y, s_next, q_out, 8, stream);
 }
 
-// cu: null (every sequence has seq rows, a multiple of 32) or device array [batch + 1] of row offsets
-// (then seq is only an upper bound of the lengths)
+// Longest sequence the attention kernels take (the key loop has no limit of its own; this bounds the grid).
+constexpr int64_t ATTENTION_MAX_SEQ = 4096;
+
+// cu: null (every sequence has seq rows) or device array [batch + 1] of row offsets (then seq is only an
+// upper bound of the lengths).  q_pitch: codes per row of q_out (0: hidden).
 static int attention_run(const void *qkv, int64_t batch, int64_t seq, int64_t hidden, int64_t heads, void *ctx,
-                         float s_next, void *q_out_v, int q_bits, void *stream, const int32_t *cu = nullptr)
+                         float s_next, void *q_out_v, int q_bits, void *stream, const int32_t *cu = nullptr,
+                         int64_t q_pitch = 0)
 {
     uint8_t *q_out = (uint8_t *)q_out_v;
-    if (cu && seq > 0) seq = ceil_div(seq, 32) * 32;
     if (batch < 0 || seq <= 0 || hidden <= 0 || heads <= 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
+    if (q_pitch == 0) q_pitch = hidden;
+    if (q_pitch < hidden || (q_pitch % 8) != 0) return MKQ_ERR_SHAPE;
     if (q_out && !scale_ok(s_next)) return MKQ_ERR_SCALE;
-    if (hidden / heads != 64 || (seq % 32) != 0 || seq > 128 || batch * heads > 0x7FFFFFFF)
+    const int64_t dk = hidden / heads;
+    const int64_t q_blocks = ceil_div(seq, 128);
+    if (dk > 64 || (dk % 2) != 0 || (hidden % 8) != 0 || seq > ATTENTION_MAX_SEQ ||
+        batch * heads * q_blocks > 0x7FFFFFFF)
         return MKQ_ERR_UNSUPPORTED;
     if (batch == 0) return MKQ_OK;
     if (!qkv || (!ctx && !q_out)) return MKQ_ERR_NULL;
     if (!aligned16(qkv) || (ctx && !aligned16(ctx)) || (q_out && !aligned16(q_out))) return MKQ_ERR_ALIGN;
-    const unsigned grid = (unsigned)(batch * heads);
     hipStream_t st = as_stream(stream);
     const uint16_t *in = (const uint16_t *)qkv;
-    switch (seq / 32) {
+    if (dk != 64 || seq > 128 || q_pitch != hidden) {
+        const unsigned grid = (unsigned)(batch * heads * q_blocks);
+#define MKQ_ATT(DKP, VEC)                                                                                        \
+    attention_blocks_kernel<DKP, VEC><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (int)dk,     \
+                                                            (int)q_blocks, (uint16_t *)ctx, s_next, q_out, q_bits, \
+                                                            (int)q_pitch, cu)
+        if ((dk % 8) == 0) {
+            if (dk <= 32) MKQ_ATT(32, 8);
+            else MKQ_ATT(64, 8);
+        } else {
+            if (dk <= 32) MKQ_ATT(32, 2);
+            else MKQ_ATT(64, 2);
+        }
+#undef MKQ_ATT
+        return launch_status();
+    }
+    const unsigned grid = (unsigned)(batch * heads);
+    switch (ceil_div(seq, 32)) {
     case 1: attention_kernel<1><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits, cu); break;
     case 2: attention_kernel<2><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits, cu); break;
     case 3: attention_kernel<3><<<grid, 256, 0, st>>>(in, (int)seq, (int)hidden, (int)heads, (uint16_t *)ctx, s_next, q_out, q_bits, cu); break;

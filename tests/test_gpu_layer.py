@@ -66,6 +66,63 @@ def test_attention(mkq, B, S, heads):
     assert np.abs(to_np(ctx1).astype(np.float32) - 1.0).max() < 2e-3
 
 
+# head sizes other than 64 (the 4-layer student: 312 / 12 = 26) and sequences longer than one key block
+@pytest.mark.parametrize("B,S,heads,dk", [(2, 512, 16, 64), (1, 512, 12, 26), (3, 200, 12, 26), (2, 128, 12, 26),
+                                          (2, 130, 4, 32), (2, 77, 2, 48), (1, 129, 1, 64), (2, 384, 3, 64),
+                                          (1, 40, 4, 2), (1, 300, 4, 62)])
+def test_attention_any_head_size_and_length(mkq, B, S, heads, dk):
+    H = heads * dk
+    rng = np.random.default_rng(S + heads + dk)
+    qkv = _f16(rng.normal(0, 1.0, (B * S, 3 * H)))
+    s_next = 0.05
+    ctx, q = mkq.mkq_attention(to_dev(qkv), B, S, H, heads, s_next=s_next, want_q=True)
+    ref = oracle.attention(qkv.astype(np.float32), B, S, H, heads, p_dtype=oracle.F16)
+    assert_float_close(to_np(ctx).astype(np.float32), ref, RTOL[1], "attention")
+    got = oracle.unpack_nibbles(to_np(q), H)
+    for b in range(B):
+        rows = slice(b * S, (b + 1) * S)
+        codes_match(got[rows], oracle.quantize(ref[rows], s_next), ref[rows], s_next,
+                    attention_code_band(qkv[rows].astype(np.float32), S, H, heads, s_next), "attention codes")
+    ctx8, q8 = mkq.mkq_attention_int8(to_dev(qkv), B, S, H, heads, s_next=s_next / 16)
+    assert np.array_equal(to_np(ctx8), to_np(ctx))
+    for b in range(B):
+        rows = slice(b * S, (b + 1) * S)
+        codes_match(to_np(q8)[rows], oracle.quantize(ref[rows], s_next / 16, qmin=-128, qmax=127), ref[rows],
+                    s_next / 16, attention_code_band(qkv[rows].astype(np.float32), S, H, heads, s_next / 16),
+                    "attention codes, 8 bits")
+    # a sharply peaked softmax (one key far above the rest) and the probabilities summing to one
+    peaked = qkv.copy()
+    peaked[:, :2 * H] *= 6.0
+    ctxp, _ = mkq.mkq_attention(to_dev(peaked), B, S, H, heads)
+    assert_float_close(to_np(ctxp).astype(np.float32),
+                       oracle.attention(peaked.astype(np.float32), B, S, H, heads, p_dtype=oracle.F16), RTOL[1], "peaked")
+    ones = qkv.copy()
+    ones[:, 2 * H:] = 1.0
+    ctx1, _ = mkq.mkq_attention(to_dev(ones), B, S, H, heads)
+    assert np.abs(to_np(ctx1).astype(np.float32) - 1.0).max() < 4e-3
+
+
+@pytest.mark.parametrize("batch,total,max_seq,heads,dk", [(5, 2300, 512, 4, 64), (5, 700, 300, 12, 26),
+                                                          (4, 9, 512, 2, 64), (3, 520, 512, 2, 32)])
+def test_attention_over_long_ragged_sequences(mkq, batch, total, max_seq, heads, dk):
+    H = heads * dk
+    lens = _lengths(total, batch, max_seq, seed=total)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rng = np.random.default_rng(total + heads)
+    qkv = _f16(rng.normal(0, 1.0, (total, 3 * H)))
+    s_next = 0.05
+    ctx, q = mkq.mkq_attention_varlen(to_dev(qkv), to_dev(cu), max_seq, H, heads, s_next=s_next, q_bits=4)
+    got, codes = to_np(ctx).astype(np.float32), oracle.unpack_nibbles(to_np(q), H)
+    for b in range(batch):
+        rows = slice(cu[b], cu[b + 1])
+        if lens[b] == 0:
+            continue
+        ref = oracle.attention(qkv[rows].astype(np.float32), 1, int(lens[b]), H, heads, p_dtype=oracle.F16)
+        assert_float_close(got[rows], ref, RTOL[1], f"sequence {b} of length {lens[b]}")
+        codes_match(codes[rows], oracle.quantize(ref, s_next), ref, s_next,
+                    attention_code_band(qkv[rows].astype(np.float32), int(lens[b]), H, heads, s_next), "context codes")
+
+
 @pytest.mark.parametrize("M,N,K", [(128, 768, 768), (200, 328, 192), (1024, 2304, 768), (77, 64, 3072)])
 @pytest.mark.parametrize("variant", ["plain", "gelu", "residual_f32out"])
 def test_linear_fp16_baseline(mkq, M, N, K, variant):
