@@ -139,6 +139,10 @@ typedef struct mkq_epilogue {
     void *splitk_scratch; /* NULL, or a scratch area prepared by mkq_splitk_scratch_init (see there): lets a
                              linear with few tokens split K across workgroups to fill the chip */
     size_t splitk_scratch_bytes;
+    int64_t q_pitch;      /* codes per row of the code outputs (`out` of MKQ_I4 / MKQ_I8, q_out); 0 = N.  A
+                             consumer whose reduction length is padded (mkq_padded_k) takes rows of that
+                             many codes: give the padded length here and clear the buffer once -- the
+                             columns from N on are never written.  Otherwise >= N and a multiple of 8. */
 } mkq_epilogue;
 
 /* Scratch of a K split across workgroups.  Few tokens against a weight matrix with few output channels
@@ -329,8 +333,13 @@ int mkq_bert_layer_workspace(const mkq_bert_layer_params *p_host,
  *   q_in   NULL, or packed codes of h_in under sx_qkv (skips the first quantizer)
  *   h_out  [M, hidden] binary16
  *   q_out_next  [M, hidden/2] bytes (or [M, hidden] when next_bits == 8), required iff s_out_next > 0
- * hidden % 64 == 0, ffn % 64 == 0, hidden % heads == 0; currently d_k == 64, seq % 32 == 0 and
- * seq <= 128 (anything else: UNSUPPORTED).
+ * hidden % 8 == 0, ffn % 8 == 0, hidden % heads == 0 (else SHAPE); d_k = hidden / heads even and <= 64,
+ * seq <= 4096, hidden <= 8192 (else UNSUPPORTED).
+ * A hidden or FFN size that is no multiple of 32 (the 4-layer student of section 5.2: 312 and 1200) is
+ * carried padded: every 4-bit code buffer whose rows feed a linear of that reduction length -- q_in,
+ * q_out_next, the workspace's c0..c3 -- has rows of mkq_padded_k(size) / 2 bytes with zero codes past the
+ * real columns (the layer clears and fills them itself), and the weights come from
+ * mkq_pack_weights_int4_padded.  Sizes that are a multiple of 32 are stored as they are.
  * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, WORKSPACE, UNSUPPORTED, HIP. */
 int mkq_bert_layer_int4(const mkq_bert_layer_params *p_host, const void *h_in, int h_dtype,
                         const uint8_t *q_in, void *h_out, uint8_t *q_out_next, void *workspace,
@@ -357,7 +366,7 @@ int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *p_host, const void *h_
  * Wq_* = int8 codes [N, K] from mkq_pack_weights_int8 and sx_* the steps of the 8-bit
  * range; every code buffer (q_in, q_out_next, the c* intermediates) holds one byte per
  * code, so the workspace layout has c0, c1, c2 of M*hidden bytes and c3 of M*ffn bytes.
- * Same shape limits and errors as mkq_bert_layer_int4. */
+ * Shape limits and errors of mkq_bert_layer_int4, but hidden % 64 == 0 and ffn % 64 == 0 (no padding). */
 int mkq_bert_layer_int8_workspace(const mkq_bert_layer_params *p_host,
                                   mkq_bert_layer_workspace_layout *layout_host);
 int mkq_bert_layer_int8(const mkq_bert_layer_params *p_host, const void *h_in, int h_dtype,

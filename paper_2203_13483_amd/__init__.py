@@ -46,7 +46,7 @@ class MkqError(RuntimeError):
 class Epilogue(C.Structure):
     _fields_ = [("act", C.c_int), ("residual", C.c_void_p), ("residual_dtype", C.c_int),
                 ("s_next", C.c_float), ("q_out", C.c_void_p), ("acc_out", C.c_void_p),
-                ("splitk_scratch", C.c_void_p), ("splitk_scratch_bytes", C.c_size_t)]
+                ("splitk_scratch", C.c_void_p), ("splitk_scratch_bytes", C.c_size_t), ("q_pitch", C.c_int64)]
 
 
 class BertLayerParams(C.Structure):
@@ -326,14 +326,15 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
                     s_next: float = 0.0, want_q: bool = False, want_acc: bool = False,
                     out=None, workspace=None, stream=None, splitk_scratch=None,
                     config: int | None = None, k_slices: int = 0, w_stream: bool = False,
-                    prefetch_stages: int = 0):
+                    prefetch_stages: int = 0, q_pitch: int = 0):
     """The quantized linear.  ``a`` is packed codes (uint8 [M,K/2]) or float [M,K].
 
     Returns a dict with ``out`` (float tensor, or uint8 [M,N/2] for MKQ_I4) and
     optionally ``q`` (packed codes under s_next) and ``acc`` (int32 [M,N]).
     ``config`` / ``k_slices`` call mkq_tuning_linear_int4 (the kernel configuration chosen by the caller).
     ``w_stream``: Wq is in the streaming layout (mkq_linear_int4_stream; ``prefetch_stages`` / ``k_slices``
-    call its tuning variant).
+    call its tuning variant).  ``q_pitch``: codes per row of the code outputs (0 = N); the buffers are zeroed
+    when it is given, since the columns from N on are not written.
     """
     torch = _torch()
     if a_is_codes is None:
@@ -341,10 +342,11 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
     M = a.shape[0]
     a_dtype = MKQ_I4 if a_is_codes else _dtype_code(a)
     dev = a.device
+    code_cols = (int(q_pitch) or N) // 2
     if out is None:
-        out = (torch.empty((M, N // 2), dtype=torch.uint8, device=dev) if out_dtype == MKQ_I4
+        out = (torch.zeros((M, code_cols), dtype=torch.uint8, device=dev) if out_dtype == MKQ_I4
                else torch.empty((M, N), dtype=_torch_dtype(out_dtype), device=dev))
-    q = torch.empty((M, N // 2), dtype=torch.uint8, device=dev) if want_q else None
+    q = torch.zeros((M, code_cols), dtype=torch.uint8, device=dev) if want_q else None
     acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
     epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
                    residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
@@ -352,7 +354,7 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
                    acc_out=acc.data_ptr() if acc is not None else None,
                    splitk_scratch=splitk_scratch.data_ptr() if splitk_scratch is not None else None,
                    splitk_scratch_bytes=(splitk_scratch.numel() * splitk_scratch.element_size()
-                                         if splitk_scratch is not None else 0))
+                                         if splitk_scratch is not None else 0), q_pitch=int(q_pitch))
     need = mkq_linear_int4_workspace_bytes(M, N, K, a_dtype)
     if need and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)

@@ -1351,6 +1351,8 @@ static int linear_int4_run(const void *a, int a_dtype, float s_x, const uint8_t 
     const bool writes_codes = (out && out_dtype == MKQ_I4) || want_q;
     if (M < 0 || N <= 0 || K <= 0 || (K % 32) != 0) return MKQ_ERR_SHAPE;
     if (writes_codes && (N % 2) != 0) return MKQ_ERR_SHAPE;
+    const int64_t q_pitch = epi ? epi->q_pitch : 0;
+    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF)) return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
     if (writes_codes && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
     if (M == 0) return MKQ_OK;  // empty batch: pointers may be NULL
@@ -1382,6 +1384,7 @@ static int linear_int4_run(const void *a, int a_dtype, float s_x, const uint8_t 
     p.s_next = epi ? epi->s_next : 1.0f;
     p.q_out = (epi && !(out && out_dtype == MKQ_I4)) ? epi->q_out : nullptr;
     p.acc_out = epi ? epi->acc_out : nullptr;
+    p.q_pitch = (int)q_pitch;
     p.acc_shift = 8;
     p.acc_unit = 0.00390625f;
     // the kernel that will run is set up (and a forced configuration that does not apply is refused)
@@ -1593,6 +1596,8 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
             return MKQ_ERR_DTYPE;
     }
     if (M < 0 || N <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
+    const int64_t q_pitch = epi ? epi->q_pitch : 0;
+    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF)) return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
     if (out && out_dtype == MKQ_I8 && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
     if (M == 0) return MKQ_OK;
@@ -1617,6 +1622,7 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
     p.s_next = (epi && out_dtype == MKQ_I8) ? epi->s_next : 1.0f;
     p.q_out = nullptr;
     p.acc_out = epi ? epi->acc_out : nullptr;
+    p.q_pitch = (int)q_pitch;
     p.acc_shift = 0;   // byte operands enter the MFMA as they are
     p.acc_unit = 1.0f;
     return run_gemm_i8(p, as_stream(stream));
@@ -1638,6 +1644,8 @@ static int linear_int4_e3m2_run(const uint8_t *a, float s_x, const uint8_t *Wq, 
     const bool writes_codes = (out && out_dtype == MKQ_I4) || want_q;
     if (M < 0 || N <= 0 || K <= 0 || (K % 128) != 0) return MKQ_ERR_SHAPE;
     if (writes_codes && (N % 2) != 0) return MKQ_ERR_SHAPE;
+    const int64_t q_pitch = epi ? epi->q_pitch : 0;
+    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF)) return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
     if (writes_codes && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
     if (M == 0) return MKQ_OK;
@@ -1662,6 +1670,7 @@ static int linear_int4_e3m2_run(const uint8_t *a, float s_x, const uint8_t *Wq, 
     p.s_next = epi ? epi->s_next : 1.0f;
     p.q_out = (epi && !(out && out_dtype == MKQ_I4)) ? epi->q_out : nullptr;
     p.acc_out = epi ? epi->acc_out : nullptr;
+    p.q_pitch = (int)q_pitch;
     p.acc_shift = 0;
     p.acc_unit = 1.0f;
     return run_gemm_e3m2(p, as_stream(stream), forced_cfg);

@@ -21,6 +21,7 @@ struct GemmI4Params {
     float s_next;
     uint8_t *q_out;     // extra packed codes, or null
     int32_t *acc_out;   // raw accumulators, or null
+    int q_pitch = 0;    // codes per row of the code outputs (out of MKQ_I4 / MKQ_I8, q_out); 0 = N
     // What the int32 accumulator holds: 2^acc_shift * sum(a*w).  The 4-bit path feeds the
     // matrix core 16*code on both sides (shift 8); the 8-bit path feeds the codes themselves.
     int acc_shift;
@@ -145,6 +146,7 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                 const int m = m0 + wm * Cfg::WTM + j * 32 + fr;
                 if (m >= p.M) return;
                 const int64_t o = (int64_t)m * p.N + nb;
+                const int64_t oq = p.q_pitch ? (int64_t)m * p.q_pitch + nb : o;  // in the code outputs
                 int a[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] = acc[j][t][8 * G + e];
@@ -223,7 +225,7 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                     int cd[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) cd[e] = quantize_code8(y[e], p.s_next);
-                    uint8_t *qdst = (uint8_t *)p.out + o;
+                    uint8_t *qdst = (uint8_t *)p.out + oq;
                     if (vec_ok) {
                         *reinterpret_cast<uint2 *>(qdst) = bytes8(cd);
                     } else {
@@ -231,12 +233,12 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                     }
                 }
                 if (out_dtype == MKQ_I4 || q_extra) {
-                    // Eq. 1 on the binary32 value.  N is even and nb % 8 == 0, so o is even.
+                    // Eq. 1 on the binary32 value.  The pitch is even and nb % 8 == 0, so oq is even.
                     uint32_t packed = 0;
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
                         packed |= ((uint32_t)quantize_code(y[e], p.s_next) & 0xFu) << (4 * e);
-                    uint8_t *qdst = (out_dtype == MKQ_I4 ? (uint8_t *)p.out : q_extra) + (o >> 1);
+                    uint8_t *qdst = (out_dtype == MKQ_I4 ? (uint8_t *)p.out : q_extra) + (oq >> 1);
                     if (vec_ok) {
                         *reinterpret_cast<uint32_t *>(qdst) = packed;
                     } else {
@@ -491,7 +493,7 @@ enum { EPI_F16 = 0, EPI_BF16, EPI_F32, EPI_F16_RES16, EPI_I4_GELU, EPI_I4, EPI_I
 
 inline int classify_epilogue(const GemmI4Params &p)
 {
-    if ((p.N % 8) != 0 || p.acc_out || p.q_out) return EPI_GENERIC;
+    if ((p.N % 8) != 0 || p.acc_out || p.q_out || (p.q_pitch && p.q_pitch != p.N)) return EPI_GENERIC;
     const bool res16 = p.residual && p.residual_dtype == MKQ_F16;
     const bool gelu = p.act == MKQ_ACT_GELU;
     if (p.residual && !res16) return EPI_GENERIC;

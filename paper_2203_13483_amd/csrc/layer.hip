@@ -17,7 +17,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
                                                         const float *__restrict__ gamma,
                                                         const float *__restrict__ beta, float eps,
                                                         uint16_t *__restrict__ y, float s_next,
-                                                        uint32_t *__restrict__ q, int q_bits)
+                                                        uint32_t *__restrict__ q, int q_bits, int q_chunks)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -73,12 +73,12 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
                 int cd[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
-                reinterpret_cast<uint2 *>(q)[(int64_t)row * chunks + c] = bytes8(cd);
+                reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = bytes8(cd);
             } else if (q) {
                 uint32_t packed = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
-                q[(int64_t)row * chunks + c] = packed;
+                q[(int64_t)row * q_chunks + c] = packed;
             }
         }
     }
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void layernorm_half_kernel(const uint16_t *__r
                                                              const float *__restrict__ gamma,
                                                              const float *__restrict__ beta, float eps,
                                                              uint16_t *__restrict__ y, float s_next,
-                                                             uint32_t *__restrict__ q, int q_bits)
+                                                             uint32_t *__restrict__ q, int q_bits, int q_chunks)
 {
     const int lane = threadIdx.x & 31;
     const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
@@ -163,12 +163,12 @@ __global__ __launch_bounds__(256) void layernorm_half_kernel(const uint16_t *__r
                 int cd[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
-                reinterpret_cast<uint2 *>(q)[(int64_t)row * chunks + c] = bytes8(cd);
+                reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = bytes8(cd);
             } else if (q) {
                 uint32_t packed = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
-                q[(int64_t)row * chunks + c] = packed;
+                q[(int64_t)row * q_chunks + c] = packed;
             }
         }
     }
@@ -550,10 +550,14 @@ static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 using namespace mkq;
 
+// q_pitch: codes per row of q_out (0: D)
 static int layernorm_run(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta, float eps,
-                         void *y, float s_next, void *q_out, int q_bits, void *stream)
+                         void *y, float s_next, void *q_out, int q_bits, void *stream, int64_t q_pitch = 0)
 {
     if (M < 0 || D <= 0 || (D % 8) != 0) return MKQ_ERR_SHAPE;
+    if (q_pitch == 0) q_pitch = D;
+    if (q_pitch < D || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF) return MKQ_ERR_SHAPE;
+    const int q_chunks = (int)(q_pitch / 8);
     if (D > 8192) return MKQ_ERR_UNSUPPORTED;
     if (q_out && !scale_ok(s_next)) return MKQ_ERR_SCALE;
     if (!(eps >= 0.0f)) return MKQ_ERR_SCALE;
@@ -567,12 +571,12 @@ static int layernorm_run(const void *x, int64_t M, int64_t D, const float *gamma
     hipStream_t st = as_stream(stream);
 #define MKQ_LN(C)                                                                                       \
     layernorm_kernel<C><<<grid, 256, 0, st>>>((const uint16_t *)x, (int)M, (int)D, gamma, beta, eps, \
-                                              (uint16_t *)y, s_next, (uint32_t *)q_out, q_bits)
+                                              (uint16_t *)y, s_next, (uint32_t *)q_out, q_bits, q_chunks)
     if (D <= 1024 && M >= 2048) {
         const unsigned grid8 = (unsigned)ceil_div(M, 8);
 #define MKQ_LNH(C)                                                                                             \
     layernorm_half_kernel<C><<<grid8, 256, 0, st>>>((const uint16_t *)x, (int)M, (int)D, gamma, beta, eps, \
-                                                    (uint16_t *)y, s_next, (uint32_t *)q_out, q_bits)
+                                                    (uint16_t *)y, s_next, (uint32_t *)q_out, q_bits, q_chunks)
         if (D <= 256) MKQ_LNH(1);
         else if (D <= 512) MKQ_LNH(2);
         else if (D <= 768) MKQ_LNH(3);
@@ -671,15 +675,39 @@ extern "C" int mkq_attention_varlen(const void *qkv, const int32_t *cu_seqlens, 
 }
 
 // ---------------------------------------------------------------------------------
-// varlen: seq is an upper bound of the sequence lengths of a padding-free batch of `tokens` rows
-static int check_layer_dims(int64_t batch, int64_t seq, int64_t hidden, int64_t heads, int64_t ffn,
+// varlen: seq is an upper bound of the sequence lengths of a padding-free batch of `tokens` rows.
+// bits: 4, 8, or 16 for the binary16 baseline.  Only the 4-bit layer pads reduction lengths.
+static int check_layer_dims(int bits, int64_t batch, int64_t seq, int64_t hidden, int64_t heads, int64_t ffn,
                             bool varlen = false, int64_t tokens = 0)
 {
     if (batch < 0 || seq <= 0 || hidden <= 0 || heads <= 0 || ffn <= 0) return MKQ_ERR_SHAPE;
-    if ((hidden % 64) != 0 || (ffn % 64) != 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
+    const int64_t unit = bits == 4 ? 8 : 64;
+    if ((hidden % unit) != 0 || (ffn % unit) != 0 || (hidden % heads) != 0) return MKQ_ERR_SHAPE;
     if (varlen && (tokens < 0 || tokens > batch * seq)) return MKQ_ERR_SHAPE;
-    if (hidden / heads != 64 || (!varlen && (seq % 32) != 0) || seq > 128 || hidden > 8192) return MKQ_ERR_UNSUPPORTED;
+    const int64_t dk = hidden / heads;
+    if (dk > 64 || (dk % 2) != 0 || seq > ATTENTION_MAX_SEQ || hidden > 8192) return MKQ_ERR_UNSUPPORTED;
     return MKQ_OK;
+}
+
+// Codes per row of a buffer that feeds a linear of reduction length K: the 4-bit linear takes K % 32 == 0,
+// other lengths are padded with zero codes.
+static inline int64_t code_row(int bits, int64_t K)
+{
+    return (bits == 4 && (K % 32) != 0) ? mkq_padded_k(K) : K;
+}
+
+__global__ void clear16_kernel(uint4 *__restrict__ p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+static int clear_bytes(void *p, size_t bytes, hipStream_t st)  // bytes % 16 == 0
+{
+    const int64_t n = (int64_t)(bytes / 16);
+    if (n == 0) return MKQ_OK;
+    clear16_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>((uint4 *)p, n);
+    return launch_status();
 }
 
 template <class P>
@@ -692,19 +720,20 @@ static inline int64_t layer_tokens(const P *p)
 static int layer_workspace(const mkq_bert_layer_params *p, mkq_bert_layer_workspace_layout *L, int bits)
 {
     if (!p || !L) return MKQ_ERR_NULL;
-    const int rc = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
+    const int rc = check_layer_dims(bits, p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
                                     p->total_tokens);
     if (rc != MKQ_OK) return rc;
-    const size_t M = (size_t)layer_tokens(p), H = (size_t)p->hidden, F = (size_t)p->ffn;
+    const size_t M = (size_t)layer_tokens(p), H = (size_t)p->hidden;
+    const size_t Hp = (size_t)code_row(bits, p->hidden), Fp = (size_t)code_row(bits, p->ffn);
     const size_t cpb = bits == 4 ? 2 : 1;  // codes per byte
     size_t o = 0;
-    L->c0 = o;  o += align256(M * H / cpb);
+    L->c0 = o;  o += align256(M * Hp / cpb);
     L->qkv = o; o += align256(M * 3 * H * 2);
-    L->c1 = o;  o += align256(M * H / cpb);
+    L->c1 = o;  o += align256(M * Hp / cpb);
     L->u = o;   o += align256(M * H * 2);
     L->h1 = o;  o += align256(M * H * 2);
-    L->c2 = o;  o += align256(M * H / cpb);
-    L->c3 = o;  o += align256(M * F / cpb);
+    L->c2 = o;  o += align256(M * Hp / cpb);
+    L->c3 = o;  o += align256(M * Fp / cpb);
     L->d = o;   o += align256(M * H * 2);
     L->total = o;
     return MKQ_OK;
@@ -762,42 +791,63 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
     if (!workspace || workspace_bytes < L.total || !aligned16(workspace)) return MKQ_ERR_WORKSPACE;
 
     const int64_t M = layer_tokens(p), H = p->hidden, F = p->ffn;
+    // rows of the code buffers: hidden / ffn, padded where the 4-bit linear that reads them needs it
+    const int64_t Hp = code_row(bits, H), Fp = code_row(bits, F);
+    const int64_t next_pitch = want_next ? code_row(next_bits, H) : H;
+    if (next_bits == 8 && (H % 64) != 0) return MKQ_ERR_SHAPE;  // the 8-bit layer that would read them
     const int code_dtype = bits == 8 ? MKQ_I8 : MKQ_I4;
     uint8_t *ws = (uint8_t *)workspace;
+    hipStream_t st = as_stream(stream);
+    // the writers of codes leave padding columns alone: they are zero from here on
+    if (Hp != H) {
+        rc = clear_bytes(ws + L.c1, align256((size_t)(M * Hp / 2)), st);
+        if (rc == MKQ_OK) rc = clear_bytes(ws + L.c2, align256((size_t)(M * Hp / 2)), st);
+        if (rc != MKQ_OK) return rc;
+    }
+    if (Fp != F) {
+        rc = clear_bytes(ws + L.c3, align256((size_t)(M * Fp / 2)), st);
+        if (rc != MKQ_OK) return rc;
+    }
+    if (want_next && next_pitch != H) {
+        rc = clear_bytes(q_out_next, (size_t)(M * next_pitch / 2), st);  // rows of a multiple of 64 bytes
+        if (rc != MKQ_OK) return rc;
+    }
     const uint8_t *c0 = q_in;
     if (!c0) {
-        rc = bits == 8 ? mkq_quantize_int8(h_in, h_dtype, M, H, H, p->sx_qkv, (int8_t *)(ws + L.c0), stream)
+        rc = bits == 8   ? mkq_quantize_int8(h_in, h_dtype, M, H, H, p->sx_qkv, (int8_t *)(ws + L.c0), stream)
+             : Hp != H ? mkq_quantize_padded(h_in, h_dtype, M, H, H, p->sx_qkv, ws + L.c0, stream)
                        : mkq_quantize(h_in, h_dtype, M, H, H, p->sx_qkv, ws + L.c0, stream);
         if (rc != MKQ_OK) return rc;
         c0 = ws + L.c0;
     }
     // q | k | v
-    rc = layer_linear(bits, c0, p->sx_qkv, p->Wq_qkv, p->sw_qkv, p->b_qkv, M, 3 * H, H, ws + L.qkv, MKQ_F16,
+    rc = layer_linear(bits, c0, p->sx_qkv, p->Wq_qkv, p->sw_qkv, p->b_qkv, M, 3 * H, Hp, ws + L.qkv, MKQ_F16,
                       nullptr, stream);
     if (rc != MKQ_OK) return rc;
     // attention context, re-quantized for the output projection
     rc = attention_run(ws + L.qkv, p->batch, p->seq, H, p->heads, nullptr, p->sx_ao, ws + L.c1, bits, stream,
-                       p->cu_seqlens);
+                       p->cu_seqlens, Hp);
     if (rc != MKQ_OK) return rc;
     mkq_epilogue e = {};
     e.act = MKQ_ACT_NONE; e.residual = h_in; e.residual_dtype = h_dtype; e.s_next = 0.0f;
     e.q_out = nullptr; e.acc_out = nullptr;
-    rc = layer_linear(bits, ws + L.c1, p->sx_ao, p->Wq_ao, p->sw_ao, p->b_ao, M, H, H, ws + L.u, MKQ_F16, &e, stream);
+    rc = layer_linear(bits, ws + L.c1, p->sx_ao, p->Wq_ao, p->sw_ao, p->b_ao, M, H, Hp, ws + L.u, MKQ_F16, &e, stream);
     if (rc != MKQ_OK) return rc;
     rc = layernorm_run(ws + L.u, M, H, p->ln1_gamma, p->ln1_beta, p->ln_eps, ws + L.h1, p->sx_up, ws + L.c2, bits,
-                       stream);
+                       stream, Hp);
     if (rc != MKQ_OK) return rc;
     // FFN up: GELU and re-quantization fused, only codes leave the kernel
-    e.act = MKQ_ACT_GELU; e.residual = nullptr; e.s_next = p->sx_down;
-    rc = layer_linear(bits, ws + L.c2, p->sx_up, p->Wq_up, p->sw_up, p->b_up, M, F, H, ws + L.c3, code_dtype, &e,
+    e.act = MKQ_ACT_GELU; e.residual = nullptr; e.s_next = p->sx_down; e.q_pitch = Fp != F ? Fp : 0;
+    rc = layer_linear(bits, ws + L.c2, p->sx_up, p->Wq_up, p->sw_up, p->b_up, M, F, Hp, ws + L.c3, code_dtype, &e,
                       stream);
     if (rc != MKQ_OK) return rc;
-    e.act = MKQ_ACT_NONE; e.residual = ws + L.h1; e.residual_dtype = MKQ_F16; e.s_next = 0.0f;
-    rc = layer_linear(bits, ws + L.c3, p->sx_down, p->Wq_down, p->sw_down, p->b_down, M, H, F, ws + L.d, MKQ_F16, &e,
+    e.act = MKQ_ACT_NONE; e.residual = ws + L.h1; e.residual_dtype = MKQ_F16; e.s_next = 0.0f; e.q_pitch = 0;
+    rc = layer_linear(bits, ws + L.c3, p->sx_down, p->Wq_down, p->sw_down, p->b_down, M, H, Fp, ws + L.d, MKQ_F16, &e,
                       stream);
     if (rc != MKQ_OK) return rc;
     return layernorm_run(ws + L.d, M, H, p->ln2_gamma, p->ln2_beta, p->ln_eps, h_out,
-                         want_next ? p->s_out_next : 1.0f, want_next ? q_out_next : nullptr, next_bits, stream);
+                         want_next ? p->s_out_next : 1.0f, want_next ? q_out_next : nullptr, next_bits, stream,
+                         next_pitch);
 }
 
 extern "C" int mkq_bert_layer_int4(const mkq_bert_layer_params *p, const void *h_in, int h_dtype,
@@ -817,7 +867,7 @@ extern "C" int mkq_bert_layer_int8(const mkq_bert_layer_params *p, const void *h
 
 extern "C" size_t mkq_bert_layer_fp16_workspace_bytes(const mkq_bert_layer_params_fp16 *p)
 {
-    if (!p || check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
+    if (!p || check_layer_dims(16, p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
                                p->total_tokens) != MKQ_OK)
         return 0;
     const size_t M = (size_t)layer_tokens(p), H = (size_t)p->hidden, F = (size_t)p->ffn;
@@ -828,7 +878,7 @@ extern "C" int mkq_bert_layer_fp16(const mkq_bert_layer_params_fp16 *p, const vo
                                    void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!p) return MKQ_ERR_NULL;
-    const int rc0 = check_layer_dims(p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
+    const int rc0 = check_layer_dims(16, p->batch, p->seq, p->hidden, p->heads, p->ffn, p->cu_seqlens != nullptr,
                                      p->total_tokens);
     if (rc0 != MKQ_OK) return rc0;
     if (p->batch == 0 || layer_tokens(p) == 0) return MKQ_OK;

@@ -46,6 +46,12 @@ def codes_match(got, want, pre_round, step, band, what):
                                             max_frac=float(inside.mean()) + 1e-4, what=what)
 
 
+def code_row_pitch(cols):
+    """Codes per row of a 4-bit code buffer of the layer: rows whose length is no multiple of 32 are stored
+    padded with zero codes to the next multiple of 128."""
+    return cols if cols % 32 == 0 else (cols + 127) // 128 * 128
+
+
 class LayerBuffers:
     """The layer's workspace and outputs as numpy arrays (read back once)."""
 
@@ -56,7 +62,10 @@ class LayerBuffers:
     def codes(self, off, cols):
         if self.bits == 8:
             return self.ws[off: off + self.M * cols].view(np.int8).reshape(self.M, cols)
-        return oracle.unpack_nibbles(self.ws[off: off + self.M * cols // 2], cols)
+        pitch = code_row_pitch(cols)
+        rows = oracle.unpack_nibbles(self.ws[off: off + self.M * pitch // 2], pitch)
+        assert not rows[:, cols:].any(), "padding codes must be zero"
+        return rows[:, :cols]
 
     def f16(self, off, cols):
         return self.ws[off: off + self.M * cols * 2].view(np.float16).reshape(self.M, cols).astype(np.float32)

@@ -177,21 +177,35 @@ def test_int8_argument_errors(lib):
     assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L4)) == mkq.MKQ_OK
     assert lib.mkq_bert_layer_int8_workspace(C.byref(lay), C.byref(L8)) == mkq.MKQ_OK
     assert L8.qkv - L8.c0 == 2 * (L4.qkv - L4.c0) and L8.total > L4.total
-    lay.seq = 160
+    lay.seq = 5000                                                                    # longest sequence: 4096
     assert lib.mkq_bert_layer_int8_workspace(C.byref(lay), C.byref(L8)) == mkq.MKQ_ERR_UNSUPPORTED
+    lay.seq, lay.heads = 160, 1                                                       # d_k = 128
+    assert lib.mkq_bert_layer_int8_workspace(C.byref(lay), C.byref(L8)) == mkq.MKQ_ERR_UNSUPPORTED
+    # the student's sizes (312 = 12 heads of 26, FFN 1200): padded code rows at 4 bits, refused at 8
+    lay.seq, lay.hidden, lay.heads, lay.ffn = 128, 312, 12, 1200
+    assert lib.mkq_bert_layer_int8_workspace(C.byref(lay), C.byref(L8)) == mkq.MKQ_ERR_SHAPE
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L4)) == mkq.MKQ_OK
+    assert L4.qkv - L4.c0 == 256 * 384 // 2 and L4.d - L4.c3 == 256 * 1280 // 2        # rows of padded_k codes
+    lay.heads = 8                                                                     # d_k = 39 is odd
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L4)) == mkq.MKQ_ERR_UNSUPPORTED
+    lay.hidden, lay.heads = 316, 2                                                    # hidden % 8
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L4)) == mkq.MKQ_ERR_SHAPE
 
 
 def test_padding_free_argument_errors(lib):
     av = lib.mkq_attention_varlen
     assert av(P, None, 2, 64, 128, 2, P, 1.0, None, 4, None) == mkq.MKQ_ERR_NULL      # cu_seqlens
     assert av(P, P, 2, 64, 128, 2, P, 1.0, None, 5, None) == mkq.MKQ_ERR_DTYPE        # q_bits
-    assert av(P, P, 2, 200, 128, 2, P, 1.0, None, 4, None) == mkq.MKQ_ERR_UNSUPPORTED  # max_seq > 128
+    assert av(P, P, 2, 5000, 128, 2, P, 1.0, None, 4, None) == mkq.MKQ_ERR_UNSUPPORTED  # max_seq > 4096
+    assert av(P, P, 2, 200, 256, 2, P, 1.0, None, 4, None) == mkq.MKQ_ERR_UNSUPPORTED   # d_k = 128
+    assert av(P, P, 2, 200, 120, 8, P, 1.0, None, 4, None) == mkq.MKQ_ERR_UNSUPPORTED   # d_k = 15 is odd
+    assert av(P, P, 2, 200, 36, 2, P, 1.0, None, 4, None) == mkq.MKQ_ERR_SHAPE          # hidden % 8 (code rows)
     assert av(P, P, 2, 70, 128, 3, P, 1.0, None, 4, None) == mkq.MKQ_ERR_SHAPE        # hidden % heads
     assert av(P, P, 0, 70, 128, 2, None, 1.0, None, 4, None) == mkq.MKQ_OK            # empty batch
     lay = mkq.BertLayerParams()
-    lay.batch, lay.seq, lay.hidden, lay.heads, lay.ffn = 4, 100, 128, 2, 256          # seq = bound, any value <= 128
+    lay.batch, lay.seq, lay.hidden, lay.heads, lay.ffn = 4, 100, 128, 2, 256          # any length, fixed or bound
     L = mkq.BertLayerWorkspaceLayout()
-    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L)) == mkq.MKQ_ERR_UNSUPPORTED  # fixed length: % 32
+    assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L)) == mkq.MKQ_OK
     lay.cu_seqlens, lay.total_tokens = 0x1000, 230
     assert lib.mkq_bert_layer_workspace(C.byref(lay), C.byref(L)) == mkq.MKQ_OK
     assert L.qkv - L.c0 == 256 * ((230 * 128 // 2 + 255) // 256)

@@ -229,7 +229,7 @@ def test_linear_int8_code_output_with_gelu(mkq):
     assert ref["q"].min() == -128 and ref["q"].max() == 127
 
 
-@pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 64, 128, 2, 256), (2, 128, 768, 12, 3072)])
+@pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 64, 128, 2, 256), (2, 128, 768, 12, 3072), (1, 300, 512, 16, 1024), (1, 512, 256, 4, 512)])
 def test_bert_layer_int8_stagewise_and_end_to_end(mkq, B, S, hidden, heads, ffn):
     import torch
     from paper_2203_13483_amd import workloads as wl

@@ -240,7 +240,7 @@ def test_bert_layer_int4_stagewise_and_end_to_end(mkq, B, S, hidden, heads, ffn)
     assert np.array_equal(to_np(h_out2), to_np(h_out))
 
 
-@pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 64, 128, 2, 256), (2, 128, 768, 12, 3072)])
+@pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 64, 128, 2, 256), (2, 128, 768, 12, 3072), (1, 300, 512, 16, 1024), (1, 512, 256, 4, 512)])
 def test_bert_layer_fp16_baseline(mkq, B, S, hidden, heads, ffn):
     import torch
     p, h = _layer_case(41, B, S, hidden, heads, ffn)
@@ -258,6 +258,49 @@ def test_bert_layer_fp16_baseline(mkq, B, S, hidden, heads, ffn):
     out = to_np(layer(to_dev(h), ws)).astype(np.float32)
     ref = oracle.bert_layer_float(ref_params, h.astype(np.float32), act_dtype=oracle.F16)
     assert_float_close(out, oracle.round_storage(ref, oracle.F16), RTOL[1], "fp16 layer")
+
+
+# The 4-layer student of section 5.2 (hidden 312, 12 heads of 26, FFN 1200: no reduction length is a multiple
+# of 32, every code buffer is stored padded) and a BERT-large layer on 512-token sequences.
+@pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 128, 312, 12, 1200), (3, 50, 312, 12, 1200),
+                                                  (1, 512, 1024, 16, 4096), (2, 200, 768, 12, 3072)])
+def test_bert_layer_int4_other_head_sizes_and_long_sequences(mkq, B, S, hidden, heads, ffn):
+    import torch
+    from layer_checks import code_row_pitch
+    p, h = _layer_case(47, B, S, hidden, heads, ffn)
+    q = _quantized_params(p, h, B, S)
+    M = B * S
+    padded = hidden % 32 != 0
+    packed, sx = {}, {}
+    for nm in ("qkv", "ao", "up", "down"):
+        pack = mkq.mkq_pack_weights_int4_padded if padded else mkq.mkq_pack_weights_int4
+        Wq, s_w = pack(to_dev(p["W_" + nm]))
+        assert np.array_equal(to_np(s_w), q["sw_" + nm])
+        packed[nm] = (Wq, s_w, to_dev(p["b_" + nm]))
+        sx[nm] = q["sx_" + nm]
+    ln = {k: to_dev(p[k]) for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    s_out_next = 0.4
+    layer = mkq.BertLayerInt4(B, S, hidden, heads, ffn, packed, sx, ln, p["ln_eps"], s_out_next)
+    ws = torch.full((layer.workspace_bytes(),), 0x5A, dtype=torch.uint8, device="cuda")  # stale contents
+    pitch = code_row_pitch(hidden)
+    q_next = torch.full((M, pitch // 2), 0x5A, dtype=torch.uint8, device="cuda")
+    h_out = layer(to_dev(h), ws, q_out_next=q_next)
+    torch.cuda.synchronize()
+    buf = LayerBuffers(to_np(ws), layer.layout, M, hidden, ffn, 4)
+    qn = oracle.unpack_nibbles(to_np(q_next), pitch)
+    assert not qn[:, hidden:].any()
+    check_layer_stagewise(buf, q, h.astype(np.float32), to_np(h_out).astype(np.float32),
+                          [(b * S, S) for b in range(B)], q_next=qn[:, :hidden], s_out_next=s_out_next,
+                          what=f"layer {hidden}/{heads}/{ffn}")
+    # end to end against the oracle's own layer
+    ref_out, it = oracle.bert_layer_int4(q, h.astype(np.float32), act_dtype=oracle.F16)
+    assert (buf.codes(layer.layout.c3, ffn) != it["c3"]).mean() < 0.02
+    err = np.abs(to_np(h_out).astype(np.float32) - ref_out)
+    assert np.sqrt((err ** 2).mean()) < 0.03 * np.sqrt((ref_out ** 2).mean())
+    # handing in the (padded) input codes gives the same result
+    c0 = torch.from_numpy(buf.ws[layer.layout.c0: layer.layout.c0 + M * pitch // 2].copy()).cuda()
+    h_out2 = layer(to_dev(h), ws, q_in=c0, q_out_next=q_next)
+    assert np.array_equal(to_np(h_out2), to_np(h_out))
 
 
 # --- padding-free batches (the "valid tokens" of Table 2) ----------------------------------

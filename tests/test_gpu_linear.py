@@ -96,6 +96,25 @@ def test_residual_and_requant_without_gelu_is_bit_exact(mkq, res_dtype):
     assert np.array_equal(to_np(r4["out"]), oracle.pack_nibbles(ref["q"]))
 
 
+# code outputs with a row pitch: the next linear's reduction length is padded (312 -> 384, 1200 -> 1280 codes)
+@pytest.mark.parametrize("M,N,K,pitch", [(100, 312, 384, 384), (1, 1200, 384, 1280), (300, 1200, 128, 1280),
+                                         (40, 312, 1280, 320), (700, 768, 256, 768)])
+def test_code_outputs_with_a_row_pitch(mkq, M, N, K, pitch):
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M + pitch)
+    ref32 = oracle.linear_int4(A, s_x, Wc, s_w, bias)
+    s_next = float(np.float32(np.abs(ref32["y"]).max() / 20))
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.F16, s_next=s_next)
+    want = np.zeros((M, pitch), np.int8)
+    want[:, :N] = ref["q"]
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, s_next=s_next, want_q=True, q_pitch=pitch)
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(want))
+    r4 = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=s_next, q_pitch=pitch)
+    assert np.array_equal(to_np(r4["out"]), oracle.pack_nibbles(want))
+    with pytest.raises(mkq.MkqError):
+        _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=s_next, q_pitch=N - 8)
+
+
 @pytest.mark.parametrize("M,N,K", [(128, 3072, 768), (130, 202, 96)])
 def test_gelu_then_requant(mkq, M, N, K):
     A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=9)
