@@ -546,6 +546,13 @@ def side_measurements(mkq, event_time, ceil):
     except Exception as e:
         res["table2_layers"] = {"error": repr(e)}
 
+    # Whole layers beyond BERT-base at 128 tokens: the 4-layer student (head size 26, padded code rows) and a
+    # BERT-large layer on 512-token sequences (key-block attention kernel)
+    try:
+        res["layers_other_shapes"] = layers_other_shapes(mkq)
+    except Exception as e:
+        res["layers_other_shapes"] = {"error": repr(e)}
+
     # 12-layer BERT-base encoder, batch 32 x seq 128 (M = 4096), int4 vs binary16 layers
     try:
         res["encoder"] = encoder_latency(mkq, event_time)
@@ -588,6 +595,45 @@ def table2_layers(mkq):
         row["int8_over_int4"] = row["int8_us"] / row["int4_us"]
         row["fp16_over_int4"] = row["fp16_us"] / row["int4_us"]
         row["paper_T4_us"] = {"float32": t4_f32, "int8": t4_i8, "int4": t4_i4, "int8_over_int4": t4_i8 / t4_i4}
+        rows.append(row)
+    return rows
+
+
+def layers_other_shapes(mkq):
+    import torch
+    from paper_2203_13483_amd import workloads as wl
+    rows = []
+    for (name, batch, seq, H, heads, F) in (("student_4layer", 32, 128, 312, 12, 1200),
+                                            ("bert_large_seq512", 16, 512, 1024, 16, 4096)):
+        p = wl.bert_layer_weights(H, heads, F, 301)
+        ln = {k: torch.from_numpy(p[k]).cuda() for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+        padded = H % 32 != 0
+        packed4, packed8, w16 = {}, {}, {}
+        for nm in ("qkv", "ao", "up", "down"):
+            W = torch.from_numpy(p["W_" + nm]).cuda()
+            b = torch.from_numpy(p["b_" + nm]).cuda()
+            packed4[nm] = (mkq.mkq_pack_weights_int4_padded if padded else mkq.mkq_pack_weights_int4)(W) + (b,)
+            if not padded:
+                packed8[nm] = mkq.mkq_pack_weights_int8(W) + (b,)
+                w16[nm] = (W.half(), b)
+        sx4 = {"qkv": wl.LEARNED_STEP_UNIT_GAUSSIAN, "ao": 0.05, "up": wl.LEARNED_STEP_UNIT_GAUSSIAN, "down": 0.05}
+        sx8 = {k: v * 7.0 / 127.0 for k, v in sx4.items()}
+        M = batch * seq
+        h = torch.randn((M, H), dtype=torch.float16, device="cuda")
+        out = torch.empty_like(h)
+        layers = {"int4": mkq.BertLayerInt4(batch, seq, H, heads, F, packed4, sx4, ln, 1e-12)}
+        if not padded:  # the 8-bit and binary16 layers take hidden % 64 == 0 only
+            layers["int8"] = mkq.BertLayerInt8(batch, seq, H, heads, F, packed8, sx8, ln, 1e-12)
+            layers["fp16"] = mkq.BertLayerFp16(batch, seq, H, heads, F, w16, ln, 1e-12)
+        row = {"layer": name, "batch": batch, "seq": seq, "hidden": H, "heads": heads, "ffn": F}
+        for kind, layer in layers.items():
+            ws = torch.empty(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+            row[kind + "_us"] = graph_time(lambda: layer(h, ws, h_out=out), rep=10, repeats=5) * 1e6
+        qkv = torch.randn((M, 3 * H), dtype=torch.float16, device="cuda")
+        row["attention_core_us"] = graph_time(lambda: mkq.mkq_attention(qkv, batch, seq, H, heads, s_next=0.05,
+                                                                        want_ctx=False, want_q=True), rep=10, repeats=5) * 1e6
+        # q k^T and p v: 4 * seq * d_k operations per (query, head)
+        row["attention_core_TFLOPs"] = 4.0 * batch * heads * seq * seq * (H // heads) / (row["attention_core_us"] * 1e-6) / 1e12
         rows.append(row)
     return rows
 

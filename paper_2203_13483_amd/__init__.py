@@ -83,6 +83,9 @@ def load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with "
                            f"`python -m paper_2203_13483_amd.build` (there is no fallback path)")
+    # torch first: the device memory and streams handed to the library are torch's, so both must sit on the
+    # HIP runtime that torch brings; loaded before torch, the library would pull in the system's copy instead
+    _torch()
     lib = C.CDLL(LIB_PATH)
     i64, vp, f32, ci, sz = C.c_int64, C.c_void_p, C.c_float, C.c_int, C.c_size_t
     sig = {

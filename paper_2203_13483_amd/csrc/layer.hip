@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
 // so the probabilities that meet V are the normalized ones, as in the one-block kernel above (an online
 // softmax would narrow unnormalized ones).  VEC = 8: 16-byte accesses (d_k % 8 == 0); VEC = 2: 4-byte ones.
 template <int DKP, int VEC>
-__global__ __launch_bounds__(256) void attention_blocks_kernel(const uint16_t *__restrict__ qkv, int seq_fixed,
+__global__ __launch_bounds__(256, 3) void attention_blocks_kernel(const uint16_t *__restrict__ qkv, int seq_fixed,
                                                                int hidden, int heads, int dk, int q_blocks,
                                                                uint16_t *__restrict__ ctx, float s_next,
                                                                uint8_t *__restrict__ qout, int q_bits, int q_pitch,
@@ -348,8 +348,7 @@ __global__ __launch_bounds__(256) void attention_blocks_kernel(const uint16_t *_
     constexpr int ROWB = DKP * 2;  // bytes of a staged q or k row
     constexpr int CH = DKP / 8;    // its 16-byte chunks
     constexpr int VROW = 256;      // V^T row: 128 keys
-    __shared__ __attribute__((aligned(16))) uint8_t sQ[128 * ROWB];
-    __shared__ __attribute__((aligned(16))) uint8_t sK[128 * ROWB];
+    __shared__ __attribute__((aligned(16))) uint8_t sK[128 * ROWB];  // first the queries, then the key blocks
     __shared__ __attribute__((aligned(16))) uint8_t sVt[DKP * VROW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -385,89 +384,123 @@ __global__ __launch_bounds__(256) void attention_blocks_kernel(const uint16_t *_
             *reinterpret_cast<Piece *>(dst + r * ROWB + (((d >> 3) ^ swz<CH>(r & 15)) * 16) + (d & 7) * 2) = v[i];
         }
     };
-    auto store_transposed = [&](const Piece (&v)[PER_T]) __attribute__((always_inline)) {
+    // V is stored transposed, [d][key]: a thread takes the same columns of two neighbouring rows (pieces 2i and
+    // 2i + 1), so every LDS write carries the two keys of one head dimension
+    static_assert(PER_T % 2 == 0, "pairs of rows");
+    auto load_block_pairs = [&](Piece (&v)[PER_T], int r_base, int col) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < PER_T; ++i) {
-            const int idx = tid + i * 256;
-            const int r = idx / (DKP / VEC), d0 = (idx % (DKP / VEC)) * VEC;
-            uint32_t w[VEC / 2];
-            if constexpr (VEC == 8) { w[0] = v[i].x; w[1] = v[i].y; w[2] = v[i].z; w[3] = v[i].w; }
-            else w[0] = v[i];
+            const int j = tid + (i >> 1) * 256;
+            const int r = 2 * (j / (DKP / VEC)) + (i & 1), d = (j % (DKP / VEC)) * VEC;
+            int rr = r_base + r;
+            rr = rr < seq ? rr : seq - 1;
+            if (d < dk) v[i] = *reinterpret_cast<const Piece *>(qkv + (row0 + rr) * ld + col + head * dk + d);
+            else v[i] = Piece{};
+        }
+    };
+    auto store_transposed = [&](const Piece (&v)[PER_T]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < PER_T; i += 2) {
+            const int j = tid + (i >> 1) * 256;
+            const int r = 2 * (j / (DKP / VEC)), d0 = (j % (DKP / VEC)) * VEC;
+            uint32_t w0[VEC / 2], w1[VEC / 2];
+            if constexpr (VEC == 8) {
+                w0[0] = v[i].x; w0[1] = v[i].y; w0[2] = v[i].z; w0[3] = v[i].w;
+                w1[0] = v[i + 1].x; w1[1] = v[i + 1].y; w1[2] = v[i + 1].z; w1[3] = v[i + 1].w;
+            } else {
+                w0[0] = v[i];
+                w1[0] = v[i + 1];
+            }
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 const int d = d0 + e;
-                *reinterpret_cast<uint16_t *>(sVt + d * VROW + (((r >> 3) ^ (d & 15)) * 16) + (r & 7) * 2) =
-                    (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                const uint32_t lo = (w0[e >> 1] >> (16 * (e & 1))) & 0xFFFFu, hi = (w1[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                *reinterpret_cast<uint32_t *>(sVt + d * VROW + (((r >> 3) ^ (d & 15)) * 16) + (r & 7) * 2) = lo | (hi << 16);
             }
         }
     };
 
     const bool active = q_base + wave * 32 < seq;  // this wave has queries
     const int qrow = wave * 32 + fr;                // within the block
-    const float scale = 1.0f / sqrtf((float)dk);
-    // scores of key block kb (transposed): register v of tile kt is key kb*128 + kt*32 + 16*(v/8) + 8*fh + v%8
-    auto scores = [&](v16f (&sc)[4], int kb) __attribute__((always_inline)) {
+    // exp(x / sqrt(d_k)) as exp2(x * c): one multiply-add and one exponential per score
+    const float c_exp = (1.0f / sqrtf((float)dk)) * 1.4426950408889634f;
+    constexpr float MASKED = -1.0e30f;  // a key past the end of the sequence: exp2 gives 0
+    v8h qf[DKP / 16];  // this lane's query as MFMA operand
+    // raw scores q.k of the 32 keys of tile kt of block kb (transposed): register v is key
+    // kb*128 + kt*32 + 16*(v/8) + 8*fh + v%8
+    auto score_tile = [&](int kb, int kt) __attribute__((always_inline)) {
+        v16f sc;
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sc[kt][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) sc[v] = 0.0f;
+        const int krow = kt * 32 + w_row_perm(fr);
 #pragma unroll
         for (int ds = 0; ds < DKP / 16; ++ds) {
-            const int c = ds * 2 + fh;
-            const v8h qf = *reinterpret_cast<const v8h *>(sQ + qrow * ROWB + ((c ^ swz<CH>(qrow & 15)) * 16));
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
-                const int krow = kt * 32 + w_row_perm(fr);
-                const v8h kf = *reinterpret_cast<const v8h *>(sK + krow * ROWB + ((c ^ swz<CH>(krow & 15)) * 16));
-                sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf, sc[kt], 0, 0, 0);
-            }
+            const v8h kf = *reinterpret_cast<const v8h *>(sK + krow * ROWB + (((ds * 2 + fh) ^ swz<CH>(krow & 15)) * 16));
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ds], sc, 0, 0, 0);
         }
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+        if (kb * 128 + kt * 32 + 32 > seq) {  // (uniform) the tile holds keys that do not exist
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int key = kb * 128 + kt * 32 + 16 * (v / 8) + 8 * fh + (v % 8);
-                sc[kt][v] = (key < seq) ? sc[kt][v] * scale : -3.0e38f;
+                sc[v] = (key < seq) ? sc[v] : MASKED;
             }
+        }
+        return sc;
     };
 
-    Piece ld0[PER_T], ld1[PER_T];
-    load_block(ld0, q_base, 0);
-    load_block(ld1, 0, hidden);
-    store_rows(sQ, ld0);
-    store_rows(sK, ld1);
+    // The next block's rows are loaded into registers before the current block is computed and written to
+    // LDS after it, so the trip to memory hides behind the arithmetic.
+    Piece ldK[PER_T], ldV[PER_T];
+    load_block(ldV, q_base, 0);
+    load_block(ldK, 0, hidden);
+    store_rows(sK, ldV);
+    __syncthreads();
+#pragma unroll
+    for (int ds = 0; ds < DKP / 16; ++ds)
+        qf[ds] = *reinterpret_cast<const v8h *>(sK + qrow * ROWB + (((ds * 2 + fh) ^ swz<CH>(qrow & 15)) * 16));
+    __syncthreads();
+    store_rows(sK, ldK);
     __syncthreads();
 
     // pass 1: row maximum and denominator (each lane sums its half of the keys; the halves meet at the end)
-    float mx = -3.0e38f, den = 0.0f;
+    float mx = MASKED, den = 0.0f;  // mx: maximum of the raw scores so far
     for (int kb = 0; kb < key_blocks; ++kb) {
-        if (kb > 0) {
-            load_block(ld1, kb * 128, hidden);
-            __syncthreads();  // every wave is done with the previous block
-            store_rows(sK, ld1);
-            __syncthreads();
+        const bool more = kb + 1 < key_blocks;
+        if (more) {
+            load_block(ldK, (kb + 1) * 128, hidden);
+        } else {  // the first block of pass 2
+            load_block_pairs(ldV, 0, 2 * hidden);
+            if (key_blocks > 1) load_block(ldK, 0, hidden);
         }
         if (active) {
-            v16f sc[4];
-            scores(sc, kb);
-            float bm = -3.0e38f;
+#pragma unroll 1
+            for (int kt = 0; kt < 4; ++kt) {
+                const v16f sc = score_tile(kb, kt);
+                float bm = sc[0];
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+                for (int v = 1; v < 16; ++v) bm = fmaxf(bm, sc[v]);
+                bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+                const float m_new = fmaxf(mx, bm);
+                const float shift = -m_new * c_exp;
+                float part = 0.0f;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) bm = fmaxf(bm, sc[kt][v]);
-            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-            const float m_new = fmaxf(mx, bm);
-            float part = 0.0f;
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) part += exp2f((sc[kt][v] - m_new) * 1.4426950408889634f);
-            den = den * exp2f((mx - m_new) * 1.4426950408889634f) + part;
-            mx = m_new;
+                for (int v = 0; v < 16; ++v) part += __builtin_amdgcn_exp2f(__fmaf_rn(sc[v], c_exp, shift));
+                den = den * __builtin_amdgcn_exp2f((mx - m_new) * c_exp) + part;
+                mx = m_new;
+            }
         }
+        __syncthreads();  // every wave is done with the block
+        if (more) {
+            store_rows(sK, ldK);
+        } else {
+            store_transposed(ldV);
+            if (key_blocks > 1) store_rows(sK, ldK);  // one block: the keys are still there
+        }
+        __syncthreads();
     }
     den += __shfl_xor(den, 32, 64);
-    const float inv = 1.0f / den;
+    // p = exp2(x c - max c - log2(denominator)): the division folded into the exponent
+    const float shift2 = -mx * c_exp - __log2f(den);
 
     // pass 2: O^T = V^T P^T over the key blocks
     constexpr int DT = DKP / 32;
@@ -477,23 +510,21 @@ __global__ __launch_bounds__(256) void attention_blocks_kernel(const uint16_t *_
 #pragma unroll
         for (int v = 0; v < 16; ++v) ot[dt][v] = 0.0f;
     for (int kb = 0; kb < key_blocks; ++kb) {
-        load_block(ld0, kb * 128, 2 * hidden);
-        if (key_blocks > 1) load_block(ld1, kb * 128, hidden);
-        __syncthreads();
-        store_transposed(ld0);
-        if (key_blocks > 1) store_rows(sK, ld1);  // one block: the keys are still there
-        __syncthreads();
+        const bool more = kb + 1 < key_blocks;
+        if (more) {
+            load_block_pairs(ldV, (kb + 1) * 128, 2 * hidden);
+            load_block(ldK, (kb + 1) * 128, hidden);
+        }
         if (active) {
-            v16f sc[4];
-            scores(sc, kb);
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll 1
+            for (int kt = 0; kt < 4; ++kt) {
+                const v16f sc = score_tile(kb, kt);
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
                     v8h pf;
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        pf[e] = (_Float16)(exp2f((sc[kt][8 * st + e] - mx) * 1.4426950408889634f) * inv);
+                        pf[e] = (_Float16)__builtin_amdgcn_exp2f(__fmaf_rn(sc[8 * st + e], c_exp, shift2));
                     const int kc = (2 * kt + st) * 2 + fh;  // chunk of 8 keys
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
@@ -502,6 +533,13 @@ __global__ __launch_bounds__(256) void attention_blocks_kernel(const uint16_t *_
                         ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, ot[dt], 0, 0, 0);
                     }
                 }
+            }
+        }
+        if (more) {
+            __syncthreads();
+            store_transposed(ldV);
+            store_rows(sK, ldK);
+            __syncthreads();
         }
     }
 

@@ -17,7 +17,14 @@ constexpr int QMAX = 7;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool scale_ok(float s) { return s > 0.0f && s < __builtin_inff(); }
-inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+// Every entry point converts its stream argument here before it launches anything.  The runtime keeps the
+// last error of the thread until somebody reads it: one left behind by an earlier call of the process (not
+// ours, and handled or ignored there) must not be taken for a failure of our launch, so it is read away here.
+inline hipStream_t as_stream(void *s)
+{
+    (void)hipGetLastError();
+    return reinterpret_cast<hipStream_t>(s);
+}
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MKQ_OK : MKQ_ERR_HIP; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
