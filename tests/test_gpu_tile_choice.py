@@ -54,9 +54,13 @@ def test_automatic_choice_is_within_five_percent_of_the_best(M, K, N):
             assert e.status == mkq.MKQ_ERR_UNSUPPORTED
             continue
         times[cfg] = _time(run(cfg))
-    auto = _time(run(None))
     best_cfg = min(times, key=times.get)
-    auto = min(auto, _time(run(None)))  # (second sample: the clock moves between measurements)
+    # the clock moves between measurements (the sweep above heats the chip): the two that are compared are timed
+    # again side by side, three times, and each keeps its fastest sample
+    auto = float("inf")
+    for _ in range(3):
+        auto = min(auto, _time(run(None)))
+        times[best_cfg] = min(times[best_cfg], _time(run(best_cfg)))
     print(f"M={M} K={K} N={N}: automatic {auto * 1e3:.2f} us, best forced {best_cfg}: {times[best_cfg] * 1e3:.2f} us; "
           + " ".join(f"{c}:{t * 1e3:.1f}" for c, t in sorted(times.items())))
     assert auto <= 1.05 * times[best_cfg] + 0.0003, (auto, best_cfg, times[best_cfg])
