@@ -271,3 +271,23 @@ def test_splitk_scratch_and_stream_layout_argument_errors(lib):
     assert t(P, mkq.MKQ_I4, 1.0, P, P, None, 512, 256, 256, P, mkq.MKQ_F16, None, None, 0, None, 50, 0) == mkq.MKQ_ERR_UNSUPPORTED
     assert t(P, mkq.MKQ_I4, 1.0, P, P, None, 512, 256, 96, P, mkq.MKQ_F16, None, None, 0, None, 18, 0) == mkq.MKQ_ERR_UNSUPPORTED
     assert t(P, mkq.MKQ_I4, 1.0, P, P, None, 512, 256, 256, P, mkq.MKQ_F16, None, None, 0, None, 999, 0) == mkq.MKQ_ERR_UNSUPPORTED
+
+
+def test_ceiling_probe_argument_errors(lib):
+    ms = lib.mkq_measure_stream
+    ms.restype, ms.argtypes = C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    assert ms(3, P, P, 1024, None) == mkq.MKQ_ERR_DTYPE          # kind
+    assert ms(0, None, P, 1024, None) == mkq.MKQ_ERR_NULL        # a read needs a source
+    assert ms(1, None, None, 1024, None) == mkq.MKQ_ERR_NULL     # a write needs a destination
+    assert ms(2, P, ODD, 1024, None) == mkq.MKQ_ERR_ALIGN
+    assert ms(2, P, P, 1000, None) == mkq.MKQ_ERR_SHAPE          # bytes % 16
+    assert ms(2, P, P, 0, None) == mkq.MKQ_ERR_SHAPE
+    # the size of the operand block and the operation count depend on the device's compute units: without a
+    # device both are 0, with one they are checked in the GPU tier
+    assert lib.mkq_measure_mfma_i8_ops(0) == 0 and lib.mkq_measure_mfma_i8_ops(-3) == 0
+    mm = lib.mkq_measure_mfma_i8
+    mm.restype, mm.argtypes = C.c_int, [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p]
+    assert mm(None, 1 << 20, 4, P, None) == mkq.MKQ_ERR_NULL
+    assert mm(P, 1 << 20, 4, None, None) == mkq.MKQ_ERR_NULL
+    assert mm(ODD, 1 << 20, 4, P, None) == mkq.MKQ_ERR_ALIGN
+    assert mm(P, 1 << 20, 0, P, None) == mkq.MKQ_ERR_SHAPE

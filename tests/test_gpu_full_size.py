@@ -9,7 +9,7 @@ import pytest
 import oracle
 from paper_2203_13483_amd import workloads as wl
 from helpers import RTOL, assert_codes_match_with_tie_band, assert_float_close, to_dev, to_np
-from layer_checks import LayerBuffers, check_layer_stagewise
+from layer_checks import LayerBuffers, attention_code_band, check_layer_stagewise, codes_match
 
 pytestmark = pytest.mark.gpu
 
@@ -164,6 +164,51 @@ def test_encoder_layer_full_batch_sampled_sequences(mkq):
     assert np.sqrt((err ** 2).mean()) < 0.03 * np.sqrt((ref_out ** 2).mean())
     assert np.isfinite(out).all()
     # LayerNorm with gamma = 1, beta = 0: every output row has zero mean and unit variance
+    assert np.abs(out.mean(axis=1)).max() < 2e-2 and np.abs(out.var(axis=1) - 1).max() < 5e-2
+
+
+def test_attention_bert_large_512_tokens_full_batch(mkq):
+    """BASELINE configs[3] shape of the attention core: 16 sequences of 512 tokens, 16 heads of 64 (the shape
+    bench.py times), context and codes of four of the sequences against the oracle."""
+    B, S, heads, dk = 16, 512, 16, 64
+    H = heads * dk
+    rng = np.random.default_rng(77)
+    qkv = rng.normal(0, 1.0, (B * S, 3 * H)).astype(np.float16)
+    s_next = 0.05
+    ctx, q = mkq.mkq_attention(to_dev(qkv), B, S, H, heads, s_next=s_next, want_q=True)
+    got, codes = to_np(ctx).astype(np.float32), oracle.unpack_nibbles(to_np(q), H)
+    assert np.isfinite(got).all()
+    for b in (0, 5, 10, 15):
+        rows = slice(b * S, (b + 1) * S)
+        x = qkv[rows].astype(np.float32)
+        ref = oracle.attention(x, 1, S, H, heads, p_dtype=oracle.F16)
+        assert_float_close(got[rows], ref, RTOL[1], f"sequence {b}")
+        codes_match(codes[rows], oracle.quantize(ref, s_next), ref, s_next,
+                    attention_code_band(x, S, H, heads, s_next), f"context codes of sequence {b}")
+
+
+def test_student_layer_full_batch_sampled_sequences(mkq):
+    """The 4-layer student's layer (hidden 312, 12 heads of 26, FFN 1200: padded code rows) at 32 x 128 tokens,
+    stage by stage on the first and the last sequence."""
+    import torch
+    B, S, H, heads, F = 32, 128, 312, 12, 1200
+    p = wl.bert_layer_weights(H, heads, F, 103)
+    steps = {"qkv": wl.LEARNED_STEP_UNIT_GAUSSIAN, "ao": 0.05, "up": wl.LEARNED_STEP_UNIT_GAUSSIAN, "down": 0.05}
+    packed, q = {}, {k: p[k] for k in ("hidden", "heads", "ffn", "ln_eps", "ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    for nm in ("qkv", "ao", "up", "down"):
+        Wq, s_w = mkq.mkq_pack_weights_int4_padded(to_dev(p["W_" + nm]))
+        packed[nm] = (Wq, s_w, to_dev(p["b_" + nm]))
+        q["w_" + nm], q["sw_" + nm] = oracle.quantize_weights(p["W_" + nm])
+        q["b_" + nm], q["sx_" + nm] = p["b_" + nm], steps[nm]
+    ln = {k: to_dev(p[k]) for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+    h = wl.hidden_states(B, S, H, 3).astype(np.float16)
+    layer = mkq.BertLayerInt4(B, S, H, heads, F, packed, steps, ln, p["ln_eps"], 0.0)
+    ws = torch.full((layer.workspace_bytes(),), 0xA5, dtype=torch.uint8, device="cuda")
+    out = to_np(layer(to_dev(h), ws)).astype(np.float32)
+    torch.cuda.synchronize()
+    buf = LayerBuffers(to_np(ws), layer.layout, B * S, H, F, 4)
+    check_layer_stagewise(buf, q, h.astype(np.float32), out, [(0, S), (31 * S, S)], what="student layer")
+    assert np.isfinite(out).all()
     assert np.abs(out.mean(axis=1)).max() < 2e-2 and np.abs(out.var(axis=1) - 1).max() < 5e-2
 
 

@@ -324,3 +324,30 @@ def test_few_token_linear_on_streaming_layout(mkq, scratch, M, N, K, prefetch, k
     assert np.array_equal(to_np(r["acc"]), ref["acc"])
     assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
     assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"]))
+
+
+def test_init_and_ceiling_probes(mkq):
+    """mkq_init (all once-per-device set-up ahead of the first call) and the probes behind the benchmark's
+    measured ceilings: they run, move the bytes they say they move, and report whole MFMA instructions."""
+    import torch
+    lib = mkq.load()
+    assert lib.mkq_init() == mkq.MKQ_OK and lib.mkq_init() == mkq.MKQ_OK
+    n = 1 << 20
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    mkq.mkq_measure_stream(2, src, dst, n)
+    assert torch.equal(src, dst)
+    mkq.mkq_measure_stream(0, src, dst, n)       # a read leaves both alone
+    assert torch.equal(src, dst)
+    mkq.mkq_measure_stream(1, None, dst, n - 4096)
+    assert torch.equal(src[n - 4096:], dst[n - 4096:]) and not torch.equal(src[:n - 4096], dst[:n - 4096])
+    need = lib.mkq_measure_mfma_i8_operand_bytes()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert need == cus * 2 * 256 * 6 * 16
+    ops = torch.randint(0, 256, (need,), dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    done = mkq.mkq_measure_mfma_i8(ops, 16, sink)
+    torch.cuda.synchronize()
+    assert done == cus * 8 * 16 * 8 * 2 * 32 * 32 * 32
+    with pytest.raises(mkq.MkqError):
+        mkq.mkq_measure_mfma_i8(ops[:need - 16], 16, sink)
