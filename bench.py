@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the large-M / small-M side measurements")
-    ap.add_argument("--only", choices=["headline", "large-m", "small-m", "calibration"], default=None,
+    ap.add_argument("--only", choices=["headline", "large-m", "small-m", "calibration", "layers"], default=None,
                     help="run only that group of side measurements, eagerly and a few launches each (the form "
                          "that rocprofv3 --kernel-trace / --pmc runs are taken of); prints their JSON")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -283,6 +283,27 @@ def profile_launches(mkq, which, launches=5):
             done.append({"M": M, "K": K, "N": N, "launches": launches, "ops_per_launch": 2.0 * M * N * K,
                          "grid_threads": None})
             del a, w, out, a6, w6
+    elif which == "layers":
+        # whole encoder layers in 4 bits, eagerly: every kernel of the layer shows with its own duration
+        from paper_2203_13483_amd import workloads as wl
+        for (name, batch, seq, H, heads, F) in (("bert_base", 32, 128, 768, 12, 3072),
+                                                ("bert_large_seq512", 16, 512, 1024, 16, 4096),
+                                                ("student_4layer", 32, 128, 312, 12, 1200)):
+            p = wl.bert_layer_weights(H, heads, F, 301)
+            ln = {k: torch.from_numpy(p[k]).cuda() for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+            pack = mkq.mkq_pack_weights_int4_padded if H % 32 else mkq.mkq_pack_weights_int4
+            packed = {nm: pack(torch.from_numpy(p["W_" + nm]).cuda()) + (torch.from_numpy(p["b_" + nm]).cuda(),)
+                      for nm in ("qkv", "ao", "up", "down")}
+            sx = {"qkv": wl.LEARNED_STEP_UNIT_GAUSSIAN, "ao": 0.05, "up": wl.LEARNED_STEP_UNIT_GAUSSIAN, "down": 0.05}
+            layer = mkq.BertLayerInt4(batch, seq, H, heads, F, packed, sx, ln, 1e-12)
+            h = torch.randn((batch * seq, H), dtype=torch.float16, device="cuda")
+            out = torch.empty_like(h)
+            ws = torch.empty(layer.workspace_bytes(), dtype=torch.uint8, device="cuda")
+            for _ in range(launches):
+                layer(h, ws, h_out=out)
+            torch.cuda.synchronize()
+            done.append({"layer": name, "batch": batch, "seq": seq, "hidden": H, "heads": heads, "ffn": F,
+                         "launches": launches})
     elif which == "calibration":
         M, K = CALIBRATION_SHAPE
         x = torch.randn((M, K), dtype=torch.float16, device="cuda")

@@ -141,8 +141,8 @@ typedef struct mkq_epilogue {
     size_t splitk_scratch_bytes;
     int64_t q_pitch;      /* codes per row of the code outputs (`out` of MKQ_I4 / MKQ_I8, q_out); 0 = N.  A
                              consumer whose reduction length is padded (mkq_padded_k) takes rows of that
-                             many codes: give the padded length here and clear the buffer once -- the
-                             columns from N on are never written.  Otherwise >= N and a multiple of 8. */
+                             many codes: give the padded length here; the columns N .. q_pitch - 1 of every
+                             row are written as zero codes.  >= N, a multiple of 8, and N % 8 == 0. */
 } mkq_epilogue;
 
 /* Scratch of a K split across workgroups.  Few tokens against a weight matrix with few output channels
@@ -338,7 +338,7 @@ int mkq_bert_layer_workspace(const mkq_bert_layer_params *p_host,
  * A hidden or FFN size that is no multiple of 32 (the 4-layer student of section 5.2: 312 and 1200) is
  * carried padded: every 4-bit code buffer whose rows feed a linear of that reduction length -- q_in,
  * q_out_next, the workspace's c0..c3 -- has rows of mkq_padded_k(size) / 2 bytes with zero codes past the
- * real columns (the layer clears and fills them itself), and the weights come from
+ * real columns (every kernel of the layer that writes codes writes the padding too), and the weights come from
  * mkq_pack_weights_int4_padded.  Sizes that are a multiple of 32 are stored as they are.
  * Errors: NULL, SHAPE, ALIGN, SCALE, DTYPE, WORKSPACE, UNSUPPORTED, HIP. */
 int mkq_bert_layer_int4(const mkq_bert_layer_params *p_host, const void *h_in, int h_dtype,

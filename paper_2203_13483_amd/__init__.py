@@ -329,15 +329,15 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
                     s_next: float = 0.0, want_q: bool = False, want_acc: bool = False,
                     out=None, workspace=None, stream=None, splitk_scratch=None,
                     config: int | None = None, k_slices: int = 0, w_stream: bool = False,
-                    prefetch_stages: int = 0, q_pitch: int = 0):
+                    prefetch_stages: int = 0, q_pitch: int = 0, q_out=None):
     """The quantized linear.  ``a`` is packed codes (uint8 [M,K/2]) or float [M,K].
 
     Returns a dict with ``out`` (float tensor, or uint8 [M,N/2] for MKQ_I4) and
     optionally ``q`` (packed codes under s_next) and ``acc`` (int32 [M,N]).
     ``config`` / ``k_slices`` call mkq_tuning_linear_int4 (the kernel configuration chosen by the caller).
     ``w_stream``: Wq is in the streaming layout (mkq_linear_int4_stream; ``prefetch_stages`` / ``k_slices``
-    call its tuning variant).  ``q_pitch``: codes per row of the code outputs (0 = N); the buffers are zeroed
-    when it is given, since the columns from N on are not written.
+    call its tuning variant).  ``q_pitch``: codes per row of the code outputs (0 = N; the columns from N on are written
+    as zero codes).  ``q_out``: the caller's buffer for the extra codes (implies ``want_q``).
     """
     torch = _torch()
     if a_is_codes is None:
@@ -347,9 +347,9 @@ def mkq_linear_int4(a, s_x: float, Wq, s_w, bias, N: int, K: int, out_dtype: int
     dev = a.device
     code_cols = (int(q_pitch) or N) // 2
     if out is None:
-        out = (torch.zeros((M, code_cols), dtype=torch.uint8, device=dev) if out_dtype == MKQ_I4
+        out = (torch.empty((M, code_cols), dtype=torch.uint8, device=dev) if out_dtype == MKQ_I4
                else torch.empty((M, N), dtype=_torch_dtype(out_dtype), device=dev))
-    q = torch.zeros((M, code_cols), dtype=torch.uint8, device=dev) if want_q else None
+    q = q_out if q_out is not None else (torch.empty((M, code_cols), dtype=torch.uint8, device=dev) if want_q else None)
     acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
     epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
                    residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,

@@ -1356,7 +1356,8 @@ static int linear_int4_run(const void *a, int a_dtype, float s_x, const uint8_t 
     if (M < 0 || N <= 0 || K <= 0 || (K % 32) != 0) return MKQ_ERR_SHAPE;
     if (writes_codes && (N % 2) != 0) return MKQ_ERR_SHAPE;
     const int64_t q_pitch = epi ? epi->q_pitch : 0;
-    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF)) return MKQ_ERR_SHAPE;
+    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF || (q_pitch != N && (N % 8) != 0)))
+        return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
     if (writes_codes && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
     if (M == 0) return MKQ_OK;  // empty batch: pointers may be NULL
@@ -1601,7 +1602,8 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
     }
     if (M < 0 || N <= 0 || K <= 0 || (K % 64) != 0) return MKQ_ERR_SHAPE;
     const int64_t q_pitch = epi ? epi->q_pitch : 0;
-    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF)) return MKQ_ERR_SHAPE;
+    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF || (q_pitch != N && (N % 8) != 0)))
+        return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
     if (out && out_dtype == MKQ_I8 && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
     if (M == 0) return MKQ_OK;
@@ -1649,7 +1651,8 @@ static int linear_int4_e3m2_run(const uint8_t *a, float s_x, const uint8_t *Wq, 
     if (M < 0 || N <= 0 || K <= 0 || (K % 128) != 0) return MKQ_ERR_SHAPE;
     if (writes_codes && (N % 2) != 0) return MKQ_ERR_SHAPE;
     const int64_t q_pitch = epi ? epi->q_pitch : 0;
-    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF)) return MKQ_ERR_SHAPE;
+    if (q_pitch != 0 && (q_pitch < N || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF || (q_pitch != N && (N % 8) != 0)))
+        return MKQ_ERR_SHAPE;
     if (!scale_ok(s_x)) return MKQ_ERR_SCALE;
     if (writes_codes && !scale_ok(epi ? epi->s_next : 0.0f)) return MKQ_ERR_SCALE;
     if (M == 0) return MKQ_OK;

@@ -228,6 +228,8 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                     uint8_t *qdst = (uint8_t *)p.out + oq;
                     if (vec_ok) {
                         *reinterpret_cast<uint2 *>(qdst) = bytes8(cd);
+                        if (p.q_pitch > p.N && nb + 8 == p.N)
+                            for (int c = 8; c < p.q_pitch - nb; c += 8) reinterpret_cast<uint2 *>(qdst)[c / 8] = make_uint2(0u, 0u);
                     } else {
                         for (int e = 0; e < nvalid; ++e) qdst[e] = (uint8_t)cd[e];
                     }
@@ -241,6 +243,10 @@ __device__ __forceinline__ void gemm_i4_epilogue(const GemmI4Params &p, v16i (&a
                     uint8_t *qdst = (out_dtype == MKQ_I4 ? (uint8_t *)p.out : q_extra) + (oq >> 1);
                     if (vec_ok) {
                         *reinterpret_cast<uint32_t *>(qdst) = packed;
+                        // a row with a pitch: the lane that owns the last 8 channels also writes the zero
+                        // padding codes N .. pitch - 1 (both multiples of 8)
+                        if (p.q_pitch > p.N && nb + 8 == p.N)
+                            for (int c = 8; c < p.q_pitch - nb; c += 8) reinterpret_cast<uint32_t *>(qdst)[c / 8] = 0u;
                     } else {
                         for (int e = 0; e < nvalid / 2; ++e) qdst[e] = (uint8_t)(packed >> (8 * e));
                     }

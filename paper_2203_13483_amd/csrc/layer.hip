@@ -80,6 +80,9 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
                 for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
                 q[(int64_t)row * q_chunks + c] = packed;
             }
+        } else if (q && c < q_chunks) {  // padding codes of a row with a pitch: zero
+            if (q_bits == 8) reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = make_uint2(0u, 0u);
+            else q[(int64_t)row * q_chunks + c] = 0u;
         }
     }
 }
@@ -170,6 +173,9 @@ __global__ __launch_bounds__(256) void layernorm_half_kernel(const uint16_t *__r
                 for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
                 q[(int64_t)row * q_chunks + c] = packed;
             }
+        } else if (q && c < q_chunks) {  // padding codes of a row with a pitch: zero
+            if (q_bits == 8) reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = make_uint2(0u, 0u);
+            else q[(int64_t)row * q_chunks + c] = 0u;
         }
     }
 }
@@ -545,6 +551,14 @@ __global__ __launch_bounds__(256, 3) void attention_blocks_kernel(const uint16_t
 
     if (q_base + qrow >= seq) return;
     const int64_t orow = row0 + q_base + qrow;
+    if (qout && head == heads - 1 && fh == 0 && q_pitch > hidden) {
+        // padding codes of a row with a pitch: zero (hidden and the pitch are multiples of 8 codes)
+        if (q_bits == 8) {
+            for (int c = hidden; c < q_pitch; c += 8) *reinterpret_cast<uint2 *>(qout + orow * q_pitch + c) = make_uint2(0u, 0u);
+        } else {
+            for (int c = hidden; c < q_pitch; c += 8) *reinterpret_cast<uint32_t *>(qout + ((orow * q_pitch + c) >> 1)) = 0u;
+        }
+    }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -588,13 +602,14 @@ static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 using namespace mkq;
 
-// q_pitch: codes per row of q_out (0: D)
+// q_pitch: codes per row of q_out (0: D; at most D rounded up to a multiple of 128, which every kernel
+// variant's lanes cover): the codes D .. q_pitch - 1 of a row are written as zero
 static int layernorm_run(const void *x, int64_t M, int64_t D, const float *gamma, const float *beta, float eps,
                          void *y, float s_next, void *q_out, int q_bits, void *stream, int64_t q_pitch = 0)
 {
     if (M < 0 || D <= 0 || (D % 8) != 0) return MKQ_ERR_SHAPE;
     if (q_pitch == 0) q_pitch = D;
-    if (q_pitch < D || (q_pitch % 8) != 0 || q_pitch > 0x7FFFFFFF) return MKQ_ERR_SHAPE;
+    if (q_pitch < D || (q_pitch % 8) != 0 || q_pitch > ceil_div(D, 128) * 128) return MKQ_ERR_SHAPE;
     const int q_chunks = (int)(q_pitch / 8);
     if (D > 8192) return MKQ_ERR_UNSUPPORTED;
     if (q_out && !scale_ok(s_next)) return MKQ_ERR_SCALE;
@@ -734,19 +749,6 @@ static inline int64_t code_row(int bits, int64_t K)
     return (bits == 4 && (K % 32) != 0) ? mkq_padded_k(K) : K;
 }
 
-__global__ void clear16_kernel(uint4 *__restrict__ p, int64_t n)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = make_uint4(0, 0, 0, 0);
-}
-
-static int clear_bytes(void *p, size_t bytes, hipStream_t st)  // bytes % 16 == 0
-{
-    const int64_t n = (int64_t)(bytes / 16);
-    if (n == 0) return MKQ_OK;
-    clear16_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>((uint4 *)p, n);
-    return launch_status();
-}
 
 template <class P>
 static inline int64_t layer_tokens(const P *p)
@@ -835,21 +837,8 @@ static int bert_layer_run(int bits, const mkq_bert_layer_params *p, const void *
     if (next_bits == 8 && (H % 64) != 0) return MKQ_ERR_SHAPE;  // the 8-bit layer that would read them
     const int code_dtype = bits == 8 ? MKQ_I8 : MKQ_I4;
     uint8_t *ws = (uint8_t *)workspace;
-    hipStream_t st = as_stream(stream);
-    // the writers of codes leave padding columns alone: they are zero from here on
-    if (Hp != H) {
-        rc = clear_bytes(ws + L.c1, align256((size_t)(M * Hp / 2)), st);
-        if (rc == MKQ_OK) rc = clear_bytes(ws + L.c2, align256((size_t)(M * Hp / 2)), st);
-        if (rc != MKQ_OK) return rc;
-    }
-    if (Fp != F) {
-        rc = clear_bytes(ws + L.c3, align256((size_t)(M * Fp / 2)), st);
-        if (rc != MKQ_OK) return rc;
-    }
-    if (want_next && next_pitch != H) {
-        rc = clear_bytes(q_out_next, (size_t)(M * next_pitch / 2), st);  // rows of a multiple of 64 bytes
-        if (rc != MKQ_OK) return rc;
-    }
+    // (every writer of codes -- quantizer, attention, LayerNorm, the FFN-up epilogue -- fills the padding
+    // columns of its rows with zero codes itself)
     const uint8_t *c0 = q_in;
     if (!c0) {
         rc = bits == 8   ? mkq_quantize_int8(h_in, h_dtype, M, H, H, p->sx_qkv, (int8_t *)(ws + L.c0), stream)

@@ -106,10 +106,12 @@ def test_code_outputs_with_a_row_pitch(mkq, M, N, K, pitch):
     ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.F16, s_next=s_next)
     want = np.zeros((M, pitch), np.int8)
     want[:, :N] = ref["q"]
-    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, s_next=s_next, want_q=True, q_pitch=pitch)
+    import torch
+    stale = lambda: torch.full((M, pitch // 2), 0x5A, dtype=torch.uint8, device="cuda")  # the padding must be written
+    r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, s_next=s_next, q_out=stale(), q_pitch=pitch)
     assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
     assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(want))
-    r4 = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=s_next, q_pitch=pitch)
+    r4 = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=s_next, out=stale(), q_pitch=pitch)
     assert np.array_equal(to_np(r4["out"]), oracle.pack_nibbles(want))
     with pytest.raises(mkq.MkqError):
         _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, s_next=s_next, q_pitch=N - 8)
