@@ -23,8 +23,11 @@ extern "C" {
  *                          64x64 four-stage, 64x64 three-stage, 128x128
  *             30           first few-token kernel (M <= 128, K % 256 == 0; waves split K, operands through registers)
  *             50           few-token weight-streaming kernel (M <= 128, K % 256 == 0)
- *   k_slices  0 = the library's choice; otherwise the number of K slices across workgroups of configuration
- *             50 (needs epi->splitk_scratch; clamped to what K and the scratch area allow)
+ *             60, 61, 62   128 x 128, 64 x 64 (two wave groups) and 128 x 64 tiles with the k loop also split
+ *                          across workgroups (needs epi->splitk_scratch; k_slices must divide K's 128-code
+ *                          stages and leave two per slice; measured slower than the unsplit tiles, kept for study)
+ *   k_slices  0 = the library's choice; otherwise the number of K slices across workgroups of configurations
+ *             50 (needs epi->splitk_scratch; clamped to what K and the scratch area allow) and 60 .. 62
  * A configuration that does not apply to the arguments returns MKQ_ERR_UNSUPPORTED before anything is enqueued. */
 int mkq_tuning_linear_int4(const void *a, int a_dtype, float s_x, const uint8_t *Wq, const float *s_w,
                            const float *bias, int64_t M, int64_t N, int64_t K, void *out, int out_dtype,

@@ -279,11 +279,18 @@ constexpr int PRIO_SLICE_LOG2 = 15;
 // k loop, where a lone wave per SIMD is bound by its own instruction stream); the other groups'
 // partial accumulators meet the first group's in LDS at the end of a tile and the first group
 // runs the epilogue.
-template <class Cfg, class Epi, int BITS, int KSPLIT = 1>
+// XS: the reduction over K of an output tile is, beyond that, cut into p.ks slices that different workgroups
+// sum (few tokens against a weight matrix with few output channels give too few tiles to fill the chip).
+// The persistent loop then runs over (tile, slice) pairs; at the end of a pair the workgroup stores its partial
+// accumulators to the caller's scratch area and draws a ticket on the tile's counter, and the one that draws the
+// last ticket adds the others' partials to its registers and runs the epilogue ("last ticket": nobody waits
+// for anybody, so the grid drains in any scheduling order).  int32 addition is associative: same bits as unsplit.
+template <class Cfg, class Epi, int BITS, int KSPLIT = 1, bool XS = false>
 __global__ __launch_bounds__(Cfg::THREADS * KSPLIT)
 __attribute__((amdgpu_waves_per_eu(KSplitXch<Cfg>::waves_per_eu(KSPLIT), KSplitXch<Cfg>::waves_per_eu(KSPLIT))))
 void gemm_i4_dma_kernel(const GemmI4Params p)
 {
+    const int ks = XS ? p.ks : 1;
     static_assert(BITS == 4 || (BITS == 8 && Cfg::RB == 64), "8-bit operands use 64-byte stages");
     static_assert(KSPLIT == 1 || KSPLIT == 2 || KSPLIT == 4, "one, two or four wave groups");
     constexpr int BM = Cfg::BM, BN = Cfg::BN, RB = Cfg::RB, CH = Cfg::CH;
@@ -306,11 +313,10 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     const int fr = lane & 31, fh = lane >> 5;
 
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const int total_tiles = tiles_m * tiles_n;
+    const int total_tiles = tiles_m * tiles_n * ks;     // (tile, slice) pairs: pair v is slice v % ks of tile v / ks
     const int row_bytes = p.K * BITS / 8;
-    const int kt_count = row_bytes / RB / KSPLIT;       // stages per tile of this group
-    const int k_first = grp * kt_count * RB;            // first byte of its K range in a row
-    // Persistent workgroup: tiles blockIdx.x, blockIdx.x + gridDim.x, ... run through ONE
+    const int kt_count = row_bytes / RB / KSPLIT / ks;  // stages per pair of this group
+    // Persistent workgroup: pairs blockIdx.x, blockIdx.x + gridDim.x, ... run through ONE
     // software pipeline, so a tile's first stages are in flight during the previous
     // tile's epilogue.
     const int my_tiles = (total_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
@@ -320,9 +326,11 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     uint32_t goff[LPW];  // byte offset (from A or W) of this lane's chunk at k = 0
     const int c_row = lane / CH;   // row inside the copy
     const int c_slot = lane % CH;  // 16-byte slot inside the row
-    auto set_tile = [&](int tile) {
+    int k_first = 0;  // first byte, in a row, of this group's K range in the pair the copy cursor is in
+    auto set_tile = [&](int pair) {
         int tm, tn;
-        tile_coords(tile, tiles_m, tiles_n, tm, tn);
+        tile_coords(pair / ks, tiles_m, tiles_n, tm, tn);
+        k_first = ((pair % ks) * KSPLIT + grp) * kt_count * RB;
 #pragma unroll
         for (int q = 0; q < LPW; ++q) {
             const int row = (wave * LPW + q) * Cfg::ROWS_PER_COPY + c_row;  // stage row
@@ -404,12 +412,12 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
         w_k += RB;
         if (++lk == kt_count) {
             lk = 0;
-            a_k = p.A + k_first;
-            w_k = p.W + k_first;
             if (lt + (int)gridDim.x < total_tiles) {
                 lt += gridDim.x;
                 set_tile(lt);
             }
+            a_k = p.A + k_first;
+            w_k = p.W + k_first;
         }
     };
 
@@ -543,9 +551,9 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
     constexpr bool ROWS_EPI = !Epi::generic && EpiShuffle<Cfg>::usable;
     float *const sc_lds = reinterpret_cast<float *>(smem + Cfg::LDS_BYTES + wave * EpiShuffle<Cfg>::SCALE_BYTES);
     // copies s_w / bias of this wave's channels of tile `tile` to sc_lds
-    auto stage_scales = [&](int tile) {
+    auto stage_scales = [&](int pair) {
         int tm, tn;
-        tile_coords(tile, tiles_m, tiles_n, tm, tn);
+        tile_coords(pair / ks, tiles_m, tiles_n, tm, tn);
         const uint32_t dst = lds0 + Cfg::LDS_BYTES + wave * EpiShuffle<Cfg>::SCALE_BYTES;
         static_for<EpiShuffle<Cfg>::NSL>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
@@ -609,7 +617,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
 
         if (ck == kt_count) {
             int tile_m, tile_n;
-            tile_coords(ct, tiles_m, tiles_n, tile_m, tile_n);
+            tile_coords(ct / ks, tiles_m, tiles_n, tile_m, tile_n);
             if constexpr (KSPLIT > 1) {
                 // the other groups hand their partial sums over, KSplitXch<Cfg>::TPP 32x32 tiles of a wave
                 // (16 registers per lane, 4 KiB per tile) per pass through the exchange buffer
@@ -645,7 +653,65 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
                     }
                 });
             }
-            if (grp == 0) {
+            bool finish = true;  // this workgroup runs the tile's epilogue
+            if constexpr (XS) {
+                if (ks > 1) {
+                    // partial tile of a wave: TM * TN blocks of 16 registers x 64 lanes; register pair q of all
+                    // lanes is one contiguous 512-byte piece.  Agent-scope relaxed atomics: the stores write
+                    // through to memory and the loads do not hit a stale line of this XCD's L2.
+                    const int tile = ct / ks, slice = ct % ks;
+                    constexpr size_t WAVE_WORDS = (size_t)TM * TN * 8 * 64;  // 64-bit words
+                    uint64_t *const area = reinterpret_cast<uint64_t *>(p.sk_partials);
+                    if (grp == 0) {
+                        uint64_t *const mine = area + ((size_t)(tile * ks + slice) * Cfg::WAVES + wave) * WAVE_WORDS + lane;
+#pragma unroll
+                        for (int j = 0; j < TM; ++j)
+#pragma unroll
+                            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                                for (int q = 0; q < 8; ++q) {
+                                    const uint64_t v = (uint64_t)(uint32_t)acc[j][t][2 * q] |
+                                                       ((uint64_t)(uint32_t)acc[j][t][2 * q + 1] << 32);
+                                    __hip_atomic_store(mine + ((j * TN + t) * 8 + q) * 64, v, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+                                }
+                    }
+                    wait_vmcnt<0>();   // this wave's partials have reached memory (and every copy in flight has landed)
+                    __syncthreads();   // ... and every other wave's
+                    // whether this workgroup drew the last ticket is told through the first word of the first
+                    // group's ring slot of the stage just finished (idle until the next stage boundary)
+                    volatile int *const xs_last =
+                        reinterpret_cast<volatile int *>(smem_all + ((buf == 0) ? S - 1 : buf - 1) * Cfg::STAGE_BYTES);
+                    if (tid == 0) {
+                        const unsigned old = __hip_atomic_fetch_add(p.sk_counters + tile, 1u, __ATOMIC_RELAXED,
+                                                                    __HIP_MEMORY_SCOPE_AGENT);
+                        const int last = old == (unsigned)(ks - 1);
+                        if (last) __hip_atomic_store(p.sk_counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        *xs_last = last;
+                    }
+                    __syncthreads();
+                    finish = *xs_last != 0;
+                    __syncthreads();  // (the slot serves the epilogue as scratch next)
+                    if (finish && grp == 0) {
+                        for (int o = 0; o < ks; ++o) {
+                            if (o == slice) continue;
+                            const uint64_t *theirs = area + ((size_t)(tile * ks + o) * Cfg::WAVES + wave) * WAVE_WORDS + lane;
+#pragma unroll
+                            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                                    for (int q = 0; q < 8; ++q) {
+                                        const uint64_t v = __hip_atomic_load(theirs + ((j * TN + t) * 8 + q) * 64,
+                                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                        acc[j][t][2 * q] += (int)(uint32_t)v;
+                                        acc[j][t][2 * q + 1] += (int)(uint32_t)(v >> 32);
+                                    }
+                        }
+                    }
+                }
+            }
+            if (grp == 0 && finish) {
                 if constexpr (ROWS_EPI) {
                     // the slot of the stage just finished is idle until every wave has passed
                     // the next stage boundary: each wave shuffles through its share of it
@@ -670,7 +736,7 @@ void gemm_i4_dma_kernel(const GemmI4Params p)
             }
             const bool interior = (tile_m + 1) * BM <= p.M && (tile_n + 1) * BN <= p.N;
             // (a group without stores must not count them in its waits)
-            stores_pending = (ASYNC_STORES && interior && grp == 0) ? INFLIGHT : 0;
+            stores_pending = (ASYNC_STORES && interior && grp == 0 && finish) ? INFLIGHT : 0;
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
@@ -855,10 +921,10 @@ static int launch_gemm_i4(const GemmI4Params &p, hipStream_t st)
     return full ? launch_one<Cfg, true>(p, tiles, st) : launch_one<Cfg, false>(p, tiles, st);
 }
 
-template <class Cfg, class Epi, int BITS = 4, int KSPLIT = 1>
+template <class Cfg, class Epi, int BITS = 4, int KSPLIT = 1, bool XS = false>
 static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
 {
-    const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
+    const int64_t tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN) * (XS ? p.ks : 1);
     if (tiles > 0x7FFFFFFF) return MKQ_ERR_UNSUPPORTED;
     constexpr bool rows_epi = !Epi::generic && EpiShuffle<Cfg>::usable;
     constexpr size_t lds_kernel =
@@ -868,11 +934,11 @@ static int launch_gemm_i4_dma(const GemmI4Params &p, hipStream_t st)
     const size_t lds = lds_kernel;
     static PerDeviceOnce once;  // per instantiation
     int64_t resident = 0;
-    const int rc = resident_workgroups(once, gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT>, Cfg::THREADS * KSPLIT, lds,
+    const int rc = resident_workgroups(once, gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT, XS>, Cfg::THREADS * KSPLIT, lds,
                                        1 << 20, &resident);
     if (rc != MKQ_OK || p.setup_only) return rc;
     const unsigned grid = (unsigned)(tiles < resident ? tiles : resident);
-    gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT><<<grid, Cfg::THREADS * KSPLIT, lds, st>>>(p);
+    gemm_i4_dma_kernel<Cfg, Epi, BITS, KSPLIT, XS><<<grid, Cfg::THREADS * KSPLIT, lds, st>>>(p);
     return launch_status();
 }
 
@@ -887,6 +953,19 @@ static int launch_dma_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st
     case EPI_I4_GELU: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, true>>(p, st);
     case EPI_I4: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, false>>(p, st);
     default: return launch_gemm_i4_dma<Cfg, EpiGeneric>(p, st);
+    }
+}
+
+// Tiles whose k loop is also split across workgroups (p.ks slices, partial sums through the caller's scratch).
+template <class Cfg, int KS>
+static int launch_xsplit_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
+{
+    switch (epi) {
+    case EPI_F16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, false, false>, 4, KS, true>(p, st);
+    case EPI_BF16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_BF16, false, false>, 4, KS, true>(p, st);
+    case EPI_F16_RES16: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_F16, true, false>, 4, KS, true>(p, st);
+    case EPI_I4_GELU: return launch_gemm_i4_dma<Cfg, EpiFixed<MKQ_I4, false, true>, 4, KS, true>(p, st);
+    default: return launch_gemm_i4_dma<Cfg, EpiGeneric, 4, KS, true>(p, st);
     }
 }
 
@@ -933,6 +1012,33 @@ static int choose_tiles(const GemmI4Params &p)
     return 28;
 }
 
+// K split across workgroups of a tile kernel with BM x BN tiles and `groups` wave groups per workgroup: fills
+// q.ks and the scratch pointers.  forced_ks: 0 = the largest power of two that keeps at least four 64-byte
+// stages per wave group and pair, at most two (tile, slice) pairs per compute unit and partial sums that fit the scratch area.  Returns false when the
+// split does not apply (no scratch, K does not divide, the partial sums or the tile count exceed the scratch).
+static bool xsplit_plan(GemmI4Params &q, const SplitKScratch *scr, int BM, int BN, int groups, int forced_ks)
+{
+    if (!scr) return false;
+    const int64_t tiles = ceil_div(q.M, BM) * ceil_div(q.N, BN);
+    const int stages = q.K / 128 / groups;
+    if ((q.K % (128 * groups)) != 0 || tiles > SPLITK_MAX_TILES) return false;
+    int cus = 256;
+    device_cus(&cus);
+    int ks = forced_ks;
+    if (ks <= 0) {
+        ks = 1;
+        while (ks < 32 && (stages % (2 * ks)) == 0 && stages / (2 * ks) >= 4 && tiles * 2 * ks <= 2 * cus &&
+               (size_t)tiles * 2 * ks * BM * BN * sizeof(int32_t) <= scr->partial_bytes)
+            ks *= 2;
+    }
+    if (ks < 1 || (stages % ks) != 0 || stages / ks < 2) return false;
+    if ((size_t)tiles * ks * BM * BN * sizeof(int32_t) > scr->partial_bytes) return false;
+    q.ks = ks;
+    q.sk_counters = scr->counters;
+    q.sk_partials = scr->partials;
+    return true;
+}
+
 // forced_cfg: -1 = the library's own choice, otherwise one configuration by number (tuning interface);
 // scr: scratch of a K split across workgroups, or null; forced_ks: 0 = automatic.
 int run_gemm_i4(const GemmI4Params &p, hipStream_t st, int forced_cfg, const SplitKScratch *scr, int forced_ks)
@@ -970,6 +1076,19 @@ int run_gemm_i4(const GemmI4Params &p, hipStream_t st, int forced_cfg, const Spl
             cfg = (t64 <= 256 && (p.K >= 6144 || (int64_t)p.N * p.K >= ((int64_t)8 << 20))) ? 31 : 33;
     }
     if ((cfg == 31 || cfg == 33 || cfg == 35) && (p.K % 256) != 0) return MKQ_ERR_UNSUPPORTED;
+    if (cfg >= 60 && cfg <= 62) {  // tile kernels with the k loop also split across workgroups
+        GemmI4Params q = p;
+        if (cfg == 60) {
+            if (!xsplit_plan(q, scr, 128, 128, 1, forced_ks)) return MKQ_ERR_UNSUPPORTED;
+            return launch_xsplit_by_epilogue<GemmI4DmaCfg<128, 128, 2, 2, 64, 3>, 1>(q, epi, st);
+        }
+        if (cfg == 61) {
+            if (!xsplit_plan(q, scr, 64, 64, 2, forced_ks)) return MKQ_ERR_UNSUPPORTED;
+            return launch_xsplit_by_epilogue<GemmI4DmaCfg<64, 64, 2, 2, 64, 4>, 2>(q, epi, st);
+        }
+        if (!xsplit_plan(q, scr, 128, 64, 1, forced_ks)) return MKQ_ERR_UNSUPPORTED;
+        return launch_xsplit_by_epilogue<GemmI4DmaCfg<128, 64, 2, 2, 64, 3>, 1>(q, epi, st);
+    }
     switch (cfg) {
     case 2: return launch_gemm_i4<GemmI4Cfg<128, 128, 2, 2, 64>>(p, st);
     case 3: return launch_gemm_i4<GemmI4Cfg<64, 64, 2, 2, 64>>(p, st);

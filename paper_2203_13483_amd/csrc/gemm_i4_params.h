@@ -26,6 +26,11 @@ struct GemmI4Params {
     // matrix core 16*code on both sides (shift 8); the 8-bit path feeds the codes themselves.
     int acc_shift;
     float acc_unit;     // 2^-acc_shift, folded into the per-channel scale (exact)
+    // K split across workgroups of the tile kernels (their XS instantiations): slices per output tile and the
+    // caller's scratch area; 1 = no split
+    int ks = 1;
+    unsigned *sk_counters = nullptr;
+    int32_t *sk_partials = nullptr;
     // host side only: do the once-per-device setup of the kernel that would run, launch nothing
     bool setup_only = false;
 };

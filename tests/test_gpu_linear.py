@@ -353,3 +353,45 @@ def test_init_and_ceiling_probes(mkq):
     assert done == cus * 8 * 16 * 8 * 2 * 32 * 32 * 32
     with pytest.raises(mkq.MkqError):
         mkq.mkq_measure_mfma_i8(ops[:need - 16], 16, sink)
+
+
+# Tile kernels with the k loop split across workgroups (configurations 60: 128 x 128 tiles, 61: 64 x 64 tiles with
+# two wave groups, 62: 128 x 64 tiles).  k_slices: 0 = the library's choice, else forced; a split that does not
+# divide K's stages is refused before anything is launched.
+@pytest.mark.parametrize("k_slices", [0, 1, 2, 4, 8])
+@pytest.mark.parametrize("cfg", [60, 61, 62])
+@pytest.mark.parametrize("M,N,K", [(65, 200, 1024), (128, 768, 2048), (300, 520, 4096), (512, 1100, 1024),
+                                   (100, 130, 8192), (257, 4096, 2048), (700, 300, 3072)])
+def test_tiles_with_k_split_across_workgroups(mkq, scratch, cfg, M, N, K, k_slices):
+    import torch
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M + N + cfg)
+    try:
+        r = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, want_acc=True, splitk_scratch=scratch, config=cfg,
+                 k_slices=k_slices)
+    except mkq.MkqError as e:
+        assert e.status == mkq.MKQ_ERR_UNSUPPORTED
+        stages = K // 128 // (2 if cfg == 61 else 1)
+        BM, BN = {60: (128, 128), 61: (64, 64), 62: (128, 64)}[cfg]
+        tiles = -(-M // BM) * -(-N // BN)
+        too_big = tiles * k_slices * BM * BN * 4 > 16 << 20  # the partial sums exceed the scratch area
+        assert k_slices > 0 and (stages % k_slices or stages // k_slices < 2 or too_big), "a split that applies was refused"
+        pytest.skip("this split does not divide the k loop or does not fit the scratch area")
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, out_dtype=oracle.F16)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    assert int(scratch[:16384].view(torch.int32).abs().sum()) == 0, "ticket counters not cleared"
+    # the compile-time epilogues: plain binary16, binary16 residual, GELU + codes
+    r16 = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, splitk_scratch=scratch, config=cfg, k_slices=k_slices)
+    assert np.array_equal(to_np(r16["out"]).astype(np.float32), ref["y"])
+    if N % 8 == 0:
+        res = np.random.default_rng(M).normal(0, 1, (M, N)).astype(np.float16)
+        refr = oracle.linear_int4(A, s_x, Wc, s_w, bias, residual=res.astype(np.float32), out_dtype=oracle.F16)
+        rr = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_F16, residual=to_dev(res), splitk_scratch=scratch, config=cfg,
+                  k_slices=k_slices)
+        assert np.array_equal(to_np(rr["out"]).astype(np.float32), refr["y"])
+        refg = oracle.linear_int4(A, s_x, Wc, s_w, bias, act=oracle.ACT_GELU, s_next=0.5)
+        rg = _run(mkq, A, Wc, s_w, s_x, bias, mkq.MKQ_I4, act=mkq.MKQ_ACT_GELU, s_next=0.5, splitk_scratch=scratch,
+                  config=cfg, k_slices=k_slices)
+        assert_codes_match_with_tie_band(oracle.unpack_nibbles(to_np(rg["out"]), N), refg["q"], refg["y"], 0.5,
+                                         what="gelu codes")
+    assert int(scratch[:16384].view(torch.int32).abs().sum()) == 0, "ticket counters not cleared"
