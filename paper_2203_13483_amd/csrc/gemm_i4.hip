@@ -1577,7 +1577,9 @@ extern "C" int mkq_init(void)
     p.M = p.N = 256; p.K = 1024;
     p.setup_only = true;
     int rc = setup_gemm_i4_stream(p, nullptr);
-    for (int cfg : {2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29, 31, 33, 35}) {
+    // (the configurations that split K across workgroups only look at the scratch area's size here)
+    const SplitKScratch any_scratch = {reinterpret_cast<unsigned *>(16), reinterpret_cast<int32_t *>(16), (size_t)1 << 40};
+    for (int cfg : {2, 3, 11, 12, 14, 18, 19, 20, 27, 28, 29, 31, 33, 35, 60, 61, 62}) {
         // one pass per epilogue class: the parameter block is made to classify as each in turn
         for (int e = 0; e < 7 && rc == MKQ_OK; ++e) {
             GemmI4Params q = p;
@@ -1586,7 +1588,7 @@ extern "C" int mkq_init(void)
             if (e == 3) { q.residual = &q; q.residual_dtype = MKQ_F16; }
             if (e == 4) q.act = MKQ_ACT_GELU;
             if (e == 6) q.acc_out = reinterpret_cast<int32_t *>(&q);
-            rc = run_gemm_i4(q, nullptr, cfg, nullptr, 0);
+            rc = run_gemm_i4(q, nullptr, cfg, cfg >= 60 ? &any_scratch : nullptr, 0);
             if (cfg < 10) break;  // the register-staged kernel has one epilogue
         }
     }
