@@ -1002,6 +1002,9 @@ static int choose_tiles(const GemmI4Params &p)
     const double ops = 2.0 * p.M * p.N * p.K;
     if (t256x128 >= 512 && ops >= 6e10) return 18;
     if (t128x64 <= 256) return 27;
+    // GELU (and the code decision behind it) makes the epilogue a large share of a short tile: up to four 64x64
+    // workgroups per CU spread it over all SIMDs (FFN-up at M = 1024: 9.2 instead of 10.4 us)
+    if (p.act == MKQ_ACT_GELU && p.K < 2048 && ceil_div(p.M, 64) * ceil_div(p.N, 64) <= 1024) return 27;
     if (t128 >= 400 || p.K >= 2048) {
         // at most one 128x128 workgroup per CU and a long k loop: two wave groups share the tile's K
         // (a lone wave per SIMD is bound by its own instruction stream); 6-14 % at N = 768 / 1024,

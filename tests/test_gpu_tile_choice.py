@@ -33,8 +33,14 @@ def _time(fn, rep=10, samples=7):
     return sorted(ts)[len(ts) // 2]
 
 
-@pytest.mark.parametrize("M,K,N", SHAPES)
-def test_automatic_choice_is_within_five_percent_of_the_best(M, K, N):
+# the layer's own epilogues at the BERT-base shapes: binary16 residual (attention-out, FFN-down), GELU with
+# codes out (FFN-up)
+EPILOGUES = [(M, K, N, kind) for M in (1024, 4096)
+             for (K, N, kind) in ((768, 768, "residual"), (768, 3072, "gelu"), (3072, 768, "residual"))]
+
+
+@pytest.mark.parametrize("M,K,N,kind", [s + ("plain",) for s in SHAPES] + EPILOGUES)
+def test_automatic_choice_is_within_five_percent_of_the_best(M, K, N, kind):
     import torch
     import paper_2203_13483_amd as mkq
     mkq.load()
@@ -42,9 +48,14 @@ def test_automatic_choice_is_within_five_percent_of_the_best(M, K, N):
     w = torch.randint(0, 256, (N * K // 2,), dtype=torch.uint8, device="cuda")
     sw = torch.rand(N, device="cuda") * 0.049 + 0.001
     out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    res = torch.randn((M, N), dtype=torch.float16, device="cuda") if kind == "residual" else None
+    codes = torch.empty((M, N // 2), dtype=torch.uint8, device="cuda")
 
     def run(cfg):
-        return lambda: mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_F16, out=out, config=cfg)
+        if kind == "gelu":
+            return lambda: mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_I4, out=codes, act=mkq.MKQ_ACT_GELU,
+                                               s_next=0.3, config=cfg)
+        return lambda: mkq.mkq_linear_int4(a, 0.01, w, sw, None, N, K, mkq.MKQ_F16, out=out, residual=res, config=cfg)
 
     times = {}
     for cfg in CONFIGS:
@@ -61,6 +72,6 @@ def test_automatic_choice_is_within_five_percent_of_the_best(M, K, N):
     for _ in range(3):
         auto = min(auto, _time(run(None)))
         times[best_cfg] = min(times[best_cfg], _time(run(best_cfg)))
-    print(f"M={M} K={K} N={N}: automatic {auto * 1e3:.2f} us, best forced {best_cfg}: {times[best_cfg] * 1e3:.2f} us; "
+    print(f"M={M} K={K} N={N} {kind}: automatic {auto * 1e3:.2f} us, best forced {best_cfg}: {times[best_cfg] * 1e3:.2f} us; "
           + " ".join(f"{c}:{t * 1e3:.1f}" for c, t in sorted(times.items())))
     assert auto <= 1.05 * times[best_cfg] + 0.0003, (auto, best_cfg, times[best_cfg])
