@@ -215,6 +215,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
     // stage Q, K (row-major, swizzled chunks) and V (transposed): all of a thread's loads are issued
     // before the first LDS write, so the tile arrives in one memory round trip
     constexpr int PER_T = SMAX * 8 / 256;  // 16-byte chunks of each of q, k, v per thread
+    // With an even number of chunks per thread the v chunks of a thread are the same columns of two neighbouring
+    // rows (chunks 2i, 2i + 1), so the transposition writes the two keys of a head dimension with one LDS store.
+    constexpr bool PAIRS = (PER_T % 2) == 0;
+    auto v_row = [&](int i) { return PAIRS ? 2 * ((tid + (i >> 1) * 256) >> 3) + (i & 1) : (tid + i * 256) >> 3; };
+    auto v_col = [&](int i) { return PAIRS ? (tid + (i >> 1) * 256) & 7 : (tid + i * 256) & 7; };
     uint4 qv[PER_T], kv[PER_T], vv[PER_T];
 #pragma unroll
     for (int i = 0; i < PER_T; ++i) {
@@ -223,7 +228,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
         const uint16_t *src = qkv + (row0 + (r < seq ? r : seq - 1)) * ld + head * DK + c * 8;
         qv[i] = *reinterpret_cast<const uint4 *>(src);
         kv[i] = *reinterpret_cast<const uint4 *>(src + hidden);
-        vv[i] = *reinterpret_cast<const uint4 *>(src + 2 * hidden);
+        const int rv = v_row(i);
+        vv[i] = *reinterpret_cast<const uint4 *>(qkv + (row0 + (rv < seq ? rv : seq - 1)) * ld + 2 * hidden + head * DK +
+                                                 v_col(i) * 8);
     }
 #pragma unroll
     for (int i = 0; i < PER_T; ++i) {
@@ -232,13 +239,27 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
         const int slot = (c ^ swz<8>(r & 15)) * 16;
         *reinterpret_cast<uint4 *>(sQ + r * 128 + slot) = qv[i];
         *reinterpret_cast<uint4 *>(sK + r * 128 + slot) = kv[i];
-        const uint32_t w[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
+        if constexpr (PAIRS) {
+            if (i & 1) continue;  // (chunks 2i and 2i + 1 go together)
+            const int rv = v_row(i), cv = v_col(i);
+            const uint32_t w0[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
+            const uint32_t w1[4] = {vv[i | 1].x, vv[i | 1].y, vv[i | 1].z, vv[i | 1].w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int d = c * 8 + e;
-            const uint16_t val = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-            const int vslot = ((r >> 3) ^ (d & (VCHP - 1))) * 16;
-            *reinterpret_cast<uint16_t *>(sVt + d * VROW + vslot + (r & 7) * 2) = val;
+            for (int e = 0; e < 8; ++e) {
+                const int d = cv * 8 + e;
+                const uint32_t lo = (w0[e >> 1] >> (16 * (e & 1))) & 0xFFFFu, hi = (w1[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                const int vslot = ((rv >> 3) ^ (d & (VCHP - 1))) * 16;
+                *reinterpret_cast<uint32_t *>(sVt + d * VROW + vslot + (rv & 7) * 2) = lo | (hi << 16);
+            }
+        } else {
+            const uint32_t w[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int d = c * 8 + e;
+                const uint16_t val = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                const int vslot = ((r >> 3) ^ (d & (VCHP - 1))) * 16;
+                *reinterpret_cast<uint16_t *>(sVt + d * VROW + vslot + (r & 7) * 2) = val;
+            }
         }
     }
     __syncthreads();
@@ -263,23 +284,25 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
         }
     }
     // register v of tile kt is key kt*32 + 16*(v/8) + 8*fh + v%8; keys >= seq do not exist
-    const float scale = 0.125f;  // 1/sqrt(64)
-    float mx = -3.0e38f;
+    // exp(x / sqrt(64) - max) as exp2(x c - max c): one multiply-add and one exponential per score
+    const float c_exp = 0.125f * 1.4426950408889634f;
+    float mx = -1.0e30f;
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int key = kt * 32 + 16 * (v / 8) + 8 * fh + (v % 8);
-            sc[kt][v] = (key < seq) ? sc[kt][v] * scale : -3.0e38f;
+            sc[kt][v] = (key < seq) ? sc[kt][v] : -1.0e30f;
             mx = fmaxf(mx, sc[kt][v]);
         }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float shift = -mx * c_exp;
     float den = 0.0f;
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            sc[kt][v] = exp2f((sc[kt][v] - mx) * 1.4426950408889634f);
+            sc[kt][v] = __builtin_amdgcn_exp2f(__fmaf_rn(sc[kt][v], c_exp, shift));
             den += sc[kt][v];
         }
     den += __shfl_xor(den, 32, 64);
