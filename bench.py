@@ -247,8 +247,30 @@ def main():
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(A, Wc, s_w, s_x, rows=16384)
+    if not args.no_extra:
+        res["summary"] = summary(extra)
     res["extra"] = extra
     print(json.dumps(res))
+
+
+def summary(extra):
+    """The target-bearing side measurements in short form, ahead of the long `extra` object: fractions of the
+    published peaks (int8 matrix 5000 TOP/s, HBM 8000 GB/s) and, second, of the ceilings measured in this run."""
+    r3 = lambda v: None if v is None else round(v, 3)
+    out = {"large_m_MKN_frac_int8_peak_frac_measured_ceiling_e3m2_route_frac": [
+               [r["M"], r["K"], r["N"], r3(r["frac_int8_peak"]), r3(r["frac_measured_mfma_ceiling"]),
+                r3(r.get("e3m2_route_frac_int8_peak"))] for r in extra.get("large_m", [])],
+           "small_m_MKN_layout_us_frac_hbm_peak_frac_measured_read": []}
+    for r in extra.get("small_m", []):
+        for layout in ("canonical", "stream"):
+            if layout + "_us_per_call" in r:
+                out["small_m_MKN_layout_us_frac_hbm_peak_frac_measured_read"].append(
+                    [r["M"], r["K"], r["N"], layout, round(r[layout + "_us_per_call"], 1), r3(r[layout + "_frac_hbm_peak"]),
+                     r3(r[layout + "_frac_measured_read_ceiling"])])
+    enc = extra.get("encoder") or {}
+    out["bert_base_layer_us_int4_int8_fp16"] = [r3(enc.get("int4_us_per_layer")), r3(enc.get("int8_us_per_layer")),
+                                                r3(enc.get("fp16_us_per_layer"))]
+    return out
 
 
 # (M, K, N): BASELINE configs[4] and, last, a long-K square where the k loop outweighs the per-tile costs
