@@ -489,6 +489,32 @@ def side_measurements(mkq, event_time, ceil):
             del a, out
         del ws
 
+    # The same protocol for the 8-bit linear (one byte per code): few tokens take the register-streaming kernel too
+    res["small_m_int8"] = []
+    for (K, N, pool, Ms) in ((4096, 4096, 64, (1, 16, 64)), (8192, 8192, 16, (16,))):
+        ws8 = [torch.randint(-128, 128, (N, K), dtype=torch.int8, device="cuda") for _ in range(pool)]
+        sw = torch.rand(N, device="cuda") * 0.049 + 0.001
+        for M in Ms:
+            a8 = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda")
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            nbytes = M * K + N * K + 8 * N + 2 * M * N
+
+            def sweep8():
+                for w in ws8:
+                    mkq.mkq_linear_int8(a8, 0.01, w, sw, None, mkq.MKQ_F16, out=out)
+
+            sweep8()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                sweep8()
+            t = sorted(event_time(g.replay, 5, warm=1) for _ in range(5))[2] / pool
+            res["small_m_int8"].append({"M": M, "K": K, "N": N, "weight_MiB": N * K >> 20, "algorithmic_bytes": nbytes,
+                                        "us_per_call": t * 1e6, "GBps": nbytes / t / 1e9,
+                                        "frac_hbm_peak": nbytes / t / 1e9 / HBM_PEAK_GBS})
+            del g, a8, out
+        del ws8
+
     # Scale machinery (streaming reductions, HBM-bound): one read of x per pass
     res["calibration"] = []
     M, K = CALIBRATION_SHAPE

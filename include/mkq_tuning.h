@@ -41,6 +41,12 @@ int mkq_tuning_linear_int4_stream(const void *a, int a_dtype, float s_x, const u
                                   const mkq_epilogue *epi, void *workspace, size_t workspace_bytes, void *stream,
                                   int prefetch_stages, int k_slices);
 
+/* mkq_linear_int8 with config -1 (the library's choice), 18 (256x128 tiles), 29 (128x128), 28 (128x64), 27 (64x64)
+ * or 30 (few-token weight-streaming kernel: M <= 64, K % 128 == 0). */
+int mkq_tuning_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w, const float *bias,
+                           int64_t M, int64_t N, int64_t K, void *out, int out_dtype, const mkq_epilogue *epi,
+                           void *stream, int config);
+
 /* mkq_linear_int4_e3m2 with config -1 (the library's choice), 41 (256x256 tiles, eight waves) or
  * 42 (256x128 tiles, four waves, two workgroups per compute unit). */
 int mkq_tuning_linear_int4_e3m2(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,

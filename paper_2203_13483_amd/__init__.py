@@ -30,7 +30,7 @@ EXPORTS = [
     "mkq_linear_fp16", "mkq_bert_layer_workspace", "mkq_bert_layer_int4",
     "mkq_bert_layer_fp16_workspace_bytes", "mkq_bert_layer_fp16", "mkq_layernorm", "mkq_attention",
     "mkq_splitk_scratch_bytes", "mkq_splitk_scratch_init", "mkq_init",
-    "mkq_tuning_linear_int4", "mkq_tuning_linear_int4_e3m2", "mkq_tuning_linear_int4_stream",
+    "mkq_tuning_linear_int4", "mkq_tuning_linear_int4_e3m2", "mkq_tuning_linear_int4_stream", "mkq_tuning_linear_int8",
     "mkq_stream_weight_bytes", "mkq_repack_weights_int4_stream", "mkq_linear_int4_stream",
     "mkq_linear_int4_stream_static",
     "mkq_measure_stream", "mkq_measure_mfma_i8_operand_bytes", "mkq_measure_mfma_i8_ops", "mkq_measure_mfma_i8",
@@ -126,6 +126,7 @@ def load() -> C.CDLL:
         "mkq_quantize_int8": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
         "mkq_pack_weights_int8": (ci, [vp, i64, i64, vp, vp, vp, vp]),
         "mkq_linear_int8": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp]),
+        "mkq_tuning_linear_int8": (ci, [vp, f32, vp, vp, vp, i64, i64, i64, vp, ci, C.POINTER(Epilogue), vp, ci]),
         "mkq_linear_fp16": (ci, [vp, vp, vp, i64, i64, i64, vp, ci, ci, vp, vp]),
         "mkq_quantize_e3m2": (ci, [vp, ci, i64, i64, i64, f32, vp, vp]),
         "mkq_pack_codes_e3m2": (ci, [vp, i64, i64, vp, vp]),
@@ -455,8 +456,9 @@ def mkq_pack_weights_int8(W, s_w_in=None, stream=None):
 
 
 def mkq_linear_int8(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, act: int = MKQ_ACT_NONE,
-                    residual=None, s_next: float = 0.0, want_acc: bool = False, out=None, stream=None):
-    """The 8-bit linear: ``a`` int8 codes [M,K], ``Wq`` int8 codes [N,K]."""
+                    residual=None, s_next: float = 0.0, want_acc: bool = False, out=None, stream=None,
+                    config: int | None = None):
+    """The 8-bit linear: ``a`` int8 codes [M,K], ``Wq`` int8 codes [N,K].  ``config``: mkq_tuning_linear_int8."""
     torch = _torch()
     M, K = a.shape
     N = Wq.shape[0]
@@ -467,8 +469,13 @@ def mkq_linear_int8(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, a
     epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
                    residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
                    s_next=float(s_next), q_out=None, acc_out=acc.data_ptr() if acc is not None else None)
-    _check(load().mkq_linear_int8(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
-                                  int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int8")
+    if config is None:
+        _check(load().mkq_linear_int8(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
+                                      int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int8")
+    else:
+        _check(load().mkq_tuning_linear_int8(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
+                                             int(out_dtype), C.byref(epi), _stream(stream), int(config)),
+               "mkq_tuning_linear_int8")
     return {"out": out, "acc": acc}
 
 

@@ -764,7 +764,8 @@ struct SkinnyCfg {
     static constexpr int WTM = 32, WTN = 32, TM = 1, TN = 1;
 };
 
-template <int TB, int UG>
+// BITS = 8: the operands are int8 codes (the 8-bit linear): a 16-byte piece is one MFMA operand as it is.
+template <int TB, int UG, int BITS = 4>
 __global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(const GemmI4Params p)
 {
     __shared__ __attribute__((aligned(16))) int red[2][SkinnyCfg::WAVES][4][64][4];  // 64 KiB
@@ -774,8 +775,8 @@ __global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(cons
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int fr = lane & 31, fh = lane >> 5;
     const int n0 = blockIdx.x * 32;
-    const int row_bytes = p.K / 2;
-    // A row is cut into groups of 128 bytes (256 codes), one cache line; a lane fetches
+    const int row_bytes = p.K * BITS / 8;
+    // A row is cut into groups of 128 bytes (256 4-bit codes), one cache line; a lane fetches
     // 64 contiguous bytes of its row per group (four 16-byte loads = eight k steps), so the
     // four loads of a group touch the same 32 lines.  Which codes a lane holds does not
     // matter to the dot product as long as weights and activations agree.
@@ -829,11 +830,20 @@ __global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(cons
 #pragma unroll
         for (int u = 0; u < NL; ++u) {
             if (g0 + u / 4 < g_end) {
-                const v4i w0 = widen(fw[buf][u].x, fw[buf][u].y), w1 = widen(fw[buf][u].z, fw[buf][u].w);
+                if constexpr (BITS == 8) {
+                    const v4i w = {(int)fw[buf][u].x, (int)fw[buf][u].y, (int)fw[buf][u].z, (int)fw[buf][u].w};
 #pragma unroll
-                for (int tb = 0; tb < TB; ++tb) {
-                    acc[tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w0, widen(fa[buf][tb][u].x, fa[buf][tb][u].y), acc[tb], 0, 0, 0);
-                    acc[tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, widen(fa[buf][tb][u].z, fa[buf][tb][u].w), acc[tb], 0, 0, 0);
+                    for (int tb = 0; tb < TB; ++tb) {
+                        const v4i a = {(int)fa[buf][tb][u].x, (int)fa[buf][tb][u].y, (int)fa[buf][tb][u].z, (int)fa[buf][tb][u].w};
+                        acc[tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, a, acc[tb], 0, 0, 0);
+                    }
+                } else {
+                    const v4i w0 = widen(fw[buf][u].x, fw[buf][u].y), w1 = widen(fw[buf][u].z, fw[buf][u].w);
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb) {
+                        acc[tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w0, widen(fa[buf][tb][u].x, fa[buf][tb][u].y), acc[tb], 0, 0, 0);
+                        acc[tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, widen(fa[buf][tb][u].z, fa[buf][tb][u].w), acc[tb], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -881,12 +891,19 @@ __global__ __launch_bounds__(SkinnyCfg::THREADS) void gemm_i4_skinny_kernel(cons
     }
 }
 
-template <int TB, int UG>
+template <int TB, int UG, int BITS = 4>
 static int launch_skinny(const GemmI4Params &p, hipStream_t st)
 {
     if (p.setup_only) return MKQ_OK;
-    gemm_i4_skinny_kernel<TB, UG><<<(unsigned)ceil_div(p.N, 32), SkinnyCfg::THREADS, 0, st>>>(p);
+    gemm_i4_skinny_kernel<TB, UG, BITS><<<(unsigned)ceil_div(p.N, 32), SkinnyCfg::THREADS, 0, st>>>(p);
     return launch_status();
+}
+
+// The same kernel on int8 codes (rows of K bytes: K % 128 == 0), M <= 64.
+static int run_gemm_i8_skinny(const GemmI4Params &p, hipStream_t st)
+{
+    if (p.M <= 32) return p.K >= 4096 ? launch_skinny<1, 1, 8>(p, st) : launch_skinny<1, 2, 8>(p, st);
+    return launch_skinny<2, 2, 8>(p, st);
 }
 
 static int run_gemm_i4_skinny(const GemmI4Params &p, hipStream_t st)
@@ -1128,6 +1145,12 @@ static int launch_i8_by_epilogue(const GemmI4Params &p, int epi, hipStream_t st)
 int run_gemm_i8(const GemmI4Params &p, hipStream_t st, int forced_cfg = -1)
 {
     if ((p.K % 64) != 0) return MKQ_ERR_UNSUPPORTED;
+    // few tokens: the linear is a stream of the weight matrix (the tile kernels take 24 us for 16 MiB of
+    // weights where this takes 8)
+    if (forced_cfg == 30) return (p.M <= 64 && (p.K % 128) == 0) ? run_gemm_i8_skinny(p, st) : MKQ_ERR_UNSUPPORTED;
+    // (33 .. 64 tokens only against at least 4 MiB of weights: below that the tile kernels are 10-20 % faster)
+    if (forced_cfg < 0 && (p.K % 128) == 0 && (p.M <= 32 || (p.M <= 64 && (int64_t)p.N * p.K >= ((int64_t)4 << 20))))
+        return run_gemm_i8_skinny(p, st);
     int epi = classify_epilogue(p);
     if (epi == EPI_I4 || epi == EPI_I4_GELU) epi = EPI_GENERIC;
     switch (forced_cfg >= 0 ? forced_cfg : choose_tiles(p)) {
@@ -1711,9 +1734,9 @@ extern "C" int mkq_tuning_linear_int4_stream(const void *a, int a_dtype, float s
                            workspace_bytes, stream, have ? &scr : nullptr, prefetch_stages, k_slices, W_STREAM);
 }
 
-extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w,
-                               const float *bias, int64_t M, int64_t N, int64_t K, void *out,
-                               int out_dtype, const mkq_epilogue *epi, void *stream)
+static int linear_int8_run(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w, const float *bias,
+                           int64_t M, int64_t N, int64_t K, void *out, int out_dtype, const mkq_epilogue *epi,
+                           void *stream, int forced_cfg)
 {
     const bool want_acc = epi && epi->acc_out;
     if (out_dtype == MKQ_I4 || (epi && epi->q_out)) return MKQ_ERR_UNSUPPORTED;
@@ -1755,7 +1778,23 @@ extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, con
     p.q_pitch = (int)q_pitch;
     p.acc_shift = 0;   // byte operands enter the MFMA as they are
     p.acc_unit = 1.0f;
-    return run_gemm_i8(p, as_stream(stream));
+    return run_gemm_i8(p, as_stream(stream), forced_cfg);
+}
+
+extern "C" int mkq_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w,
+                               const float *bias, int64_t M, int64_t N, int64_t K, void *out,
+                               int out_dtype, const mkq_epilogue *epi, void *stream)
+{
+    return linear_int8_run(a, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, epi, stream, -1);
+}
+
+extern "C" int mkq_tuning_linear_int8(const int8_t *a, float s_x, const int8_t *Wq, const float *s_w,
+                                      const float *bias, int64_t M, int64_t N, int64_t K, void *out,
+                                      int out_dtype, const mkq_epilogue *epi, void *stream, int config)
+{
+    if (config != -1 && config != 18 && config != 27 && config != 28 && config != 29 && config != 30)
+        return MKQ_ERR_UNSUPPORTED;
+    return linear_int8_run(a, s_x, Wq, s_w, bias, M, N, K, out, out_dtype, epi, stream, config);
 }
 
 static int linear_int4_e3m2_run(const uint8_t *a, float s_x, const uint8_t *Wq, const float *s_w,

@@ -291,3 +291,16 @@ def test_ceiling_probe_argument_errors(lib):
     assert mm(P, 1 << 20, 4, None, None) == mkq.MKQ_ERR_NULL
     assert mm(ODD, 1 << 20, 4, P, None) == mkq.MKQ_ERR_ALIGN
     assert mm(P, 1 << 20, 0, P, None) == mkq.MKQ_ERR_SHAPE
+
+
+def test_int8_tuning_argument_errors(lib):
+    t = lib.mkq_tuning_linear_int8
+    t.restype = C.c_int
+    t.argtypes = [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                  C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int]
+    assert t(P, 0.1, P, P, None, 16, 64, 128, P, mkq.MKQ_F16, None, None, 999) == mkq.MKQ_ERR_UNSUPPORTED   # no such configuration
+    assert t(P, 0.1, P, P, None, 16, 64, 96, P, mkq.MKQ_F16, None, None, 30) == mkq.MKQ_ERR_SHAPE           # K % 64 comes first
+    assert t(P, 0.1, P, P, None, 16, 64, 192, P, mkq.MKQ_F16, None, None, 30) == mkq.MKQ_ERR_UNSUPPORTED    # streaming: K % 128
+    assert t(P, 0.1, P, P, None, 65, 64, 128, P, mkq.MKQ_F16, None, None, 30) == mkq.MKQ_ERR_UNSUPPORTED    # streaming: M <= 64
+    assert t(None, 0.1, P, P, None, 16, 64, 128, P, mkq.MKQ_F16, None, None, 30) == mkq.MKQ_ERR_NULL
+    assert t(P, 0.0, P, P, None, 16, 64, 128, P, mkq.MKQ_F16, None, None, 27) == mkq.MKQ_ERR_SCALE

@@ -229,6 +229,42 @@ def test_linear_int8_code_output_with_gelu(mkq):
     assert ref["q"].min() == -128 and ref["q"].max() == 127
 
 
+# Few tokens (M <= 64, K % 128 == 0) take the weight-streaming kernel: eight waves split K, ragged N, K that does not
+# divide evenly over the waves, the accumulator extremes, every kind of output
+@pytest.mark.parametrize("M", [1, 16, 33, 64])
+@pytest.mark.parametrize("N,K", [(200, 128), (40, 512), (768, 768), (328, 4096), (96, 2304), (72, 8192), (3072, 768)])
+def test_few_token_linear_int8(mkq, M, N, K):
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M * 3 + N + K)
+    if N == 40:  # the extremes: |acc| = K * 128 * 128
+        A[:] = -128
+        Wc[: N // 2] = -128
+        Wc[N // 2:] = 127
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, **Q8)
+    r = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(s_w), to_dev(bias), mkq.MKQ_F32, want_acc=True)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]), ref["y"])
+    # (the library's own route takes the tile kernels for 33 .. 64 tokens against small weights: the streaming
+    # kernel is also asked for by number)
+    r30 = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(s_w), to_dev(bias), mkq.MKQ_F32, want_acc=True,
+                              config=30)
+    assert np.array_equal(to_np(r30["acc"]), ref["acc"]) and np.array_equal(to_np(r30["out"]), ref["y"])
+    if N == 40:
+        assert ref["acc"].max() == K * 128 * 128 and ref["acc"].min() == -K * 128 * 127
+    res = np.random.default_rng(N).normal(0, 1, (M, N)).astype(np.float16)
+    ref16 = oracle.linear_int4(A, s_x, Wc, s_w, bias, residual=res.astype(np.float32), out_dtype=oracle.F16, **Q8)
+    r16 = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(s_w), to_dev(bias), mkq.MKQ_F16, residual=to_dev(res))
+    assert np.array_equal(to_np(r16["out"]).astype(np.float32), ref16["y"])
+    s_next = float(np.float32(max(np.abs(ref["y"]).max(), 1e-3) / 100))
+    refq = oracle.linear_int4(A, s_x, Wc, s_w, bias, s_next=s_next, **Q8)
+    rq = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(s_w), to_dev(bias), mkq.MKQ_I8, s_next=s_next)
+    assert np.array_equal(to_np(rq["out"]), refq["q"])
+    refg = oracle.linear_int4(A, s_x, Wc, s_w, bias, act=oracle.ACT_GELU, s_next=s_next, **Q8)
+    rg = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(s_w), to_dev(bias), mkq.MKQ_I8,
+                             act=mkq.MKQ_ACT_GELU, s_next=s_next)
+    assert_codes_match_with_tie_band(to_np(rg["out"]), refg["q"], refg["y"], s_next, band=2.0 ** -7, max_frac=2e-3,
+                                     what="gelu codes")
+
+
 @pytest.mark.parametrize("B,S,hidden,heads,ffn", [(2, 64, 128, 2, 256), (2, 128, 768, 12, 3072), (1, 300, 512, 16, 1024), (1, 512, 256, 4, 512)])
 def test_bert_layer_int8_stagewise_and_end_to_end(mkq, B, S, hidden, heads, ffn):
     import torch
