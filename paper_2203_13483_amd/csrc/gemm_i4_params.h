@@ -400,13 +400,26 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
                     int cd[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(y[e], qs8);
-                    if (ok) *reinterpret_cast<uint2 *>((uint8_t *)p.out + o) = bytes8(cd);
+                    // code rows may have a pitch; the lane that owns a row's last 8 channels writes its zero padding
+                    const int pitch = p.q_pitch ? p.q_pitch : p.N;
+                    uint2 *dst = reinterpret_cast<uint2 *>((uint8_t *)p.out + (int64_t)m * pitch + n);
+                    if (ok) {
+                        *dst = bytes8(cd);
+                        if (n + 8 == p.N)
+                            for (int c = 8; c < pitch - n; c += 8) dst[c / 8] = make_uint2(0u, 0u);
+                    }
                 } else {
                     uint32_t packed = 0;  // Eq. 1 on the binary32 value
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
                         packed |= ((uint32_t)quantize_code_rs<4>(y[e], qs4) & 0xFu) << (4 * e);
-                    if (ok) *reinterpret_cast<uint32_t *>((uint8_t *)p.out + (o >> 1)) = packed;
+                    const int pitch = p.q_pitch ? p.q_pitch : p.N;
+                    uint32_t *dst = reinterpret_cast<uint32_t *>((uint8_t *)p.out + (((int64_t)m * pitch + n) >> 1));
+                    if (ok) {
+                        *dst = packed;
+                        if (n + 8 == p.N)
+                            for (int c = 8; c < pitch - n; c += 8) dst[c / 8] = 0u;
+                    }
                 }
             }
         });
@@ -504,7 +517,7 @@ enum { EPI_F16 = 0, EPI_BF16, EPI_F32, EPI_F16_RES16, EPI_I4_GELU, EPI_I4, EPI_I
 
 inline int classify_epilogue(const GemmI4Params &p)
 {
-    if ((p.N % 8) != 0 || p.acc_out || p.q_out || (p.q_pitch && p.q_pitch != p.N)) return EPI_GENERIC;
+    if ((p.N % 8) != 0 || p.acc_out || p.q_out) return EPI_GENERIC;
     const bool res16 = p.residual && p.residual_dtype == MKQ_F16;
     const bool gelu = p.act == MKQ_ACT_GELU;
     if (p.residual && !res16) return EPI_GENERIC;
