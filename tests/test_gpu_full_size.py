@@ -298,3 +298,26 @@ def test_ffn_down_shapes_split_k_tiles_sampled_rows(mkq, M, K, N):
     got = to_np(out[torch.from_numpy(rows).cuda()]).astype(np.float32)
     ref = oracle.linear_int4(A[rows], s_x, Wc, s_w, b, residual=res[rows].astype(np.float32), out_dtype=oracle.F16)
     assert np.array_equal(got, ref["y"])
+
+
+@pytest.mark.parametrize("M,K,N", [(16, 16384, 16384), (64, 16384, 16384), (16, 8192, 28672), (1, 28672, 8192)])
+def test_few_token_streaming_at_benchmark_sizes(mkq, M, K, N):
+    """The few-token points of the benchmark (112-128 MiB of weights, both weight layouts, the K split with the
+    scratch area that the benchmark hands over): whole output against the oracle."""
+    rng = np.random.default_rng(M + K + N)
+    A = rng.integers(-8, 8, (M, K), dtype=np.int8)
+    Wc = rng.integers(-8, 8, (N, K), dtype=np.int8)
+    s_w = rng.uniform(0.001, 0.05, N).astype(np.float32)
+    s_x = 0.01
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, None, out_dtype=oracle.F16)
+    a_d = mkq.mkq_pack_codes_int4(to_dev(A))
+    w_d = _pack_rows_on_device(mkq, Wc).reshape(-1)
+    scr = mkq.mkq_splitk_scratch_init()
+    r = mkq.mkq_linear_int4(a_d, s_x, w_d, to_dev(s_w), None, N, K, mkq.MKQ_F16, splitk_scratch=scr, want_acc=True)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
+    w_s = mkq.mkq_repack_weights_int4_stream(w_d, N, K)
+    del w_d
+    r = mkq.mkq_linear_int4_stream(a_d, s_x, w_s, to_dev(s_w), None, N, K, mkq.MKQ_F16, splitk_scratch=scr, want_acc=True)
+    assert np.array_equal(to_np(r["acc"]), ref["acc"])
+    assert np.array_equal(to_np(r["out"]).astype(np.float32), ref["y"])
