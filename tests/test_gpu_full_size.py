@@ -300,9 +300,9 @@ def test_ffn_down_shapes_split_k_tiles_sampled_rows(mkq, M, K, N):
     assert np.array_equal(got, ref["y"])
 
 
-@pytest.mark.parametrize("M,K,N", [(16, 16384, 16384), (64, 16384, 16384), (16, 8192, 28672), (1, 28672, 8192)])
+@pytest.mark.parametrize("M,K,N", [(16, 16384, 16384), (64, 16384, 16384), (16, 8192, 28672), (1, 28672, 8192), (16, 32768, 32768)])
 def test_few_token_streaming_at_benchmark_sizes(mkq, M, K, N):
-    """The few-token points of the benchmark (112-128 MiB of weights, both weight layouts, the K split with the
+    """The few-token points of the benchmark (112-512 MiB of weights, both weight layouts, the K split with the
     scratch area that the benchmark hands over): whole output against the oracle."""
     rng = np.random.default_rng(M + K + N)
     A = rng.integers(-8, 8, (M, K), dtype=np.int8)
