@@ -1,6 +1,7 @@
 """The library's own choice of kernel configuration against every configuration it could have picked, at the
 benchmark's shapes: the automatic choice must not be more than 5 % (plus timer noise) slower than the fastest
-forced configuration.  A timing test: medians of graph replays, on an otherwise idle GPU."""
+forced configuration.  A timing test: medians of graph replays, on an otherwise idle GPU (the file's name puts it
+behind the parity tests: a noisy machine must not keep them from running)."""
 import pytest
 
 pytestmark = pytest.mark.gpu
@@ -67,9 +68,9 @@ def test_automatic_choice_is_within_five_percent_of_the_best(M, K, N, kind):
         times[cfg] = _time(run(cfg))
     best_cfg = min(times, key=times.get)
     # the clock moves between measurements (the sweep above heats the chip): the two that are compared are timed
-    # again side by side, three times, and each keeps its fastest sample
+    # again side by side, five times, and each keeps its fastest sample
     auto = float("inf")
-    for _ in range(3):
+    for _ in range(5):
         auto = min(auto, _time(run(None)))
         times[best_cfg] = min(times[best_cfg], _time(run(best_cfg)))
     print(f"M={M} K={K} N={N} {kind}: automatic {auto * 1e3:.2f} us, best forced {best_cfg}: {times[best_cfg] * 1e3:.2f} us; "
