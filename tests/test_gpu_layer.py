@@ -387,3 +387,26 @@ def test_layers_on_a_padding_free_batch(mkq, kind):
             ref, _ = oracle.bert_layer_int4(q, x, act_dtype=oracle.F16, **qr)
             err = out[rows] - ref
             assert np.sqrt((err ** 2).mean()) < 0.04 * np.sqrt((ref ** 2).mean()), (b, int(lens[b]))
+
+
+@pytest.mark.parametrize("heads,dk,max_seq", [(2, 64, 512), (12, 26, 300), (2, 64, 128)])
+def test_attention_with_empty_and_one_token_sequences(mkq, heads, dk, max_seq):
+    """A padding-free batch may hold empty sequences (skipped) and sequences of one token (softmax of one score)."""
+    H = heads * dk
+    lens = np.array([5, 0, 1, min(max_seq, 290), 0, 33])
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(lens.sum())
+    rng = np.random.default_rng(heads + dk)
+    qkv = _f16(rng.normal(0, 1.0, (total, 3 * H)))
+    ctx, q = mkq.mkq_attention_varlen(to_dev(qkv), to_dev(cu), max_seq, H, heads, s_next=0.05, q_bits=4)
+    got, codes = to_np(ctx).astype(np.float32), oracle.unpack_nibbles(to_np(q), H)
+    for b, n in enumerate(lens):
+        if n == 0:
+            continue
+        rows = slice(cu[b], cu[b + 1])
+        ref = oracle.attention(qkv[rows].astype(np.float32), 1, int(n), H, heads, p_dtype=oracle.F16)
+        assert_float_close(got[rows], ref, RTOL[1], f"sequence {b} of length {n}")
+        codes_match(codes[rows], oracle.quantize(ref, 0.05), ref, 0.05,
+                    attention_code_band(qkv[rows].astype(np.float32), int(n), H, heads, 0.05), "context codes")
+    one = slice(cu[2], cu[3])  # one token: the context is that token's v
+    assert np.array_equal(got[one], qkv[one, 2 * H:].astype(np.float32))
