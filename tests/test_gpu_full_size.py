@@ -260,6 +260,49 @@ def test_twelve_layer_encoder_chain_teacher_forced(mkq):
     assert drift < 0.15
 
 
+def test_student_four_layer_chain_teacher_forced(mkq):
+    """The 4-layer student (hidden 312, 12 heads of 26, FFN 1200) at 32 x 128 tokens, chained through
+    q_out_next / q_in: the code rows that cross from layer to layer have a pitch of 384 codes with zero padding.
+    Every stage of every layer against the oracle on two sequences, each layer fed the GPU's previous output."""
+    import torch
+    from layer_checks import code_row_pitch
+    B, S, H, heads, F, LAYERS = 32, 128, 312, 12, 1200, 4
+    M, pitch = B * S, code_row_pitch(H)
+    steps = {"qkv": wl.LEARNED_STEP_UNIT_GAUSSIAN, "ao": 0.05, "up": wl.LEARNED_STEP_UNIT_GAUSSIAN, "down": 0.05}
+    s_next = steps["qkv"]
+    h0 = wl.hidden_states(B, S, H, 5).astype(np.float16)
+    layers = []
+    for l in range(LAYERS):
+        p = wl.bert_layer_weights(H, heads, F, 200 + l)
+        packed, q = {}, {k: p[k] for k in ("hidden", "heads", "ffn", "ln_eps", "ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+        for nm in ("qkv", "ao", "up", "down"):
+            Wq, s_w = mkq.mkq_pack_weights_int4_padded(to_dev(p["W_" + nm]))
+            packed[nm] = (Wq, s_w, to_dev(p["b_" + nm]))
+            q["w_" + nm], q["sw_" + nm] = oracle.quantize_weights(p["W_" + nm])
+            q["b_" + nm], q["sx_" + nm] = p["b_" + nm], steps[nm]
+        ln = {k: to_dev(p[k]) for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta")}
+        layers.append((mkq.BertLayerInt4(B, S, H, heads, F, packed, steps, ln, p["ln_eps"], s_next), q))
+    ws = [torch.full((layers[0][0].workspace_bytes(),), 0x3C, dtype=torch.uint8, device="cuda") for _ in range(LAYERS)]
+    hs = [torch.empty((M, H), dtype=torch.float16, device="cuda") for _ in range(LAYERS)]
+    qs = [torch.full((M, pitch // 2), 0x3C, dtype=torch.uint8, device="cuda") for _ in range(LAYERS)]
+    x, qin = to_dev(h0), None
+    for l, (layer, _) in enumerate(layers):
+        layer(x, ws[l], h_out=hs[l], q_in=qin, q_out_next=qs[l])
+        x, qin = hs[l], qs[l]
+    torch.cuda.synchronize()
+    seqs = [(0, S), (17 * S, S)]
+    h_prev, c_prev, flips = h0.astype(np.float32), None, 0
+    for l, (layer, q) in enumerate(layers):
+        buf = LayerBuffers(to_np(ws[l]), layer.layout, M, H, F, 4)
+        h_out = to_np(hs[l]).astype(np.float32)
+        rows = oracle.unpack_nibbles(to_np(qs[l]), pitch)
+        assert not rows[:, H:].any(), "padding codes handed to the next layer must be zero"
+        flips += check_layer_stagewise(buf, q, h_prev, h_out, seqs, c0_in=c_prev, q_next=rows[:, :H], s_out_next=s_next,
+                                       what=f"student layer {l}")
+        h_prev, c_prev = h_out, rows[:, :H]
+    assert np.isfinite(to_np(hs[-1]).astype(np.float32)).all()
+
+
 @pytest.mark.parametrize("M", [440, 537, 681, 1691, 2011, 2298])
 @pytest.mark.parametrize("K,N", [(768, 2304), (3072, 768)])
 def test_padding_free_token_counts(mkq, M, K, N):
