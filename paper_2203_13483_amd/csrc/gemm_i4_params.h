@@ -321,6 +321,26 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
         for (int h = 0; h < 2; ++h) rd_off[i][h] = r * 128 + (((2 * pc + h) ^ (r & 7)) * 16);
     }
 
+    // 16-bit residual: the two rows a lane needs of a 32 x 32 unit are fetched RES_AHEAD units before
+    // they are used (units in the order they are processed, j fastest), so that their latency is covered
+    // by the units in between instead of being waited for in every unit.
+    constexpr int RES_AHEAD = 2, UNITS = TN * TM;
+    uint4 res_q[RES_AHEAD][2];
+    auto fetch_residual = [&](auto uc, uint4(&dst)[2]) {
+        constexpr int u = decltype(uc)::value, t = u / TM, j = u % TM;
+        const int n = nw + t * 32 + 8 * pc;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int m = m0 + wm * Cfg::WTM + j * 32 + rrow + 16 * i;
+            dst[i] = (m < p.M && n < p.N)
+                         ? *reinterpret_cast<const uint4 *>((const uint16_t *)p.residual + (int64_t)m * p.N + n)
+                         : make_uint4(0, 0, 0, 0);
+        }
+    };
+    if constexpr (Epi::res16) {
+        static_for<(RES_AHEAD < UNITS ? RES_AHEAD : UNITS)>([&](auto uc) { fetch_residual(uc, res_q[decltype(uc)::value]); });
+    }
+
     static_for<TN>([&](auto tc) {
         constexpr int t = decltype(tc)::value;
         const int c0 = t * 32 + 8 * pc;  // first of the reader lane's channels, wave-relative
@@ -350,14 +370,11 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
                 for (int h = 0; h < 2; ++h) raw[i][h] = *reinterpret_cast<const int4 *>(scr + rd_off[i][h]);
             const int mbase = m0 + wm * Cfg::WTM + j * 32 + rrow;
             uint4 res[2];
-            if (Epi::res16) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int m = mbase + 16 * i;
-                    res[i] = (m < p.M && n < p.N)
-                                 ? *reinterpret_cast<const uint4 *>((const uint16_t *)p.residual + (int64_t)m * p.N + n)
-                                 : make_uint4(0, 0, 0, 0);
-                }
+            if constexpr (Epi::res16) {
+                constexpr int u = t * TM + j;
+                res[0] = res_q[u % RES_AHEAD][0];
+                res[1] = res_q[u % RES_AHEAD][1];
+                if constexpr (u + RES_AHEAD < UNITS) fetch_residual(IntC<u + RES_AHEAD>{}, res_q[u % RES_AHEAD]);
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
