@@ -414,22 +414,17 @@ __device__ __forceinline__ void gemm_i4_epilogue_rows(const GemmI4Params &p, v16
                         hw[e] = (Epi::out == MKQ_F16) ? pack2_f16(y[2 * e], y[2 * e + 1]) : pack2_bf16(y[2 * e], y[2 * e + 1]);
                     if (ok) *reinterpret_cast<uint4 *>((uint16_t *)p.out + o) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
                 } else if (Epi::out == MKQ_I8) {
-                    int cd[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(y[e], qs8);
+                    const uint2 pk8 = quantize8<8>(y, qs8);
                     // code rows may have a pitch; the lane that owns a row's last 8 channels writes its zero padding
                     const int pitch = p.q_pitch ? p.q_pitch : p.N;
                     uint2 *dst = reinterpret_cast<uint2 *>((uint8_t *)p.out + (int64_t)m * pitch + n);
                     if (ok) {
-                        *dst = bytes8(cd);
+                        *dst = pk8;
                         if (n + 8 == p.N)
                             for (int c = 8; c < pitch - n; c += 8) dst[c / 8] = make_uint2(0u, 0u);
                     }
                 } else {
-                    uint32_t packed = 0;  // Eq. 1 on the binary32 value
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        packed |= ((uint32_t)quantize_code_rs<4>(y[e], qs4) & 0xFu) << (4 * e);
+                    const uint32_t packed = quantize8<4>(y, qs4).x;  // Eq. 1 on the binary32 values
                     const int pitch = p.q_pitch ? p.q_pitch : p.N;
                     uint32_t *dst = reinterpret_cast<uint32_t *>((uint8_t *)p.out + (((int64_t)m * pitch + n) >> 1));
                     if (ok) {

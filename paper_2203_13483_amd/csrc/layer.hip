@@ -70,14 +70,10 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t *__restri
                 *reinterpret_cast<uint4 *>(y + (int64_t)row * D + c * 8) =
                     make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
             if (q && q_bits == 8) {
-                int cd[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
-                reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = bytes8(cd);
+                const uint2 pk8 = quantize8<8>(o, quant_step<8>(s_next));
+                reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = pk8;
             } else if (q) {
-                uint32_t packed = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
+                const uint32_t packed = quantize8<4>(o, quant_step<4>(s_next)).x;
                 q[(int64_t)row * q_chunks + c] = packed;
             }
         } else if (q && c < q_chunks) {  // padding codes of a row with a pitch: zero
@@ -163,14 +159,10 @@ __global__ __launch_bounds__(256) void layernorm_half_kernel(const uint16_t *__r
                 *reinterpret_cast<uint4 *>(y + (int64_t)row * D + c * 8) =
                     make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
             if (q && q_bits == 8) {
-                int cd[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
-                reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = bytes8(cd);
+                const uint2 pk8 = quantize8<8>(o, quant_step<8>(s_next));
+                reinterpret_cast<uint2 *>(q)[(int64_t)row * q_chunks + c] = pk8;
             } else if (q) {
-                uint32_t packed = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
+                const uint32_t packed = quantize8<4>(o, quant_step<4>(s_next)).x;
                 q[(int64_t)row * q_chunks + c] = packed;
             }
         } else if (q && c < q_chunks) {  // padding codes of a row with a pitch: zero
@@ -345,14 +337,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t *__restri
                 *reinterpret_cast<uint4 *>(ctx + off) =
                     make_uint4(pack2_f16(o[0], o[1]), pack2_f16(o[2], o[3]), pack2_f16(o[4], o[5]), pack2_f16(o[6], o[7]));
             if (qout && q_bits == 8) {
-                int cd[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
-                *reinterpret_cast<uint2 *>(qout + off) = bytes8(cd);
+                const uint2 pk8 = quantize8<8>(o, quant_step<8>(s_next));
+                *reinterpret_cast<uint2 *>(qout + off) = pk8;
             } else if (qout) {
-                uint32_t packed = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
+                const uint32_t packed = quantize8<4>(o, quant_step<4>(s_next)).x;
                 *reinterpret_cast<uint32_t *>(qout + (off >> 1)) = packed;
             }
         }
@@ -601,17 +589,13 @@ __global__ __launch_bounds__(256, 3) void attention_blocks_kernel(const uint16_t
             }
             const int64_t qo = orow * q_pitch + head * dk + d0;  // in codes
             if (qout && q_bits == 8) {
-                int cd[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) cd[e] = quantize_code_rs<8>(o[e], quant_step<8>(s_next));
-                const uint2 pk = bytes8(cd);
+                const uint2 pk8 = quantize8<8>(o, quant_step<8>(s_next));
+                const uint2 pk = pk8;
                 if constexpr (VEC == 8) *reinterpret_cast<uint2 *>(qout + qo) = pk;
                 else
                     for (int e = 0; e < nvalid; ++e) qout[qo + e] = (uint8_t)((e < 4 ? pk.x : pk.y) >> (8 * (e & 3)));
             } else if (qout) {
-                uint32_t packed = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) packed |= ((uint32_t)quantize_code_rs<4>(o[e], quant_step<4>(s_next)) & 0xFu) << (4 * e);
+                const uint32_t packed = quantize8<4>(o, quant_step<4>(s_next)).x;
                 if constexpr (VEC == 8) *reinterpret_cast<uint32_t *>(qout + (qo >> 1)) = packed;
                 else
                     for (int e = 0; e < nvalid / 2; ++e) qout[(qo >> 1) + e] = (uint8_t)(packed >> (8 * e));

@@ -92,7 +92,9 @@ struct QuantStep {
 template <int BITS>
 __device__ __forceinline__ QuantStep quant_step(float s)
 {
-    constexpr float margin = (BITS == 4) ? 2.0e-6f : 3.0e-5f;  // 1.5 * 2^-23 * 9 resp. * 129, rounded up
+    // (covers both forms below: 1.5 * 2^-23 * 9 resp. * 129 for the plain product, 33.5 * 2^-24 resp.
+    // 513.5 * 2^-24 for the biased one; rounded up)
+    constexpr float margin = (BITS == 4) ? 4.0e-6f : 5.0e-5f;
     QuantStep q;
     q.s = s;
     q.rs = 1.0f / s;
@@ -134,6 +136,49 @@ __device__ __forceinline__ uint2 bytes8(const int (&c)[8])
         hi |= ((uint32_t)c[4 + i] & 0xFFu) << (8 * i);
     }
     return make_uint2(lo, hi);
+}
+
+// Eq. 1 for eight values under one step, packed as they are stored: BITS = 4 -> eight nibbles in .x (value 0
+// lowest), BITS = 8 -> eight bytes in .x, .y.  Division-free as above, in a form that takes six vector
+// operations per value: v = fma(x, rs, 2^(BITS-1)) is the quotient moved to [0, 2^BITS - 1] (one rounding;
+// for quotients inside the clamp range it differs from the correctly rounded x / s plus the bias by less
+// than `margin`), it is rounded, clamped and written into its byte by one conversion instruction, and the
+// bias comes off all codes at once as a flip of their sign bits.  If any of the eight lies within `margin`
+// of a rounding boundary, or is NaN or infinite (v - rint(v) is then NaN), all eight take the division.
+template <int BITS>
+__device__ __forceinline__ uint2 quantize8(const float (&x)[8], const QuantStep &q)
+{
+    constexpr float bias = (BITS == 4) ? 8.0f : 128.0f, top = (BITS == 4) ? 15.0f : 255.0f;
+    uint32_t a = 0, b = 0;
+    bool divide = false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = __builtin_fmaf(x[e], q.rs, bias);
+        const float r = __builtin_rintf(v);
+        divide |= !(fabsf(v - r) <= q.thr);
+        const float c = __builtin_amdgcn_fmed3f(r, 0.0f, top);
+        // 4 bits: even values in the bytes of a, odd ones in b; 8 bits: values 0..3 in a, 4..7 in b
+        const bool to_b = (BITS == 4) ? (e & 1) : (e >= 4);
+        const unsigned at = (BITS == 4) ? (e >> 1) : (e & 3);
+        if (to_b) b = __builtin_amdgcn_cvt_pk_u8_f32(c, at, b);
+        else a = __builtin_amdgcn_cvt_pk_u8_f32(c, at, a);
+    }
+    uint2 out = (BITS == 4) ? make_uint2((a | (b << 4)) ^ 0x88888888u, 0u)
+                            : make_uint2(a ^ 0x80808080u, b ^ 0x80808080u);
+    if (__builtin_expect(divide, 0)) {
+        int cd[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cd[e] = (BITS == 4) ? quantize_code(x[e], q.s) : quantize_code8(x[e], q.s);
+        if (BITS == 4) {
+            uint32_t packed = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) packed |= ((uint32_t)cd[e] & 0xFu) << (4 * e);
+            out = make_uint2(packed, 0u);
+        } else {
+            out = bytes8(cd);
+        }
+    }
+    return out;
 }
 
 __device__ __forceinline__ float wave_max(float v)
@@ -229,7 +274,9 @@ __device__ __forceinline__ float gelu_erf(float x)
     p = __builtin_fmaf(p, t, 0.5f * 0.254829592f);
     p *= t;
     const float e = __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.4426950408889634f));
-    return __builtin_fmaf(-ax, p * e, fmaxf(x, 0.0f));
+    // max(x, 0) as a median of three: one instruction (fmaxf first quiets its operand with a second one); a
+    // NaN still reaches the result through the product
+    return __builtin_fmaf(-ax, p * e, __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff()));
 }
 
 }  // namespace mkq
