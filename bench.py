@@ -101,7 +101,7 @@ class LinearCase:
                                  self.out_dtype, out=self.out)
 
 
-HEADLINE = (65536, 1024, 4096)  # (M, K, N): the largest point of BASELINE configs[4]
+HEADLINE = (65536, 1024, 4096)  # (M, K, N): the largest point of the large-M sweep (configs[4] of the task's baseline file)
 HEADLINE_SEED = 4
 
 
@@ -178,7 +178,7 @@ def main():
         print(json.dumps(profile_launches(mkq, args.only)))
         return
 
-    # --- headline: the largest point of BASELINE configs[4]: uniform int4 codes in, int4 x int4 GEMM with
+    # --- headline: the largest point of the large-M sweep: uniform int4 codes in, int4 x int4 GEMM with
     # int32 accumulation, dequantize with per-channel scales, bf16 out ------------------------------------
     M, K, N = HEADLINE
     A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, HEADLINE_SEED)
@@ -273,7 +273,7 @@ def summary(extra):
     return out
 
 
-# (M, K, N): BASELINE configs[4] and, last, a long-K square where the k loop outweighs the per-tile costs
+# (M, K, N): the large-M sweep and, last, a long-K square where the k loop outweighs the per-tile costs
 LARGE_M_SHAPES = [(M, K, N) for M in (16384, 32768, 65536) for (K, N) in ((1024, 4096), (4096, 1024), (768, 3072))] + [
     (8192, 8192, 8192)]
 # few tokens: (K, N, number of distinct weight matrices cycled through, token counts); the pool is at least 1 GiB
@@ -359,7 +359,7 @@ def profile_launches(mkq, which, launches=5):
 
 
 def layer_gemms_m1024(mkq):
-    """BASELINE configs[1]: the four linears of a BERT-base layer at M = 1024 (8 x 128 tokens), binary16
+    """The BERT-base layer GEMMs workload: the four linears of a BERT-base layer at M = 1024 (8 x 128 tokens), binary16
     activations in -> quantize -> int4 GEMM -> dequantize -> binary16 out, replayed as a HIP graph.  Each GEMM
     is 1.2 - 4.8 GOP: launch- and latency-bound, far from either roofline."""
     import numpy as np
@@ -564,7 +564,7 @@ def side_measurements(mkq, event_time, ceil):
         row["vendor_fp16_over_int4"] = row["vendor_fp16_us"] / row["int4_us"]
         res["table2_token_counts"].append(row)
 
-    # BASELINE configs[3]: the four GEMMs of a BERT-large layer at M = 8192 (batch 16 x seq 512), int4 codes
+    # The BERT-large layer GEMMs workload: the four GEMMs of a BERT-large layer at M = 8192 (batch 16 x seq 512), int4 codes
     # in, fused re-quantization to int4 codes out (GELU on FFN-up)
     res["bert_large_gemms_int4_chain"] = []
     M = 8192

@@ -49,7 +49,7 @@ def _pack_rows_on_device(mkq, codes, chunk=8192):
 @pytest.mark.parametrize("M", [16384, 32768, 65536])
 @pytest.mark.parametrize("K,N", [(1024, 4096), (4096, 1024), (768, 3072)])
 def test_large_m_sweep_bf16_sampled_rows(mkq, M, K, N):
-    """BASELINE configs[4], all nine points: uniform codes, per-channel scales U(0.001, 0.05), bf16 out; one
+    """The large-M sweep, all nine points: uniform codes, per-channel scales U(0.001, 0.05), bf16 out; one
     sampled row in every block of 32 tokens (all channels of it), tile-edge rows and random rows."""
     import torch
     A, Wc, s_w, s_x = wl.uniform_codes_linear(M, K, N, seed=4)
@@ -67,7 +67,7 @@ def test_large_m_sweep_bf16_sampled_rows(mkq, M, K, N):
 
 
 def test_bert_large_layer_gemms_fused_requant(mkq):
-    """BASELINE configs[3]: M = 8192, hidden 1024, FFN 4096, heavy-tailed outliers; int4 in,
+    """The BERT-large layer GEMMs workload: M = 8192, hidden 1024, FFN 4096, heavy-tailed outliers; int4 in,
     int4 out through the fused re-quantization, GELU on FFN-up.  Sampled token rows."""
     import torch
     cfg = wl.CONFIGS[3]
@@ -101,7 +101,7 @@ def test_bert_large_layer_gemms_fused_requant(mkq):
 
 
 def test_bert_base_layer_gemms_as_benchmarked(mkq):
-    """BASELINE configs[1], exactly the benchmark's step: binary16 activations with 1 % x8
+    """The BERT-base layer GEMMs workload, exactly the benchmark's step: binary16 activations with 1 % x8
     outliers in, quantize + GEMM + dequantize, binary16 out; the whole output is compared."""
     import torch
     cfg = wl.CONFIGS[1]
@@ -142,7 +142,7 @@ def _bert_base_layer(mkq, seed, s_out_next=0.0):
 
 
 def test_encoder_layer_full_batch_sampled_sequences(mkq):
-    """BASELINE configs[2] shape: batch 32 x seq 128, BERT-base layer.  Sequences do not interact, so the
+    """The full-encoder workload's shape: batch 32 x seq 128, BERT-base layer.  Sequences do not interact, so the
     oracle follows the layer on two of the 32 sequences: every stage against the GPU's own previous stage."""
     import torch
     B, S, H, heads, F = 32, 128, 768, 12, 3072
@@ -168,7 +168,7 @@ def test_encoder_layer_full_batch_sampled_sequences(mkq):
 
 
 def test_attention_bert_large_512_tokens_full_batch(mkq):
-    """BASELINE configs[3] shape of the attention core: 16 sequences of 512 tokens, 16 heads of 64 (the shape
+    """The BERT-large workload's shape of the attention core: 16 sequences of 512 tokens, 16 heads of 64 (the shape
     bench.py times), context and codes of four of the sequences against the oracle."""
     B, S, heads, dk = 16, 512, 16, 64
     H = heads * dk
@@ -213,7 +213,7 @@ def test_student_layer_full_batch_sampled_sequences(mkq):
 
 
 def test_twelve_layer_encoder_chain_teacher_forced(mkq):
-    """BASELINE configs[2]: the 12-layer BERT-base encoder at batch 32 x seq 128 exactly as the benchmark
+    """The full-encoder workload: the 12-layer BERT-base encoder at batch 32 x seq 128 exactly as the benchmark
     chains it (every layer hands its binary16 output and the codes of it, under the next layer's step, to the
     next layer through q_out_next / q_in).  The oracle follows two of the 32 sequences layer by layer, each
     layer fed the GPU's previous output and codes: every stage of every layer is checked, and so is the

@@ -130,7 +130,7 @@ def test_gelu_then_requant(mkq, M, N, K):
 
 
 def test_config1_single_linear_float_input(mkq):
-    # BASELINE config 1: X [128,768] ~N(0,1), s_x = max|X|/7, W ~N(0,0.02) per-channel abs-max, seed 0
+    # The single-linear workload (configs[0]): X [128,768] ~N(0,1), s_x = max|X|/7, W ~N(0,0.02) per-channel abs-max, seed 0
     X, W, b = wl.gaussian_linear(128, 768, 768, seed=0)
     s_x = oracle.absmax_scale(X)
     wc, s_w_ref = oracle.quantize_weights(W)
