@@ -395,3 +395,32 @@ def test_tiles_with_k_split_across_workgroups(mkq, scratch, cfg, M, N, K, k_slic
         assert_codes_match_with_tie_band(oracle.unpack_nibbles(to_np(rg["out"]), N), refg["q"], refg["y"], 0.5,
                                          what="gelu codes")
     assert int(scratch[:16384].view(torch.int32).abs().sum()) == 0, "ticket counters not cleared"
+
+
+# The fused code decision at and next to exact ties.  With unit weight scales, a power-of-two activation step and
+# no bias the dequantized value is acc * s_x exactly, so a step s_next = 2 * s_x * m puts every accumulator that is
+# an odd multiple of m exactly half way between two codes (round half to even decides), and a step one ulp either
+# side of it, or one such as 2/3 or 0.4 times that has no exact binary32 form, leaves the quotient an ulp off the
+# tie, where only the correctly rounded division knows the side.  No tie band here: the codes must be the oracle's.
+@pytest.mark.parametrize("s_x", [1.0, 0.125])
+@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (300, 200, 128)])
+def test_fused_code_decision_at_and_next_to_exact_ties(mkq, M, N, K, s_x):
+    rng = np.random.default_rng(M + K)
+    # sparse codes keep the accumulators small enough that most of them fall inside the 4-bit range of a step ~ 2
+    A = (rng.integers(-8, 8, (M, K)) * (rng.random((M, K)) < 0.08)).astype(np.int8)
+    Wc = (rng.integers(-7, 8, (N, K)) * (rng.random((N, K)) < 0.3)).astype(np.int8)
+    ones = np.ones(N, np.float32)
+    two = np.float32(2.0 * s_x)
+    steps = [two, np.nextafter(two, np.float32(np.inf)), np.nextafter(two, np.float32(0)),
+             np.float32(two / 3), np.float32(two * 0.4), np.float32(two * 3), np.float32(two * 0.1)]
+    ties = 0
+    for s_next in steps:
+        ref = oracle.linear_int4(A, s_x, Wc, ones, None, s_next=float(s_next))
+        assert np.array_equal(ref["y"], ref["acc"].astype(np.float32) * np.float32(s_x))
+        q = ref["y"].astype(np.float64) / np.float64(s_next)
+        ties += int(((np.abs(q - np.floor(q) - 0.5) < 1e-6) & (np.abs(q) < 7)).sum())
+        r4 = _run(mkq, A, Wc, ones, s_x, None, mkq.MKQ_I4, s_next=float(s_next))
+        assert np.array_equal(to_np(r4["out"]), oracle.pack_nibbles(ref["q"])), f"s_next={s_next!r}"
+        r = _run(mkq, A, Wc, ones, s_x, None, mkq.MKQ_F32, s_next=float(s_next), want_q=True)
+        assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"])), f"s_next={s_next!r} (second output)"
+    assert ties > 1000  # the case really sits on the boundaries
