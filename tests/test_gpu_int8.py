@@ -425,8 +425,9 @@ def test_quantize_int8_around_every_rounding_boundary(mkq, s):
 # The fused 8-bit code decision at and next to exact ties (see the 4-bit case in test_gpu_linear.py): acc * s_x is
 # exact, a step of 2 * s_x makes every odd accumulator a tie, steps an ulp either side or without an exact binary32
 # form leave the quotient an ulp off it.  Codes must equal the oracle's, no band.
+@pytest.mark.parametrize("config", [None, 28, 29, 18])
 @pytest.mark.parametrize("s_x", [1.0, 0.25])
-def test_fused_code_decision_int8_at_and_next_to_exact_ties(mkq, s_x):
+def test_fused_code_decision_int8_at_and_next_to_exact_ties(mkq, s_x, config):
     M, N, K = 300, 264, 128
     rng = np.random.default_rng(77)
     A = (rng.integers(-9, 10, (M, K)) * (rng.random((M, K)) < 0.2)).astype(np.int8)
@@ -440,6 +441,7 @@ def test_fused_code_decision_int8_at_and_next_to_exact_ties(mkq, s_x):
         assert np.array_equal(ref["y"], ref["acc"].astype(np.float32) * np.float32(s_x))
         q = ref["y"].astype(np.float64) / np.float64(s_next)
         ties += int(((np.abs(q - np.floor(q) - 0.5) < 1e-6) & (np.abs(q) < 127)).sum())
-        r = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(ones), None, mkq.MKQ_I8, s_next=float(s_next))
+        r = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(ones), None, mkq.MKQ_I8, s_next=float(s_next),
+                                config=config)
         assert np.array_equal(to_np(r["out"]), ref["q"]), f"s_next={s_next!r}"
     assert ties > 1000

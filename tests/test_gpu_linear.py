@@ -402,9 +402,12 @@ def test_tiles_with_k_split_across_workgroups(mkq, scratch, cfg, M, N, K, k_slic
 # an odd multiple of m exactly half way between two codes (round half to even decides), and a step one ulp either
 # side of it, or one such as 2/3 or 0.4 times that has no exact binary32 form, leaves the quotient an ulp off the
 # tie, where only the correctly rounded division knows the side.  No tie band here: the codes must be the oracle's.
+# (the tile configurations are forced so that the direct epilogue of the small tiles and the row epilogue of the
+# large ones, which decides eight codes at a time, both run)
 @pytest.mark.parametrize("s_x", [1.0, 0.125])
-@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (300, 200, 128)])
-def test_fused_code_decision_at_and_next_to_exact_ties(mkq, M, N, K, s_x):
+@pytest.mark.parametrize("M,N,K,config", [(256, 128, 64, None), (300, 200, 128, None), (300, 200, 128, 28),
+                                          (300, 200, 128, 29), (520, 264, 256, 18)])
+def test_fused_code_decision_at_and_next_to_exact_ties(mkq, M, N, K, s_x, config):
     rng = np.random.default_rng(M + K)
     # sparse codes keep the accumulators small enough that most of them fall inside the 4-bit range of a step ~ 2
     A = (rng.integers(-8, 8, (M, K)) * (rng.random((M, K)) < 0.08)).astype(np.int8)
@@ -419,8 +422,8 @@ def test_fused_code_decision_at_and_next_to_exact_ties(mkq, M, N, K, s_x):
         assert np.array_equal(ref["y"], ref["acc"].astype(np.float32) * np.float32(s_x))
         q = ref["y"].astype(np.float64) / np.float64(s_next)
         ties += int(((np.abs(q - np.floor(q) - 0.5) < 1e-6) & (np.abs(q) < 7)).sum())
-        r4 = _run(mkq, A, Wc, ones, s_x, None, mkq.MKQ_I4, s_next=float(s_next))
+        r4 = _run(mkq, A, Wc, ones, s_x, None, mkq.MKQ_I4, s_next=float(s_next), config=config)
         assert np.array_equal(to_np(r4["out"]), oracle.pack_nibbles(ref["q"])), f"s_next={s_next!r}"
-        r = _run(mkq, A, Wc, ones, s_x, None, mkq.MKQ_F32, s_next=float(s_next), want_q=True)
+        r = _run(mkq, A, Wc, ones, s_x, None, mkq.MKQ_F32, s_next=float(s_next), want_q=True, config=config)
         assert np.array_equal(to_np(r["q"]), oracle.pack_nibbles(ref["q"])), f"s_next={s_next!r} (second output)"
     assert ties > 1000  # the case really sits on the boundaries
