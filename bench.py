@@ -257,9 +257,10 @@ def summary(extra):
     """The target-bearing side measurements in short form, ahead of the long `extra` object: fractions of the
     published peaks (int8 matrix 5000 TOP/s, HBM 8000 GB/s) and, second, of the ceilings measured in this run."""
     r3 = lambda v: None if v is None else round(v, 3)
-    out = {"large_m_MKN_frac_int8_peak_frac_measured_ceiling_e3m2_route_frac": [
+    out = {"large_m_MKN_frac_int8_peak_frac_measured_ceiling_e3m2_route_frac_rotating_buffers_frac": [
                [r["M"], r["K"], r["N"], r3(r["frac_int8_peak"]), r3(r["frac_measured_mfma_ceiling"]),
-                r3(r.get("e3m2_route_frac_int8_peak"))] for r in extra.get("large_m", [])],
+                r3(r.get("e3m2_route_frac_int8_peak")), r3(r.get("rotating_buffers_frac_int8_peak"))]
+               for r in extra.get("large_m", [])],
            "small_m_MKN_layout_us_frac_hbm_peak_frac_measured_read": []}
     for r in extra.get("small_m", []):
         for layout in ("canonical", "stream"):
@@ -406,7 +407,21 @@ def side_measurements(mkq, event_time, ceil):
                "frac_measured_mfma_ceiling": tops / ceil["mfma_i8_TOPS"],
                "output_write_us_at_measured_write_rate": 2.0 * M * N / (ceil["hbm_write_GBps"] * 1e9) * 1e6,
                "protocol": "HIP graph of 20 back-to-back launches, median of 7 samples"}
-        del a, w
+        # rotating buffers: every launch of the graph reads another activation matrix and writes another output,
+        # at least 1 GiB in all (4 x the 256 MB last-level cache), so that nothing a launch touches except the
+        # weights was left in a cache by the launch before it
+        pairs = max(2, min(8, -(-(1 << 30) // (M * K // 2 + 2 * M * N))))
+        rot = [(a, out)] + [(torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda"),
+                             torch.empty((M, N), dtype=torch.bfloat16, device="cuda")) for _ in range(pairs - 1)]
+
+        def every_pair():
+            for (ai, oi) in rot:
+                mkq.mkq_linear_int4(ai, 0.01, w, sw, None, N, K, mkq.MKQ_BF16, out=oi)
+        t_rot = graph_time(every_pair, rep=max(1, 20 // pairs), repeats=5) / pairs
+        row["rotating_buffers_us"] = t_rot * 1e6
+        row["rotating_buffers_frac_int8_peak"] = 2.0 * M * N * K / t_rot / 1e12 / INT8_MFMA_PEAK_TOPS
+        row["rotating_buffers"] = f"{pairs} (activations, output) pairs cycled through by the launches of one graph"
+        del rot, a, w
         if M != 16384 and (M, K, N) != (8192, 8192, 8192) and (M, K, N) != HEADLINE:
             # the comparison kernels below are timed at M = 16384 and at the headline shape only
             c8 = torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda")
