@@ -457,18 +457,21 @@ def mkq_pack_weights_int8(W, s_w_in=None, stream=None):
 
 def mkq_linear_int8(a, s_x: float, Wq, s_w, bias, out_dtype: int = MKQ_F32, *, act: int = MKQ_ACT_NONE,
                     residual=None, s_next: float = 0.0, want_acc: bool = False, out=None, stream=None,
-                    config: int | None = None):
-    """The 8-bit linear: ``a`` int8 codes [M,K], ``Wq`` int8 codes [N,K].  ``config``: mkq_tuning_linear_int8."""
+                    config: int | None = None, q_pitch: int = 0):
+    """The 8-bit linear: ``a`` int8 codes [M,K], ``Wq`` int8 codes [N,K].  ``config``: mkq_tuning_linear_int8.
+    ``q_pitch``: codes per row of an int8 code output (0 = N; the padding columns are written as zeros)."""
     torch = _torch()
     M, K = a.shape
     N = Wq.shape[0]
     if out is None:
-        out = torch.empty((M, N), dtype=torch.int8 if out_dtype == MKQ_I8 else _torch_dtype(out_dtype),
+        cols = int(q_pitch) if (out_dtype == MKQ_I8 and q_pitch) else N
+        out = torch.empty((M, cols), dtype=torch.int8 if out_dtype == MKQ_I8 else _torch_dtype(out_dtype),
                           device=a.device)
     acc = torch.empty((M, N), dtype=torch.int32, device=a.device) if want_acc else None
     epi = Epilogue(act=int(act), residual=residual.data_ptr() if residual is not None else None,
                    residual_dtype=_dtype_code(residual) if residual is not None else MKQ_F32,
-                   s_next=float(s_next), q_out=None, acc_out=acc.data_ptr() if acc is not None else None)
+                   s_next=float(s_next), q_out=None, acc_out=acc.data_ptr() if acc is not None else None,
+                   q_pitch=int(q_pitch))
     if config is None:
         _check(load().mkq_linear_int8(_ptr(a), float(s_x), _ptr(Wq), _ptr(s_w), _ptr(bias), M, N, K, _ptr(out),
                                       int(out_dtype), C.byref(epi), _stream(stream)), "mkq_linear_int8")

@@ -445,3 +445,24 @@ def test_fused_code_decision_int8_at_and_next_to_exact_ties(mkq, s_x, config):
                                 config=config)
         assert np.array_equal(to_np(r["out"]), ref["q"]), f"s_next={s_next!r}"
     assert ties > 1000
+
+
+# int8 code outputs with a row pitch: real columns at the pitch, zero codes in the padding, through the direct
+# epilogue of the small tiles and the row epilogue of the large ones (forced configurations); stale buffers show
+# that the padding is written
+@pytest.mark.parametrize("M,N,K,pitch,config", [(100, 200, 128, 256, None), (300, 328, 256, 384, 29),
+                                                (520, 264, 128, 320, 18), (64, 72, 512, 128, None),
+                                                (16, 200, 128, 256, None), (1, 328, 256, 384, None)])
+def test_int8_code_outputs_with_a_row_pitch(mkq, M, N, K, pitch, config):
+    import torch
+    A, Wc, s_w, s_x, bias = _codes_case(M, N, K, seed=M + pitch)
+    ref = oracle.linear_int4(A, s_x, Wc, s_w, bias, s_next=0.07, **Q8)
+    want = np.zeros((M, pitch), np.int8)
+    want[:, :N] = ref["q"]
+    out = torch.full((M, pitch), 0x5A, dtype=torch.int8, device="cuda")
+    r = mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(s_w), to_dev(bias), mkq.MKQ_I8, s_next=0.07,
+                            out=out, q_pitch=pitch, config=config)
+    assert np.array_equal(to_np(r["out"]), want)
+    with pytest.raises(mkq.MkqError):
+        mkq.mkq_linear_int8(to_dev(A), float(s_x), to_dev(Wc), to_dev(s_w), to_dev(bias), mkq.MKQ_I8, s_next=0.07,
+                            out=out, q_pitch=N - 8, config=config)
