@@ -323,6 +323,32 @@ def test_zero_weight_layer_reduces_to_two_layernorms():
     np.testing.assert_allclose(out, ref, rtol=1e-6, atol=1e-6)
 
 
+def test_quantized_layer_is_unchanged_by_a_permutation_of_its_heads():
+    """Renumbering the heads -- the blocks of d_k rows of the q, k and v parts of the QKV weights, with their
+    per-channel steps and biases, and the matching blocks of d_k columns of the attention-out weights -- changes
+    nothing: every head's scores and context are computed from the same numbers, and the attention-out sums run
+    over the same products in another order, which integer accumulation does not see.  Bit for bit: a head's q, k
+    or v slice taken at the wrong offset, or a context written to the wrong block, fails this."""
+    p, h = _float_layer(25)
+    q = _quantize_layer(p, h, -8, 7, sx_mult=0.6)
+    H, heads = p["hidden"], p["heads"]
+    dk = H // heads
+    rng = np.random.default_rng(7)
+    order = rng.permutation(heads)
+    assert not np.array_equal(order, np.arange(heads))
+    cols = np.concatenate([np.arange(i * dk, (i + 1) * dk) for i in order])       # new position -> old channel
+    rows_qkv = np.concatenate([part * H + cols for part in range(3)])
+    q2 = dict(q)
+    q2["w_qkv"], q2["sw_qkv"], q2["b_qkv"] = q["w_qkv"][rows_qkv], q["sw_qkv"][rows_qkv], q["b_qkv"][rows_qkv]
+    q2["w_ao"] = np.ascontiguousarray(q["w_ao"][:, cols])
+    out, it = oracle.bert_layer_int4(q, h, act_dtype=oracle.F16)
+    out2, it2 = oracle.bert_layer_int4(q2, h, act_dtype=oracle.F16)
+    assert np.array_equal(it2["qkv"], it["qkv"][:, rows_qkv])
+    assert np.array_equal(it2["ctx"], it["ctx"][:, cols]) and np.array_equal(it2["c1"], it["c1"][:, cols])
+    assert np.array_equal(it2["u"], it["u"])
+    assert np.array_equal(out2, out)
+
+
 def test_attention_with_probabilities_narrowed_before_the_value_product():
     """The p_dtype = F16 branch (softmax probabilities rounded to binary16 BEFORE P.v, as a 16-bit matrix
     unit consumes them) against torch in float64: softmax -> .half() -> matmul.  The same data distinguish it
