@@ -145,6 +145,10 @@ def measured_ceilings(mkq):
     n_ops = mkq.mkq_measure_mfma_i8(ops16, iters, sink)
     ts = sorted(event_time(lambda: mkq.mkq_measure_mfma_i8(ops16, iters, sink), 5, warm=2) for _ in range(5))
     out["mfma_i8_TOPS"] = n_ops / ts[2] / 1e12
+    # one v_mfma_i32_32x32x32_i8 (65536 operations) occupies a SIMD's matrix pipe for 32 cycles: the rate of a
+    # loop that keeps the pipe full is 2048 operations per cycle and SIMD, so its rate tells the sustained clock
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out["sustained_clock_GHz_under_the_mfma_loop"] = n_ops / ts[2] / (cus * 4 * 2048) / 1e9
     out["note"] = ("1 GiB streaming kernels; register-only v_mfma_i32_32x32x32_i8 loop, 8 accumulator tiles per "
                    "wave, 8 waves per CU, operands = 16 * uniform codes (the chip's clock under load depends on "
                    "the data)")
